@@ -1,0 +1,163 @@
+/*
+ * vla.h — C ABI of the MI355X (gfx950) library for batched Vision-Language-Action policy
+ * inference: the GPU work of an Inference Worker in the paper's "Inference-as-a-Service" rollout
+ * path (Section 3.2): a batch of observations goes in, discretised action tokens, their per-token
+ * behaviour log-probabilities (Section 3.2, Eq. 2: mu_t; Appendix "Token-level Policy
+ * Optimization") and the de-tokenised continuous actions come out.
+ *
+ * Model: decoder-only transformer (pre-norm RMSNorm, rotary embedding on half-split pairs,
+ * causal multi-head attention, SwiGLU feed-forward, no biases) over the prefix
+ * [visual patch embeddings ; instruction token embeddings], followed by autoregressive decoding
+ * of K action tokens.  The output head is the LM head restricted to the rows of the action bins
+ * (Appendix "Vocabulary Slimming"): bins are the last n_action_bins vocabulary ids, bin j is id
+ * vocab - n_action_bins + j, and the distribution is normalised over the bins only.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device; "host" pointers are ordinary
+ *     host memory that is read before the call returns.
+ *   - The library never allocates device memory.  The caller owns the weight arena, the KV cache
+ *     and the workspace (sizes from vla_query_sizes), binds them once, and keeps them alive and
+ *     untouched until vla_destroy.
+ *   - Every call that takes `hip_stream` (a hipStream_t, or NULL for the default stream) only
+ *     enqueues work on it and returns; results are valid once the caller has synchronised that
+ *     stream.  No call synchronises the device.  A context is used from one thread, with calls
+ *     ordered on one stream.
+ *   - Every function returns VLA_OK or a negative vla_status.  Arguments are validated before
+ *     anything is enqueued, so a failing call leaves the context unchanged.  vla_last_error gives
+ *     a human-readable description of the last failure on that context.
+ *   - Storage dtype (config.dtype): VLA_F32 = IEEE float32; VLA_BF16 = bfloat16 (weights, patch
+ *     embeddings, KV cache, GEMM operands in bf16; accumulation, residual stream, norm statistics,
+ *     softmax and log-softmax in float32).
+ */
+#ifndef VLA_H
+#define VLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vla_ctx vla_ctx;
+
+enum vla_dtype { VLA_F32 = 0, VLA_BF16 = 1 };
+
+enum vla_status {
+  VLA_OK = 0,
+  VLA_E_NULL = -1,      /* a required pointer is NULL */
+  VLA_E_CONFIG = -2,    /* unsupported or inconsistent vla_config */
+  VLA_E_SHAPE = -3,     /* batch / offsets / tensor shapes do not fit the config */
+  VLA_E_CAPACITY = -4,  /* max_batch, max_seq or max_prefill_tokens would be exceeded */
+  VLA_E_STATE = -5,     /* call out of order (buffers not bound, weights not loaded, no prefill) */
+  VLA_E_WEIGHTS = -6,   /* missing, duplicate or mis-shaped tensor in vla_load_weights */
+  VLA_E_HIP = -7        /* a HIP runtime call failed */
+};
+
+/* Plain data, copied by vla_create.  Requirements: n_heads * head_dim == d_model; head_dim is 64
+ * or 128 for VLA_BF16 (even, <= 256, for VLA_F32); d_model and d_ffn multiples of 64 for
+ * VLA_BF16; 0 < n_action_bins <= vocab, n_action_bins <= 1024; max_seq counts prefix plus decoded
+ * positions of one sequence; max_prefill_tokens bounds the packed prefix tokens of one batch. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab, n_action_bins;
+  float rope_theta, rms_eps;
+  int32_t dtype;              /* enum vla_dtype */
+  int32_t max_batch, max_seq;
+  int64_t max_prefill_tokens;
+} vla_config;
+
+/* One named tensor handed to vla_load_weights: device pointer, row-major, nn.Linear layout
+ * [out_features, in_features] for matrices, dtype = the config's storage dtype. */
+typedef struct {
+  const char* name;
+  const void* dev_ptr;
+  int32_t dtype;
+  int32_t ndim;
+  int64_t shape[4];
+} vla_tensor;
+
+/* Context life cycle.  vla_create validates the config and allocates host-side state only. */
+int vla_create(const vla_config* cfg, vla_ctx** out);
+int vla_destroy(vla_ctx* ctx);
+const char* vla_last_error(const vla_ctx* ctx);
+
+/* Bytes the caller must provide (each buffer 256-byte aligned): the weight arena (repacked
+ * weights, only the action rows of the head), the KV cache [layer][slot][head][position][head_dim]
+ * in the storage dtype, and the activation workspace. */
+int vla_query_sizes(const vla_config* cfg, size_t* weight_arena_bytes, size_t* kv_bytes,
+                    size_t* workspace_bytes);
+int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace);
+
+/* Copies and repacks the named tensors into the arena (fused QKV, fused gate/up, MFMA fragment
+ * order, only the action rows of `lm_head`).  Names: "embed" [V,d]; per layer l
+ * "layers.<l>.attn_norm" [d], ".wq" ".wk" ".wv" ".wo" [d,d], ".ffn_norm" [d], ".w_gate" ".w_up"
+ * [f,d], ".w_down" [d,f]; "final_norm" [d]; "lm_head" [V,d] or already slimmed [A,d].  All must
+ * be present exactly once.  Sources may be freed once the stream has completed.  Calling it again
+ * overwrites the live weights in place, which is the paper's in-place weight update on the
+ * inference GPU (Appendix "High-Performance NCCL-based Weight Synchronization"); the caller must
+ * not have a policy step in flight on another stream (the paper's drain). */
+int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream);
+
+/* Prefill: sequence slot b (0 <= b < B) gets the prefix
+ *   [patch_emb rows cu_patch[b] .. cu_patch[b+1]) ; embed[instr_ids[cu_instr[b] .. cu_instr[b+1])]]
+ * at positions 0 .. S_b-1; its keys/values are written to the cache and its length is set to S_b.
+ *   patch_emb  device, [cu_patch[B], d_model], storage dtype
+ *   cu_patch   host,   [B+1] non-decreasing, cu_patch[0] == 0
+ *   instr_ids  device, [cu_instr[B]] int32 in [0, vocab)   (may be NULL if cu_instr[B] == 0)
+ *   cu_instr   host,   [B+1] non-decreasing, cu_instr[0] == 0
+ *   logits_out device, [B, n_action_bins] float32 or NULL: action-bin logits at the last prefix
+ *              position of each sequence.
+ * Every sequence needs S_b >= 1 and S_b <= max_seq; sum S_b <= max_prefill_tokens. */
+int vla_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                const int32_t* instr_ids, const int32_t* cu_instr, float* logits_out,
+                void* hip_stream);
+
+/* One decode step for slots 0..B-1 (B = the batch of the last prefill): token_ids (device, [B],
+ * absolute vocabulary ids) are embedded and appended at each sequence's current length; returns
+ * the action-bin logits for the following token.  VLA_E_CAPACITY if a sequence is full. */
+int vla_decode_step(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits_out,
+                    void* hip_stream);
+
+/* Whole policy step, all on the device: prefill, then K = n_tokens action tokens chosen one by one
+ * (K-1 decode steps), each with its log-probability under the distribution it was chosen from.
+ *   temperature  0 => greedy (argmax of the logits, log-prob at temperature 1);
+ *                >0 => argmax of logits/temperature + gumbel (Gumbel-max sampling); if gumbel is
+ *                NULL the noise is taken as zero.  Exact ties go to the lowest bin.
+ *   gumbel       device, [B, K, n_action_bins] float32 or NULL
+ *   act_scale, act_offset  device, [action_dim] float32 or NULL (identity): token k belongs to
+ *                action dimension k mod action_dim (timestep-major chunk);
+ *                action = centre(bin) * scale + offset, centre(j) = -1 + (2j+1)/n_action_bins.
+ *   tokens_out   device, [B, K] int32 bin indices in [0, n_action_bins)
+ *   logp_out     device, [B, K] float32
+ *   actions_out  device, [B, K] float32
+ *   logits_out   device, [B, K, n_action_bins] float32 or NULL (for tests)
+ * Needs S_b + K <= max_seq for every sequence. */
+int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                    const int32_t* instr_ids, const int32_t* cu_instr, int32_t n_tokens,
+                    float temperature, const float* gumbel, const float* act_scale,
+                    const float* act_offset, int32_t action_dim, int32_t* tokens_out,
+                    float* logp_out, float* actions_out, float* logits_out, void* hip_stream);
+
+/* Selection alone, for callers that drive vla_prefill / vla_decode_step themselves:
+ * logits [B, n_action_bins] (device) -> bin index, log-prob, action, for token index k of the
+ * chunk (k selects the action dimension k mod action_dim and the row [b, k] of gumbel [B, K, A]).
+ * next_ids_out (device, [B] int32 or NULL) receives the absolute vocabulary id to feed back. */
+int vla_select(vla_ctx* ctx, int32_t B, const float* logits, float temperature, const float* gumbel,
+               int32_t k, int32_t n_tokens, const float* act_scale, const float* act_offset,
+               int32_t action_dim, int32_t* tokens_out, float* logp_out, float* actions_out,
+               int32_t out_stride, int32_t* next_ids_out, void* hip_stream);
+
+/* Timing hooks for the benchmark: duration of the launches of one kernel family, measured with
+ * HIP events recorded on the launch stream around each launch.  vla_prof_enable(ctx, mask) clears
+ * what was collected and then times the families whose bit (1 << index) is set in mask (0 = off).
+ * vla_prof_read synchronises the recorded events (host-blocking) and reports, for family index i
+ * (0 <= i < vla_prof_count()), its name, number of launches and total milliseconds.  Families:
+ * 0 gemm_prefill, 1 attn_prefill, 2 gemm_decode, 3 attn_decode, 4 rmsnorm, 5 head_select, 6 misc. */
+int vla_prof_enable(vla_ctx* ctx, int32_t mask);
+int vla_prof_count(void);
+int vla_prof_read(vla_ctx* ctx, int32_t i, const char** name, int64_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VLA_H */

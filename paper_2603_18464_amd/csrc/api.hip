@@ -1,0 +1,636 @@
+// C ABI of the VLA policy library: context, validation, weight repacking and the host-side
+// orchestration of prefill, decode step and policy step.  All device work is enqueued on the
+// caller's stream; nothing here synchronises the device except the profiling read-out.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/vla.h"
+#include "common.h"
+
+using namespace vla;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct LayerW {
+  size_t g_attn, w_qkv, w_o, g_ffn, w_gu, w_down;   // byte offsets into the weight arena
+};
+struct ArenaLayout {
+  size_t embed, g_final, head, total;
+  std::vector<LayerW> layers;
+};
+struct WorkLayout {
+  size_t x, hn, q, att, act, scratch, rope_cos, rope_sin, tok_seq, tok_pos, tok_src, last_row, seq_len,
+      cu_patch, cu_instr, cur_ids, logits, total;
+};
+
+size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
+
+ArenaLayout arena_layout(const vla_config& c) {
+  ArenaLayout a;
+  const size_t es = elem_size(c.dtype), d = c.d_model, f = c.d_ffn;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  a.embed = take((size_t)c.vocab * d * es);
+  a.layers.resize(c.n_layers);
+  for (auto& l : a.layers) {
+    l.g_attn = take(d * 4);
+    l.w_qkv = take(3 * d * d * es);
+    l.w_o = take(d * d * es);
+    l.g_ffn = take(d * 4);
+    l.w_gu = take(2 * f * d * es);
+    l.w_down = take(d * f * es);
+  }
+  a.g_final = take(d * 4);
+  a.head = take((size_t)c.n_action_bins * d * es);
+  a.total = off;
+  return a;
+}
+
+size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one layer
+  return (size_t)c.max_batch * c.n_heads * c.max_seq * c.head_dim;
+}
+size_t kv_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
+
+size_t max_rows(const vla_config& c) {
+  return (size_t)(c.max_prefill_tokens > c.max_batch ? c.max_prefill_tokens : c.max_batch);
+}
+
+WorkLayout work_layout(const vla_config& c) {
+  WorkLayout w;
+  const size_t es = elem_size(c.dtype), d = c.d_model, f = c.d_ffn, T = max_rows(c), B = c.max_batch;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  w.x = take(T * d * 4);
+  w.hn = take(T * d * es);
+  w.q = take(T * d * es);
+  w.att = take(T * d * es);
+  w.act = take(T * f * es);
+  const size_t widest = 3 * d > 2 * f ? 3 * d : 2 * f;
+  w.scratch = take(c.dtype == VLA_F32 ? T * widest * 4 : 0);
+  w.rope_cos = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
+  w.rope_sin = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
+  w.tok_seq = take(T * 4);
+  w.tok_pos = take(T * 4);
+  w.tok_src = take(T * 4);
+  w.last_row = take(B * 4);
+  w.seq_len = take(B * 4);
+  w.cu_patch = take((B + 1) * 4);
+  w.cu_instr = take((B + 1) * 4);
+  w.cur_ids = take(B * 4);
+  w.logits = take(B * (size_t)c.n_action_bins * 4);
+  w.total = off;
+  return w;
+}
+
+const char* check_config(const vla_config& c) {
+  if (c.n_layers <= 0 || c.d_model <= 0 || c.n_heads <= 0 || c.head_dim <= 0 || c.d_ffn <= 0) return "non-positive model dimension";
+  if ((int64_t)c.n_heads * c.head_dim != c.d_model) return "n_heads * head_dim must equal d_model";
+  if (c.vocab <= 0 || c.n_action_bins <= 0 || c.n_action_bins > c.vocab) return "need 0 < n_action_bins <= vocab";
+  if (c.n_action_bins > 1024) return "n_action_bins > 1024";
+  if (c.dtype != VLA_F32 && c.dtype != VLA_BF16) return "dtype must be VLA_F32 or VLA_BF16";
+  if (!(c.rope_theta > 0.f) || !(c.rms_eps >= 0.f)) return "rope_theta must be > 0 and rms_eps >= 0";
+  if (c.max_batch <= 0 || c.max_seq <= 0 || c.max_prefill_tokens <= 0) return "capacities must be positive";
+  if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128 && c.head_dim != 256) return "head_dim must be 32, 64, 128 or 256";
+  if (c.d_model % 4) return "d_model must be a multiple of 4";
+  if (c.dtype == VLA_BF16) {
+    if (c.head_dim != 64 && c.head_dim != 128) return "bf16 path needs head_dim 64 or 128";
+    if (c.d_model % 128 || c.d_ffn % 64) return "bf16 path needs d_model % 128 == 0 and d_ffn % 64 == 0";
+  }
+  if ((size_t)(c.head_dim + c.max_seq) * 16 > 64 * 1024) return "max_seq too large for the attention kernel's LDS";
+  if ((int64_t)c.d_model * 4 > 64 * 1024) return "d_model too large for the head kernel's LDS";
+  return nullptr;
+}
+
+struct EventPair { hipEvent_t a, b; };
+
+}  // namespace
+
+struct vla_ctx {
+  vla_config cfg;
+  ArenaLayout al;
+  WorkLayout wl;
+  char* arena = nullptr;
+  char* kv = nullptr;
+  char* work = nullptr;
+  bool bound = false, weights = false, tables = false;
+  int active_B = 0;                  // batch of the last prefill (0: none)
+  std::vector<int32_t> len;          // host copy of the sequence lengths
+  std::string err;
+  // pinned staging ring for the host offset arrays
+  static constexpr int kRing = 8;
+  int32_t* stage = nullptr;
+  hipEvent_t stage_ev[kRing];
+  bool stage_used[kRing];
+  int stage_next = 0;
+  // profiling
+  unsigned prof_mask = 0;
+  std::vector<EventPair> prof[FAM_COUNT];
+  std::vector<hipEvent_t> ev_pool;
+};
+
+namespace {
+
+int fail(vla_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf;
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                       \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess) return fail(ctx, VLA_E_HIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+struct ProfScope {
+  vla_ctx* c;
+  int fam;
+  hipStream_t st;
+  EventPair p;
+  bool on;
+  ProfScope(vla_ctx* c_, int fam_, hipStream_t st_) : c(c_), fam(fam_), st(st_), on((c_->prof_mask >> fam_) & 1u) {
+    if (!on) return;
+    if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(p.a, st);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(p.b, st);
+    c->prof[fam].push_back(p);
+  }
+};
+
+const char* kFamilyNames[FAM_COUNT] = {"gemm_prefill", "attn_prefill", "gemm_decode", "attn_decode",
+                                       "rmsnorm", "head_select", "misc"};
+
+template <class T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(base + off); }
+
+// ---- one pass over the layers for `rows` packed tokens (prefill: all prefix tokens; decode: B) ------
+template <class T>
+int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
+  const vla_config& c = ctx->cfg;
+  const WorkLayout& w = ctx->wl;
+  const int d = c.d_model, f = c.d_ffn;
+  float* x = at<float>(ctx->work, w.x);
+  T* hn = at<T>(ctx->work, w.hn);
+  T* q = at<T>(ctx->work, w.q);
+  T* att = at<T>(ctx->work, w.att);
+  T* act = at<T>(ctx->work, w.act);
+  float* scratch = at<float>(ctx->work, w.scratch);
+  const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
+  const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
+  const size_t kvl = kv_layer_stride(c);
+  const int fam_gemm = decode ? FAM_GEMM_DECODE : FAM_GEMM_PREFILL;
+  const int fam_attn = decode ? FAM_ATTN_DECODE : FAM_ATTN_PREFILL;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW& lw = ctx->al.layers[l];
+    RopeKv rk;
+    rk.q = q;
+    rk.k_cache = at<T>(ctx->kv, 0) + (size_t)(2 * l) * kvl;
+    rk.v_cache = at<T>(ctx->kv, 0) + (size_t)(2 * l + 1) * kvl;
+    rk.tok_seq = tok_seq;
+    rk.tok_pos = tok_pos;
+    rk.rope_cos = at<float>(ctx->work, w.rope_cos);
+    rk.rope_sin = at<float>(ctx->work, w.rope_sin);
+    rk.n_heads = c.n_heads;
+    rk.head_dim = c.head_dim;
+    rk.max_seq = c.max_seq;
+    rk.d_model = d;
+    {
+      ProfScope ps(ctx, FAM_NORM, st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, st);
+    }
+    {
+      ProfScope ps(ctx, fam_gemm, st);
+      if constexpr (sizeof(T) == 2) {
+        gemm_bf16_qkv(GemmBf16{(const bf16*)hn, d, at<bf16>(ctx->arena, lw.w_qkv), rows, 3 * d, d}, rk, st);
+      } else {
+        gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_qkv), scratch, rows, 3 * d, d, st);
+        rope_kv_f32(scratch, rows, rk, st);
+      }
+    }
+    {
+      ProfScope ps(ctx, fam_attn, st);
+      attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
+                        c.n_heads, c.head_dim, c.max_seq, st);
+    }
+    {
+      ProfScope ps(ctx, fam_gemm, st);
+      if constexpr (sizeof(T) == 2) {
+        gemm_bf16_resid(GemmBf16{(const bf16*)att, d, at<bf16>(ctx->arena, lw.w_o), rows, d, d}, x, d, st);
+      } else {
+        gemm_f32((const float*)att, d, at<float>(ctx->arena, lw.w_o), scratch, rows, d, d, st);
+        resid_add_f32(x, scratch, (size_t)rows * d, st);
+      }
+    }
+    {
+      ProfScope ps(ctx, FAM_NORM, st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, st);
+    }
+    {
+      ProfScope ps(ctx, fam_gemm, st);
+      if constexpr (sizeof(T) == 2) {
+        gemm_bf16_swiglu(GemmBf16{(const bf16*)hn, d, at<bf16>(ctx->arena, lw.w_gu), rows, 2 * f, d}, (bf16*)act, f, st);
+      } else {
+        gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_gu), scratch, rows, 2 * f, d, st);
+        swiglu_f32(scratch, (float*)act, rows, f, st);
+      }
+    }
+    {
+      ProfScope ps(ctx, fam_gemm, st);
+      if constexpr (sizeof(T) == 2) {
+        gemm_bf16_resid(GemmBf16{(const bf16*)act, f, at<bf16>(ctx->arena, lw.w_down), rows, d, f}, x, d, st);
+      } else {
+        gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), scratch, rows, d, f, st);
+        resid_add_f32(x, scratch, (size_t)rows * d, st);
+      }
+    }
+  }
+  return VLA_OK;
+}
+
+template <class T>
+void run_head(vla_ctx* ctx, int B, const int32_t* row_index, float* logits, int ld, hipStream_t st) {
+  const vla_config& c = ctx->cfg;
+  ProfScope ps(ctx, FAM_HEAD, st);
+  head_logits<T>(at<float>(ctx->work, ctx->wl.x), row_index, at<float>(ctx->arena, ctx->al.g_final),
+                 at<T>(ctx->arena, ctx->al.head), logits, ld, B, c.d_model, c.n_action_bins, c.rms_eps, st);
+}
+
+int check_ready(vla_ctx* ctx) {
+  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
+  if (!ctx->weights) return fail(ctx, VLA_E_STATE, "weights are not loaded (vla_load_weights)");
+  return VLA_OK;
+}
+
+// Validates a prefill request and returns the packed token count.
+int check_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                  const int32_t* instr_ids, const int32_t* cu_instr, int extra_positions, int64_t* T_out) {
+  const vla_config& c = ctx->cfg;
+  if (!cu_patch || !cu_instr) return fail(ctx, VLA_E_NULL, "cu_patch / cu_instr is NULL");
+  if (B <= 0) return fail(ctx, VLA_E_SHAPE, "batch %d must be positive", B);
+  if (B > c.max_batch) return fail(ctx, VLA_E_CAPACITY, "batch %d exceeds max_batch %d", B, c.max_batch);
+  if (cu_patch[0] != 0 || cu_instr[0] != 0) return fail(ctx, VLA_E_SHAPE, "cumulative offsets must start at 0");
+  int64_t T = 0;
+  for (int b = 0; b < B; ++b) {
+    const int np = cu_patch[b + 1] - cu_patch[b], li = cu_instr[b + 1] - cu_instr[b];
+    if (np < 0 || li < 0) return fail(ctx, VLA_E_SHAPE, "offsets of sequence %d decrease", b);
+    const int S = np + li;
+    if (S < 1) return fail(ctx, VLA_E_SHAPE, "sequence %d has an empty prefix", b);
+    if (S + extra_positions > c.max_seq)
+      return fail(ctx, VLA_E_CAPACITY, "sequence %d needs %d positions, max_seq is %d", b, S + extra_positions, c.max_seq);
+    T += S;
+  }
+  if (T > c.max_prefill_tokens)
+    return fail(ctx, VLA_E_CAPACITY, "%lld prefix tokens exceed max_prefill_tokens %lld", (long long)T, (long long)c.max_prefill_tokens);
+  if (cu_patch[B] > 0 && !patch_emb) return fail(ctx, VLA_E_NULL, "patch_emb is NULL");
+  if (cu_instr[B] > 0 && !instr_ids) return fail(ctx, VLA_E_NULL, "instr_ids is NULL");
+  *T_out = T;
+  return VLA_OK;
+}
+
+int ensure_tables(vla_ctx* ctx, hipStream_t st) {
+  if (ctx->tables) return VLA_OK;
+  rope_table(at<float>(ctx->work, ctx->wl.rope_cos), at<float>(ctx->work, ctx->wl.rope_sin), ctx->cfg.max_seq,
+             ctx->cfg.head_dim, ctx->cfg.rope_theta, st);
+  ctx->tables = true;
+  return VLA_OK;
+}
+
+template <class T>
+int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
+               const int32_t* cu_instr, int64_t T_tokens, float* logits, int ld_logits, hipStream_t st) {
+  const vla_config& c = ctx->cfg;
+  const WorkLayout& w = ctx->wl;
+  // stage the host offset arrays in pinned memory (a slot is reused only after its copy finished)
+  const int slot = ctx->stage_next;
+  ctx->stage_next = (slot + 1) % vla_ctx::kRing;
+  if (ctx->stage_used[slot]) HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev[slot]));
+  int32_t* host = ctx->stage + (size_t)slot * 2 * (c.max_batch + 1);
+  memcpy(host, cu_patch, (B + 1) * sizeof(int32_t));
+  memcpy(host + c.max_batch + 1, cu_instr, (B + 1) * sizeof(int32_t));
+  HIP_TRY(ctx, hipMemcpyAsync(at<int32_t>(ctx->work, w.cu_patch), host, (B + 1) * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(ctx, hipMemcpyAsync(at<int32_t>(ctx->work, w.cu_instr), host + c.max_batch + 1, (B + 1) * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(ctx, hipEventRecord(ctx->stage_ev[slot], st));
+  ctx->stage_used[slot] = true;
+  ensure_tables(ctx, st);
+  {
+    ProfScope ps(ctx, FAM_MISC, st);
+    build_token_maps(at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), B, (int)T_tokens,
+                     at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos),
+                     at<int32_t>(ctx->work, w.tok_src), at<int32_t>(ctx->work, w.last_row),
+                     at<int32_t>(ctx->work, w.seq_len), st);
+    assemble_prefix<T>((const T*)patch_emb, instr_ids, at<T>(ctx->arena, ctx->al.embed),
+                       at<int32_t>(ctx->work, w.tok_src), at<float>(ctx->work, w.x), (int)T_tokens, c.d_model, st);
+  }
+  run_layers<T>(ctx, (int)T_tokens, false, st);
+  if (logits) run_head<T>(ctx, B, at<int32_t>(ctx->work, w.last_row), logits, ld_logits, st);
+  HIP_TRY(ctx, hipGetLastError());
+  ctx->active_B = B;
+  ctx->len.assign(B, 0);
+  for (int b = 0; b < B; ++b) ctx->len[b] = (cu_patch[b + 1] - cu_patch[b]) + (cu_instr[b + 1] - cu_instr[b]);
+  return VLA_OK;
+}
+
+template <class T>
+int do_decode(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits, int ld_logits, hipStream_t st) {
+  const vla_config& c = ctx->cfg;
+  const WorkLayout& w = ctx->wl;
+  {
+    ProfScope ps(ctx, FAM_MISC, st);
+    embed_tokens<T>(token_ids, at<T>(ctx->arena, ctx->al.embed), at<float>(ctx->work, w.x), B, c.d_model, c.vocab, st);
+    decode_maps(at<int32_t>(ctx->work, w.seq_len), B, at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos), st);
+  }
+  run_layers<T>(ctx, B, true, st);
+  if (logits) run_head<T>(ctx, B, nullptr, logits, ld_logits, st);
+  {
+    ProfScope ps(ctx, FAM_MISC, st);
+    advance_lengths(at<int32_t>(ctx->work, w.seq_len), B, st);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  for (int b = 0; b < B; ++b) ctx->len[b] += 1;
+  return VLA_OK;
+}
+
+int check_decode(vla_ctx* ctx, int32_t B, int steps) {
+  if (ctx->active_B == 0) return fail(ctx, VLA_E_STATE, "decode before prefill");
+  if (B != ctx->active_B) return fail(ctx, VLA_E_SHAPE, "decode batch %d differs from the prefilled batch %d", B, ctx->active_B);
+  for (int b = 0; b < B; ++b)
+    if (ctx->len[b] + steps > ctx->cfg.max_seq)
+      return fail(ctx, VLA_E_CAPACITY, "sequence %d is full (%d of %d positions)", b, ctx->len[b], ctx->cfg.max_seq);
+  return VLA_OK;
+}
+
+}  // namespace
+
+// ---- exported functions --------------------------------------------------------------------------------
+extern "C" {
+
+int vla_create(const vla_config* cfg, vla_ctx** out) {
+  if (!cfg || !out) return VLA_E_NULL;
+  *out = nullptr;
+  if (check_config(*cfg)) return VLA_E_CONFIG;
+  vla_ctx* ctx = new vla_ctx();
+  ctx->cfg = *cfg;
+  ctx->al = arena_layout(*cfg);
+  ctx->wl = work_layout(*cfg);
+  for (int i = 0; i < vla_ctx::kRing; ++i) { ctx->stage_used[i] = false; ctx->stage_ev[i] = nullptr; }
+  *out = ctx;
+  return VLA_OK;
+}
+
+int vla_destroy(vla_ctx* ctx) {
+  if (!ctx) return VLA_E_NULL;
+  if (ctx->stage) (void)hipHostFree(ctx->stage);
+  for (int i = 0; i < vla_ctx::kRing; ++i)
+    if (ctx->stage_ev[i]) (void)hipEventDestroy(ctx->stage_ev[i]);
+  for (auto& v : ctx->prof)
+    for (auto& p : v) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  delete ctx;
+  return VLA_OK;
+}
+
+const char* vla_last_error(const vla_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int vla_query_sizes(const vla_config* cfg, size_t* weight_arena_bytes, size_t* kv_bytes_out, size_t* workspace_bytes) {
+  if (!cfg) return VLA_E_NULL;
+  if (check_config(*cfg)) return VLA_E_CONFIG;
+  if (weight_arena_bytes) *weight_arena_bytes = arena_layout(*cfg).total;
+  if (kv_bytes_out) *kv_bytes_out = kv_bytes(*cfg);
+  if (workspace_bytes) *workspace_bytes = work_layout(*cfg).total;
+  return VLA_OK;
+}
+
+int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace) {
+  if (!ctx) return VLA_E_NULL;
+  if (!weight_arena || !kv || !workspace) return fail(ctx, VLA_E_NULL, "a buffer is NULL");
+  if (((uintptr_t)weight_arena | (uintptr_t)kv | (uintptr_t)workspace) % kAlign)
+    return fail(ctx, VLA_E_SHAPE, "buffers must be %zu-byte aligned", kAlign);
+  if (!ctx->stage) {
+    HIP_TRY(ctx, hipHostMalloc((void**)&ctx->stage, (size_t)vla_ctx::kRing * 2 * (ctx->cfg.max_batch + 1) * sizeof(int32_t), hipHostMallocDefault));
+    for (int i = 0; i < vla_ctx::kRing; ++i) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming));
+  }
+  ctx->arena = (char*)weight_arena;
+  ctx->kv = (char*)kv;
+  ctx->work = (char*)workspace;
+  ctx->bound = true;
+  ctx->weights = false;
+  ctx->tables = false;
+  ctx->active_B = 0;
+  return VLA_OK;
+}
+
+int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  if (!tensors) return fail(ctx, VLA_E_NULL, "tensors is NULL");
+  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
+  const vla_config& c = ctx->cfg;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab, A = c.n_action_bins;
+  static const char* kLeaves[9] = {"attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"};
+  // slot index: 0 embed, 1 final_norm, 2 lm_head, 3 + 9*l + leaf
+  const int n_slots = 3 + 9 * c.n_layers;
+  std::vector<const vla_tensor*> slot(n_slots, nullptr);
+  for (int i = 0; i < n_tensors; ++i) {
+    const vla_tensor& t = tensors[i];
+    if (!t.name || !t.dev_ptr) return fail(ctx, VLA_E_NULL, "tensor %d has a NULL name or pointer", i);
+    int s = -1;
+    if (!strcmp(t.name, "embed")) s = 0;
+    else if (!strcmp(t.name, "final_norm")) s = 1;
+    else if (!strcmp(t.name, "lm_head")) s = 2;
+    else {
+      int l = -1, used = 0;
+      if (sscanf(t.name, "layers.%d.%n", &l, &used) == 1 && used > 0 && l >= 0 && l < c.n_layers)
+        for (int k = 0; k < 9; ++k)
+          if (!strcmp(t.name + used, kLeaves[k])) s = 3 + 9 * l + k;
+    }
+    if (s < 0) return fail(ctx, VLA_E_WEIGHTS, "unknown tensor name '%s'", t.name);
+    if (slot[s]) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' given twice", t.name);
+    if (t.dtype != c.dtype) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' has dtype %d, config has %d", t.name, t.dtype, c.dtype);
+    int64_t r = 0, k = 0;   // expected shape (k == 0: vector)
+    if (s == 0) { r = V; k = d; }
+    else if (s == 1) { r = d; }
+    else if (s == 2) { r = (t.ndim == 2 && t.shape[0] == A) ? A : V; k = d; }
+    else {
+      switch ((s - 3) % 9) {
+        case 0: case 5: r = d; break;
+        case 1: case 2: case 3: case 4: r = d; k = d; break;
+        case 6: case 7: r = f; k = d; break;
+        default: r = d; k = f; break;
+      }
+    }
+    const bool ok = k ? (t.ndim == 2 && t.shape[0] == r && t.shape[1] == k) : (t.ndim == 1 && t.shape[0] == r);
+    if (!ok) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' has the wrong shape", t.name);
+    slot[s] = &t;
+  }
+  for (int s = 0; s < n_slots; ++s)
+    if (!slot[s]) {
+      if (s < 3) return fail(ctx, VLA_E_WEIGHTS, "missing tensor '%s'", s == 0 ? "embed" : s == 1 ? "final_norm" : "lm_head");
+      return fail(ctx, VLA_E_WEIGHTS, "missing tensor 'layers.%d.%s'", (s - 3) / 9, kLeaves[(s - 3) % 9]);
+    }
+
+  const ArenaLayout& a = ctx->al;
+  const bool bf = c.dtype == VLA_BF16;
+  auto gain = [&](const vla_tensor* t, size_t off) {
+    if (bf) convert_copy<bf16>((const bf16*)t->dev_ptr, at<float>(ctx->arena, off), d, st);
+    else convert_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), d, st);
+  };
+  auto matrix = [&](const vla_tensor* t, size_t off, int64_t rows, int64_t K, int64_t row0, int mode) {
+    if (bf) {
+      pack_weight_bf16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<bf16>(ctx->arena, off), 0, (int)row0, mode, st);
+    } else {
+      const int64_t r0 = mode == 2 ? rows : row0;   // float32 path keeps [gate rows | up rows]
+      plain_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off) + r0 * K, (size_t)(rows * K), st);
+    }
+  };
+  auto rows_copy = [&](const void* src, size_t off, size_t n) {
+    if (bf) plain_copy<bf16>((const bf16*)src, at<bf16>(ctx->arena, off), n, st);
+    else plain_copy<float>((const float*)src, at<float>(ctx->arena, off), n, st);
+  };
+  rows_copy(slot[0]->dev_ptr, a.embed, (size_t)(V * d));
+  gain(slot[1], a.g_final);
+  {
+    const vla_tensor* h = slot[2];
+    const size_t skip = h->shape[0] == A ? 0 : (size_t)((V - A) * d) * elem_size(c.dtype);
+    rows_copy((const char*)h->dev_ptr + skip, a.head, (size_t)(A * d));
+  }
+  for (int l = 0; l < c.n_layers; ++l) {
+    const vla_tensor* const* t = &slot[3 + 9 * l];
+    const LayerW& lw = a.layers[l];
+    gain(t[0], lw.g_attn);
+    matrix(t[1], lw.w_qkv, d, d, 0, 0);
+    matrix(t[2], lw.w_qkv, d, d, d, 0);
+    matrix(t[3], lw.w_qkv, d, d, 2 * d, 0);
+    matrix(t[4], lw.w_o, d, d, 0, 0);
+    gain(t[5], lw.g_ffn);
+    matrix(t[6], lw.w_gu, f, d, 0, 1);
+    matrix(t[7], lw.w_gu, f, d, 0, 2);
+    matrix(t[8], lw.w_down, d, f, 0, 0);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  ctx->weights = true;
+  return VLA_OK;
+}
+
+int vla_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
+                const int32_t* cu_instr, float* logits_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  int64_t T = 0;
+  rc = check_prefill(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, 0, &T);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int A = ctx->cfg.n_action_bins;
+  if (ctx->cfg.dtype == VLA_BF16) return do_prefill<bf16>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st);
+  return do_prefill<float>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st);
+}
+
+int vla_decode_step(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if (!token_ids) return fail(ctx, VLA_E_NULL, "token_ids is NULL");
+  rc = check_decode(ctx, B, 1);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int A = ctx->cfg.n_action_bins;
+  if (ctx->cfg.dtype == VLA_BF16) return do_decode<bf16>(ctx, B, token_ids, logits_out, A, st);
+  return do_decode<float>(ctx, B, token_ids, logits_out, A, st);
+}
+
+int vla_select(vla_ctx* ctx, int32_t B, const float* logits, float temperature, const float* gumbel, int32_t k,
+               int32_t n_tokens, const float* act_scale, const float* act_offset, int32_t action_dim,
+               int32_t* tokens_out, float* logp_out, float* actions_out, int32_t out_stride, int32_t* next_ids_out,
+               void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  if (!logits || !tokens_out || !logp_out || !actions_out) return fail(ctx, VLA_E_NULL, "a required pointer is NULL");
+  if (B <= 0 || k < 0 || n_tokens <= 0 || k >= n_tokens || out_stride < n_tokens || action_dim < 0 || !(temperature >= 0.f))
+    return fail(ctx, VLA_E_SHAPE, "bad selection arguments");
+  const vla_config& c = ctx->cfg;
+  ProfScope ps(ctx, FAM_HEAD, (hipStream_t)hip_stream);
+  select_tokens(logits, c.n_action_bins, B, c.n_action_bins, temperature, gumbel, k, n_tokens, act_scale, act_offset,
+                action_dim, tokens_out, logp_out, actions_out, out_stride, next_ids_out, c.vocab - c.n_action_bins,
+                (hipStream_t)hip_stream);
+  HIP_TRY(ctx, hipGetLastError());
+  return VLA_OK;
+}
+
+int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
+                    const int32_t* cu_instr, int32_t n_tokens, float temperature, const float* gumbel,
+                    const float* act_scale, const float* act_offset, int32_t action_dim, int32_t* tokens_out,
+                    float* logp_out, float* actions_out, float* logits_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if (!tokens_out || !logp_out || !actions_out) return fail(ctx, VLA_E_NULL, "an output pointer is NULL");
+  if (n_tokens <= 0) return fail(ctx, VLA_E_SHAPE, "n_tokens must be positive");
+  if (!(temperature >= 0.f)) return fail(ctx, VLA_E_SHAPE, "temperature must be >= 0");
+  if (action_dim < 0) return fail(ctx, VLA_E_SHAPE, "action_dim must be >= 0");
+  int64_t T = 0;
+  rc = check_prefill(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, &T);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const vla_config& c = ctx->cfg;
+  const int A = c.n_action_bins, id0 = c.vocab - A;
+  int32_t* cur = at<int32_t>(ctx->work, ctx->wl.cur_ids);
+  float* own = at<float>(ctx->work, ctx->wl.logits);
+  const bool bf = c.dtype == VLA_BF16;
+  for (int k = 0; k < n_tokens; ++k) {
+    float* lg = logits_out ? logits_out + (size_t)k * A : own;
+    const int ld = logits_out ? n_tokens * A : A;
+    if (k == 0)
+      rc = bf ? do_prefill<bf16>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, lg, ld, st)
+              : do_prefill<float>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, lg, ld, st);
+    else
+      rc = bf ? do_decode<bf16>(ctx, B, cur, lg, ld, st) : do_decode<float>(ctx, B, cur, lg, ld, st);
+    if (rc) return rc;
+    ProfScope ps(ctx, FAM_HEAD, st);
+    select_tokens(lg, ld, B, A, temperature, gumbel, k, n_tokens, act_scale, act_offset, action_dim, tokens_out,
+                  logp_out, actions_out, n_tokens, cur, id0, st);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  return VLA_OK;
+}
+
+int vla_prof_enable(vla_ctx* ctx, int32_t mask) {
+  if (!ctx) return VLA_E_NULL;
+  for (auto& v : ctx->prof) {
+    for (auto& p : v) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+    v.clear();
+  }
+  ctx->prof_mask = (unsigned)mask;
+  return VLA_OK;
+}
+
+int vla_prof_count(void) { return FAM_COUNT; }
+
+int vla_prof_read(vla_ctx* ctx, int32_t i, const char** name, int64_t* launches, double* total_ms) {
+  if (!ctx) return VLA_E_NULL;
+  if (i < 0 || i >= FAM_COUNT) return fail(ctx, VLA_E_SHAPE, "family index out of range");
+  double tot = 0.0;
+  for (auto& p : ctx->prof[i]) {
+    HIP_TRY(ctx, hipEventSynchronize(p.b));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, p.a, p.b));
+    tot += ms;
+  }
+  if (name) *name = kFamilyNames[i];
+  if (launches) *launches = (int64_t)ctx->prof[i].size();
+  if (total_ms) *total_ms = tot;
+  return VLA_OK;
+}
+
+}  // extern "C"

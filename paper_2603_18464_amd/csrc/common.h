@@ -1,0 +1,115 @@
+// Shared device helpers and the host-side launcher declarations of the VLA policy library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vla {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <class T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- kernel families timed by the profiling hooks ----------------------------------------------
+enum Family {
+  FAM_GEMM_PREFILL = 0,
+  FAM_ATTN_PREFILL,
+  FAM_GEMM_DECODE,
+  FAM_ATTN_DECODE,
+  FAM_NORM,
+  FAM_HEAD,
+  FAM_MISC,
+  FAM_COUNT
+};
+
+// ---- launcher arguments ---------------------------------------------------------------------------
+struct RopeKv {
+  void* q;               // [T, d] storage dtype, rotated queries
+  void* k_cache;         // layer base: [slot][head][position][head_dim]
+  void* v_cache;
+  const int32_t* tok_seq;   // [T] slot of each packed token
+  const int32_t* tok_pos;   // [T] position of each packed token inside its sequence
+  const float* rope_cos;    // [max_seq, head_dim/2]
+  const float* rope_sin;
+  int n_heads, head_dim, max_seq, d_model;
+};
+
+struct GemmBf16 {
+  const bf16* A;   // [M, K] row-major activations
+  int lda;
+  const bf16* Wp;  // [N, K] weights in MFMA fragment order (see pack_weight_bf16)
+  int M, N, K;
+};
+
+// C = A * W^T with fused epilogues (bf16 MFMA, fp32 accumulation).
+void gemm_bf16_resid(const GemmBf16& g, float* x, int ldx, hipStream_t st);           // x += C
+void gemm_bf16_swiglu(const GemmBf16& g, bf16* act, int ldact, hipStream_t st);       // silu(gate)*up
+void gemm_bf16_qkv(const GemmBf16& g, const RopeKv& o, hipStream_t st);               // RoPE + cache
+void pack_weight_bf16(const bf16* src, int rows, int K, bf16* dst, int N_total, int row0,
+                      int interleave_mode, hipStream_t st);
+
+// fp32 path (plain, unfused).
+void gemm_f32(const float* A, int lda, const float* W, float* C, int M, int N, int K, hipStream_t st);
+void rope_kv_f32(const float* qkv, int T, const RopeKv& o, hipStream_t st);
+void resid_add_f32(float* x, const float* c, size_t n, hipStream_t st);
+void swiglu_f32(const float* gu, float* act, int T, int f, hipStream_t st);
+
+// Row-wise kernels.
+template <class T>
+void rmsnorm(const float* x, const T* /*unused tag*/, const float* gain, T* out, int rows, int d,
+             float eps, const int32_t* row_index, hipStream_t st);
+template <class T>
+void assemble_prefix(const T* patch_emb, const int32_t* instr_ids, const T* embed,
+                     const int32_t* tok_src, float* x, int T_tokens, int d, hipStream_t st);
+template <class T>
+void embed_tokens(const int32_t* ids, const T* embed, float* x, int B, int d, int vocab, hipStream_t st);
+
+// Attention: one query row per (token, head) against the cache.
+template <class T>
+void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, const int32_t* tok_seq,
+                    const int32_t* tok_pos, T* out, int ldo, int n_tok, int n_heads, int head_dim,
+                    int max_seq, hipStream_t st);
+
+// Action head: final RMSNorm + action rows of the LM head -> logits [B, A] float32.
+template <class T>
+void head_logits(const float* x, const int32_t* row_index, const float* gain, const T* w_head,
+                 float* logits, int ld_logits, int B, int d, int A, float eps, hipStream_t st);
+void select_tokens(const float* logits, int ld_logits, int B, int A, float temperature, const float* gumbel, int k,
+                   int n_tokens, const float* act_scale, const float* act_offset, int action_dim,
+                   int32_t* tokens_out, float* logp_out, float* actions_out, int out_stride,
+                   int32_t* next_ids, int id0, hipStream_t st);
+
+// Small utilities.
+void rope_table(float* cos_t, float* sin_t, int max_seq, int head_dim, float theta, hipStream_t st);
+void build_token_maps(const int32_t* cu_patch_dev, const int32_t* cu_instr_dev, int B, int T_tokens,
+                      int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src, int32_t* last_row,
+                      int32_t* seq_len, hipStream_t st);
+void decode_maps(int32_t* seq_len, int B, int32_t* tok_seq, int32_t* tok_pos, hipStream_t st);
+void advance_lengths(int32_t* seq_len, int B, hipStream_t st);
+template <class T>
+void convert_copy(const T* src, float* dst, size_t n, hipStream_t st);   // gains -> float32
+template <class T>
+void plain_copy(const T* src, T* dst, size_t n, hipStream_t st);
+
+}  // namespace vla

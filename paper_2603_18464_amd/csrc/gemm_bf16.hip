@@ -1,0 +1,301 @@
+// bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for gfx950, with the layer's elementwise work fused
+// into the epilogue (residual add; SwiGLU; rotary embedding + KV-cache write).
+//
+// Operand layouts
+//   A   row-major [M, lda] bf16 (activations produced by this library).
+//   Wp  weights repacked once at load time into MFMA fragment order: the 32x16 block
+//       (rows n0..n0+31, k0..k0+15) is stored as 64 lanes x 8 bf16 = 1 KiB, lane l holding
+//       row n0 + (l & 31), k = k0 + 8*(l >> 5) .. +7; blocks are ordered [n/32][k/16].  A wave
+//       reads one block with a single fully coalesced 16-byte-per-lane load, from global memory or
+//       from LDS, with no bank conflicts and no swizzle.
+// The kernel keeps a BM x 64 slab of A (XOR-swizzled 16-byte chunks) and a BN x 64 slab of Wp in
+// LDS, double buffered, and each of the 4 waves owns a (BM/WGM) x (BN/WGN) accumulator tile made
+// of 32x32x16 MFMAs.
+#include "common.h"
+
+namespace vla {
+
+constexpr int BK = 64;
+
+// ---- epilogues ------------------------------------------------------------------------------------
+// Accumulator layout of v_mfma_f32_32x32x16_bf16: lane l, register 4*blk + r holds
+// C[row = 8*blk + 4*(l >> 5) + r][col = l & 31].
+
+struct EpiResid {
+  float* x;
+  int ldx;
+  template <int MT, int NT>
+  __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
+    const int h = lane >> 5, c = lane & 31;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = mb + mt * 32 + 8 * blk + 4 * h + r;
+          if (m < M) {
+            float* row = x + (size_t)m * ldx + nb + c;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) row[nt * 32] += acc[mt][nt][4 * blk + r];
+          }
+        }
+  }
+};
+
+// Fused gate/up weights are interleaved in blocks of 32 rows: [gate 0..31, up 0..31, gate 32..63, ...]
+// so that a wave's even 32-column tiles are gates and the following odd tiles the matching ups.
+struct EpiSwiglu {
+  bf16* act;
+  int ld;
+  template <int MT, int NT>
+  __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
+    static_assert(NT % 2 == 0, "gate/up tiles come in pairs");
+    const int h = lane >> 5, c = lane & 31;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = mb + mt * 32 + 8 * blk + 4 * h + r;
+          if (m < M) {
+            bf16* row = act + (size_t)m * ld + nb / 2 + c;
+#pragma unroll
+            for (int j = 0; j < NT / 2; ++j) {
+              const float g = acc[mt][2 * j][4 * blk + r], u = acc[mt][2 * j + 1][4 * blk + r];
+              row[j * 32] = (bf16)(g / (1.0f + __expf(-g)) * u);
+            }
+          }
+        }
+  }
+};
+
+// Columns [0,d) are queries, [d,2d) keys, [2d,3d) values.  A wave tile covers whole heads, so the
+// rotary partner (i, i + hd/2) of every column sits in the same lane, HD/64 tiles further on.
+template <int HD>
+struct EpiQkv {
+  RopeKv o;
+  template <int MT, int NT>
+  __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
+    constexpr int HT = HD / 32;              // 32-column tiles per head
+    constexpr int HALF = HD / 2;
+    static_assert(NT % HT == 0, "wave tile must cover whole heads");
+    const int h = lane >> 5, c = lane & 31;
+    const int d = o.d_model;
+    const int sect = nb / d;                 // 0 q, 1 k, 2 v (a wave tile never straddles)
+    const int col0 = nb - sect * d;          // first column inside the section
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = mb + mt * 32 + 8 * blk + 4 * h + r;
+          if (m >= M) continue;
+          const int pos = o.tok_pos[m], slot = o.tok_seq[m];
+          const int ai = 4 * blk + r;
+          const float* cs_row = o.rope_cos + (size_t)pos * HALF;
+          const float* sn_row = o.rope_sin + (size_t)pos * HALF;
+#pragma unroll
+          for (int hh = 0; hh < NT / HT; ++hh) {
+            const int head = (col0 + hh * HD) / HD;
+            bf16* dst;
+            if (sect == 0) dst = (bf16*)o.q + (size_t)m * d + (size_t)head * HD;
+            else dst = (bf16*)(sect == 1 ? o.k_cache : o.v_cache) +
+                       (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * HD;
+#pragma unroll
+            for (int ht = 0; ht < HT / 2; ++ht) {
+              const int j = ht * 32 + c;     // index of the pair inside the head
+              float lo = acc[mt][hh * HT + ht][ai], hi = acc[mt][hh * HT + ht + HT / 2][ai];
+              if (sect < 2) {
+                const float cs = cs_row[j], sn = sn_row[j];
+                const float a = lo * cs - hi * sn, b = hi * cs + lo * sn;
+                lo = a;
+                hi = b;
+              }
+              dst[j] = (bf16)lo;
+              dst[j + HALF] = (bf16)hi;
+            }
+          }
+        }
+  }
+};
+
+// ---- kernel -----------------------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, class Epi>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
+    const bf16* __restrict__ A, int lda, const bf16* __restrict__ Wp, int M, int N, int K,
+    int tiles_m, int tiles_n, Epi epi) {
+  constexpr int NTHR = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
+  constexpr int A_ITERS = BM * 8 / NTHR;   // 16-byte chunks of the A slab per thread
+  constexpr int W_ITERS = BN * 8 / NTHR;
+  static_assert(BM * 8 % NTHR == 0 && BN * 8 % NTHR == 0, "slab must divide among threads");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* As = (bf16*)smem;                       // [2][BM*64]
+  bf16* Ws = As + 2 * BM * BK;                  // [2][BN*64]
+
+  // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give each XCD a
+  // contiguous run of tiles, walked in groups of GM row-tiles that share the same weight columns.
+  const int nblk = tiles_m * tiles_n;
+  const int per_xcd = gridDim.x >> 3;
+  const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (pid >= nblk) return;
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int grp = pid / per_group;
+  const int first_m = grp * GM;
+  const int gm = min(tiles_m - first_m, GM);
+  const int in_grp = pid - grp * per_group;
+  const int tm = first_m + in_grp % gm;
+  const int tn = in_grp / gm;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int KB16 = K >> 4, KT = K / BK;
+
+  // per-thread source addresses
+  const int a_c = t & 7, a_r = t >> 3;
+  const bf16* a_src[A_ITERS];
+  int a_dst[A_ITERS];
+#pragma unroll
+  for (int i = 0; i < A_ITERS; ++i) {
+    const int r = a_r + i * (NTHR / 8);
+    const int gr = min(m0 + r, M - 1);
+    a_src[i] = A + (size_t)gr * lda + a_c * 8;
+    a_dst[i] = r * BK + ((a_c ^ (r & 7)) << 3);
+  }
+  const bf16* w_src[W_ITERS];
+#pragma unroll
+  for (int i = 0; i < W_ITERS; ++i) {
+    const int q = t + i * NTHR;
+    const int nb = q >> 8, off = q & 255;
+    w_src[i] = Wp + ((size_t)(n0 / 32 + nb) * KB16) * 512 + off * 8;
+  }
+
+  uint4 ra[A_ITERS], rw[W_ITERS];
+  auto load_global = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const uint4*)(a_src[i] + kt * BK);
+#pragma unroll
+    for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const uint4*)(w_src[i] + (size_t)kt * 4 * 512);
+  };
+  auto store_lds = [&](int buf) {
+    bf16* as = As + buf * BM * BK;
+    bf16* ws = Ws + buf * BN * BK;
+#pragma unroll
+    for (int i = 0; i < A_ITERS; ++i) *(uint4*)(as + a_dst[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < W_ITERS; ++i) *(uint4*)(ws + (t + i * NTHR) * 8) = rw[i];
+  };
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  const int frow = wm * WTM + (lane & 31);
+  const int fhalf = lane >> 5;
+
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    if (kt + 1 < KT) load_global(kt + 1);
+    const bf16* as = As + (kt & 1) * BM * BK;
+    const bf16* ws = Ws + (kt & 1) * BN * BK;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[MT], bfr[NT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int row = frow + mt * 32;
+        const int c = kk * 2 + fhalf;
+        af[mt] = *(const bf16x8*)(as + row * BK + ((c ^ (row & 7)) << 3));
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        bfr[nt] = *(const bf16x8*)(ws + ((wn * NT + nt) * 4 + kk) * 512 + lane * 8);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_lds((kt + 1) & 1);
+    __syncthreads();
+  }
+  epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
+}
+
+template <int BM, int BN, int WGM, int WGN, class Epi>
+static void launch(const GemmBf16& g, const Epi& epi, hipStream_t st) {
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
+  const int nblk = tiles_m * tiles_n;
+  const int grid = (nblk + 7) / 8 * 8;
+  constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(bf16);
+  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, Epi>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K,
+                     tiles_m, tiles_n, epi);
+}
+
+// Tile choice: big square tiles when there are enough rows to fill them, a 64-row tile for the
+// decode-sized problems.  The QKV epilogue needs wave tiles that cover whole heads (128 columns).
+template <class Epi>
+static void dispatch(const GemmBf16& g, const Epi& epi, hipStream_t st) {
+  if (g.M > 128 && g.N % 256 == 0)
+    launch<256, 256, 2, 2, Epi>(g, epi, st);
+  else if (g.N % 256 == 0)
+    launch<64, 256, 2, 2, Epi>(g, epi, st);
+  else
+    launch<64, 128, 2, 1, Epi>(g, epi, st);   // N multiple of 128
+}
+
+void gemm_bf16_resid(const GemmBf16& g, float* x, int ldx, hipStream_t st) {
+  dispatch(g, EpiResid{x, ldx}, st);
+}
+void gemm_bf16_swiglu(const GemmBf16& g, bf16* act, int ldact, hipStream_t st) {
+  dispatch(g, EpiSwiglu{act, ldact}, st);
+}
+void gemm_bf16_qkv(const GemmBf16& g, const RopeKv& o, hipStream_t st) {
+  if (o.head_dim == 128) dispatch(g, EpiQkv<128>{o}, st);
+  else dispatch(g, EpiQkv<64>{o}, st);
+}
+
+// ---- weight repacking -------------------------------------------------------------------------------
+// Copies `rows` source rows [rows, K] into the packed matrix of N_total rows starting at packed row
+// `row0`.  interleave_mode 0: packed row = row0 + r.  1 (gate) / 2 (up): rows go to the even / odd
+// 32-row blocks of the fused gate-up matrix.
+__global__ void pack_weight_kernel(const bf16* __restrict__ src, int rows, int K, bf16* __restrict__ dst,
+                                   int row0, int mode) {
+  const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // 8 consecutive k of one row
+  const int kchunks = K >> 3;
+  if (chunk >= (size_t)rows * kchunks) return;
+  const int r = (int)(chunk / kchunks), kc = (int)(chunk % kchunks);
+  int pr;
+  if (mode == 0) pr = row0 + r;
+  else pr = (r / 32) * 64 + (mode == 2 ? 32 : 0) + (r & 31);
+  const int nb = pr >> 5, kb = kc >> 1, lane = (pr & 31) + 32 * (kc & 1);
+  const uint4 v = *(const uint4*)(src + (size_t)r * K + kc * 8);
+  *(uint4*)(dst + ((size_t)nb * (K >> 4) + kb) * 512 + lane * 8) = v;
+}
+
+void pack_weight_bf16(const bf16* src, int rows, int K, bf16* dst, int N_total, int row0,
+                      int interleave_mode, hipStream_t st) {
+  (void)N_total;
+  const size_t chunks = (size_t)rows * (K >> 3);
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, src,
+                     rows, K, dst, row0, interleave_mode);
+}
+
+}  // namespace vla

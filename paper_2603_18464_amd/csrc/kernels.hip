@@ -1,0 +1,376 @@
+// Row-wise and small kernels of the VLA policy path: prefix assembly, RMSNorm, the action head
+// (final norm + slimmed LM head), token selection with log-probs and de-tokenisation, rotary
+// tables, token maps, and the plain float32 path used when the storage dtype is float32.
+#include "common.h"
+
+namespace vla {
+
+// ---- token maps ---------------------------------------------------------------------------------
+// Packed prefix token t belongs to sequence slot b with cu_seq[b] <= t < cu_seq[b+1], where
+// cu_seq[b] = cu_patch[b] + cu_instr[b].  tok_src >= 0 is a row of patch_emb, tok_src < 0 is
+// instruction id number -1 - tok_src.
+__global__ void token_maps_kernel(const int32_t* __restrict__ cu_patch, const int32_t* __restrict__ cu_instr,
+                                  int B, int T, int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src,
+                                  int32_t* last_row, int32_t* seq_len) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < B) {
+    const int end = cu_patch[t + 1] + cu_instr[t + 1];
+    last_row[t] = end - 1;
+    seq_len[t] = end - (cu_patch[t] + cu_instr[t]);
+  }
+  if (t >= T) return;
+  int lo = 0, hi = B;                       // find b with cu_seq[b] <= t < cu_seq[b+1]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu_patch[mid] + cu_instr[mid] <= t) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  const int pos = t - (cu_patch[b] + cu_instr[b]);
+  const int np = cu_patch[b + 1] - cu_patch[b];
+  tok_seq[t] = b;
+  tok_pos[t] = pos;
+  tok_src[t] = pos < np ? cu_patch[b] + pos : -1 - (cu_instr[b] + pos - np);
+}
+
+void build_token_maps(const int32_t* cu_patch_dev, const int32_t* cu_instr_dev, int B, int T_tokens,
+                      int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src, int32_t* last_row,
+                      int32_t* seq_len, hipStream_t st) {
+  const int n = T_tokens > B ? T_tokens : B;
+  hipLaunchKernelGGL(token_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cu_patch_dev, cu_instr_dev,
+                     B, T_tokens, tok_seq, tok_pos, tok_src, last_row, seq_len);
+}
+
+__global__ void decode_maps_kernel(const int32_t* seq_len, int B, int32_t* tok_seq, int32_t* tok_pos) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) {
+    tok_seq[b] = b;
+    tok_pos[b] = seq_len[b];
+  }
+}
+void decode_maps(int32_t* seq_len, int B, int32_t* tok_seq, int32_t* tok_pos, hipStream_t st) {
+  hipLaunchKernelGGL(decode_maps_kernel, dim3((B + 255) / 256), dim3(256), 0, st, seq_len, B, tok_seq, tok_pos);
+}
+
+__global__ void advance_kernel(int32_t* seq_len, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) seq_len[b] += 1;
+}
+void advance_lengths(int32_t* seq_len, int B, hipStream_t st) {
+  hipLaunchKernelGGL(advance_kernel, dim3((B + 255) / 256), dim3(256), 0, st, seq_len, B);
+}
+
+// ---- rotary table ---------------------------------------------------------------------------------
+// cos/sin of pos * theta^(-2i/hd), evaluated in double so that the float32 path keeps 1e-4 logits.
+__global__ void rope_table_kernel(float* cos_t, float* sin_t, int max_seq, int half, double theta) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= max_seq * half) return;
+  const int pos = idx / half, i = idx - pos * half;
+  const double inv = pow(theta, -(double)i / (double)half);
+  const double ang = (double)pos * inv;
+  cos_t[idx] = (float)cos(ang);
+  sin_t[idx] = (float)sin(ang);
+}
+void rope_table(float* cos_t, float* sin_t, int max_seq, int head_dim, float theta, hipStream_t st) {
+  const int n = max_seq * (head_dim / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cos_t, sin_t, max_seq,
+                     head_dim / 2, (double)theta);
+}
+
+// ---- copies ---------------------------------------------------------------------------------------
+template <class T>
+__global__ void convert_kernel(const T* src, float* dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = to_f32(src[i]);
+}
+template <class T>
+void convert_copy(const T* src, float* dst, size_t n, hipStream_t st) {
+  hipLaunchKernelGGL(convert_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, dst, n);
+}
+template void convert_copy<float>(const float*, float*, size_t, hipStream_t);
+template void convert_copy<bf16>(const bf16*, float*, size_t, hipStream_t);
+
+template <class T>
+__global__ void copy_kernel(const T* src, T* dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+template <class T>
+void plain_copy(const T* src, T* dst, size_t n, hipStream_t st) {
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(copy_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, src, dst, n);
+}
+template void plain_copy<float>(const float*, float*, size_t, hipStream_t);
+template void plain_copy<bf16>(const bf16*, bf16*, size_t, hipStream_t);
+
+// ---- prefix assembly ------------------------------------------------------------------------------
+// x[t, :] = patch_emb[src] or embed[instr_ids[-1-src]], widened to the float32 residual stream.
+template <class T>
+__global__ void assemble_kernel(const T* __restrict__ patch_emb, const int32_t* __restrict__ instr_ids,
+                                const T* __restrict__ embed, const int32_t* __restrict__ tok_src,
+                                float* __restrict__ x, int d) {
+  const int t = blockIdx.x;
+  const int src = tok_src[t];
+  const T* row = src >= 0 ? patch_emb + (size_t)src * d : embed + (size_t)instr_ids[-1 - src] * d;
+  float* out = x + (size_t)t * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) out[i] = to_f32(row[i]);
+}
+template <class T>
+void assemble_prefix(const T* patch_emb, const int32_t* instr_ids, const T* embed, const int32_t* tok_src,
+                     float* x, int T_tokens, int d, hipStream_t st) {
+  hipLaunchKernelGGL(assemble_kernel<T>, dim3(T_tokens), dim3(256), 0, st, patch_emb, instr_ids, embed,
+                     tok_src, x, d);
+}
+template void assemble_prefix<float>(const float*, const int32_t*, const float*, const int32_t*, float*, int,
+                                     int, hipStream_t);
+template void assemble_prefix<bf16>(const bf16*, const int32_t*, const bf16*, const int32_t*, float*, int, int,
+                                    hipStream_t);
+
+template <class T>
+__global__ void embed_kernel(const int32_t* __restrict__ ids, const T* __restrict__ embed,
+                             float* __restrict__ x, int d, int vocab) {
+  const int b = blockIdx.x;
+  int id = ids[b];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // ids come from device memory: stay in bounds
+  const T* row = embed + (size_t)id * d;
+  float* out = x + (size_t)b * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) out[i] = to_f32(row[i]);
+}
+template <class T>
+void embed_tokens(const int32_t* ids, const T* embed, float* x, int B, int d, int vocab, hipStream_t st) {
+  hipLaunchKernelGGL(embed_kernel<T>, dim3(B), dim3(256), 0, st, ids, embed, x, d, vocab);
+}
+template void embed_tokens<float>(const int32_t*, const float*, float*, int, int, int, hipStream_t);
+template void embed_tokens<bf16>(const int32_t*, const bf16*, float*, int, int, int, hipStream_t);
+
+// ---- RMSNorm ----------------------------------------------------------------------------------------
+// out[r, :] = x[row, :] * gain / sqrt(mean(x^2) + eps), statistics in float32; one workgroup per row.
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                      T* __restrict__ out, int d, float eps,
+                                                      const int32_t* __restrict__ row_index) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const float* row = x + (size_t)(row_index ? row_index[r] : r) * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {
+    const float4 v = *(const float4*)(row + i);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum_256(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  T* o = out + (size_t)r * d;
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {
+    const float4 v = *(const float4*)(row + i);
+    const float4 g = *(const float4*)(gain + i);
+    o[i] = from_f32<T>(v.x * inv * g.x);
+    o[i + 1] = from_f32<T>(v.y * inv * g.y);
+    o[i + 2] = from_f32<T>(v.z * inv * g.z);
+    o[i + 3] = from_f32<T>(v.w * inv * g.w);
+  }
+}
+template <class T>
+void rmsnorm(const float* x, const T*, const float* gain, T* out, int rows, int d, float eps,
+             const int32_t* row_index, hipStream_t st) {
+  hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(rows), dim3(256), 0, st, x, gain, out, d, eps, row_index);
+}
+template void rmsnorm<float>(const float*, const float*, const float*, float*, int, int, float, const int32_t*,
+                             hipStream_t);
+template void rmsnorm<bf16>(const float*, const bf16*, const float*, bf16*, int, int, float, const int32_t*,
+                            hipStream_t);
+
+// ---- action head ------------------------------------------------------------------------------------
+// One workgroup per sequence: final RMSNorm of its row (float32, kept in LDS), then each wave takes
+// action rows of the slimmed head in turn, lanes striding over d, and reduces across the wave.
+template <class T>
+__global__ __launch_bounds__(256) void head_kernel(const float* __restrict__ x, const int32_t* __restrict__ row_index,
+                                                   const float* __restrict__ gain, const T* __restrict__ w_head,
+                                                   float* __restrict__ logits, int ld_logits, int d, int A, float eps) {
+  extern __shared__ float hrow[];          // [d]
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  const float* row = x + (size_t)(row_index ? row_index[b] : b) * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float v = row[i];
+    ss += v * v;
+  }
+  ss = block_sum_256(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) hrow[i] = row[i] * inv * gain[i];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int j = wave; j < A; j += 4) {
+    const T* w = w_head + (size_t)j * d;
+    float acc = 0.f;
+    for (int i = lane; i < d; i += 64) acc += to_f32(w[i]) * hrow[i];
+    acc = wave_sum(acc);
+    if (lane == 0) logits[(size_t)b * ld_logits + j] = acc;
+  }
+}
+template <class T>
+void head_logits(const float* x, const int32_t* row_index, const float* gain, const T* w_head, float* logits,
+                 int ld_logits, int B, int d, int A, float eps, hipStream_t st) {
+  hipLaunchKernelGGL(head_kernel<T>, dim3(B), dim3(256), d * sizeof(float), st, x, row_index, gain, w_head,
+                     logits, ld_logits, d, A, eps);
+}
+template void head_logits<float>(const float*, const int32_t*, const float*, const float*, float*, int, int, int,
+                                 int, float, hipStream_t);
+template void head_logits<bf16>(const float*, const int32_t*, const float*, const bf16*, float*, int, int, int,
+                                int, float, hipStream_t);
+
+// ---- selection ----------------------------------------------------------------------------------------
+// One wave per sequence: scores = logits / tau (+ Gumbel noise); token = lowest index among the
+// maxima; log-prob = log_softmax(logits / tau)[token]; action = bin centre (optionally affine).
+__global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ logits, int ld_logits, int A, float temperature,
+                                                    const float* __restrict__ gumbel, int k, int n_tokens,
+                                                    const float* __restrict__ act_scale,
+                                                    const float* __restrict__ act_offset, int action_dim,
+                                                    int32_t* tokens_out, float* logp_out, float* actions_out,
+                                                    int out_stride, int32_t* next_ids, int id0) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const float* z = logits + (size_t)b * ld_logits;
+  const float inv_tau = temperature > 0.f ? 1.0f / temperature : 1.0f;
+  const float* g = (gumbel && temperature > 0.f) ? gumbel + ((size_t)b * n_tokens + k) * A : nullptr;
+  float best = -INFINITY, zmax = -INFINITY;
+  int best_j = 0x7fffffff;
+  for (int j = lane; j < A; j += 64) {
+    const float y = z[j] * inv_tau;
+    const float s = g ? y + g[j] : y;
+    if (s > best) { best = s; best_j = j; }      // strict: keeps the lowest index within a lane
+    zmax = fmaxf(zmax, y);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ob = __shfl_xor(best, o, 64);
+    const int oj = __shfl_xor(best_j, o, 64);
+    if (ob > best || (ob == best && oj < best_j)) { best = ob; best_j = oj; }
+  }
+  zmax = wave_max(zmax);
+  float se = 0.f;
+  for (int j = lane; j < A; j += 64) se += expf(z[j] * inv_tau - zmax);
+  se = wave_sum(se);
+  if (lane == 0) {
+    const float logp = z[best_j] * inv_tau - zmax - logf(se);
+    float a = -1.0f + (2.0f * (float)best_j + 1.0f) / (float)A;
+    const int dim = action_dim > 0 ? k % action_dim : 0;
+    if (act_scale) a *= act_scale[dim];
+    if (act_offset) a += act_offset[dim];
+    const size_t o = (size_t)b * out_stride + k;
+    tokens_out[o] = best_j;
+    logp_out[o] = logp;
+    actions_out[o] = a;
+    if (next_ids) next_ids[b] = id0 + best_j;
+  }
+}
+void select_tokens(const float* logits, int ld_logits, int B, int A, float temperature, const float* gumbel, int k, int n_tokens,
+                   const float* act_scale, const float* act_offset, int action_dim, int32_t* tokens_out,
+                   float* logp_out, float* actions_out, int out_stride, int32_t* next_ids, int id0,
+                   hipStream_t st) {
+  hipLaunchKernelGGL(select_kernel, dim3(B), dim3(64), 0, st, logits, ld_logits, A, temperature, gumbel, k, n_tokens,
+                     act_scale, act_offset, action_dim, tokens_out, logp_out, actions_out, out_stride, next_ids,
+                     id0);
+}
+
+// ---- float32 path -------------------------------------------------------------------------------------
+// C[M,N] = A[M,K] * W[N,K]^T, 64x64 tiles, 16-deep K slabs in LDS, 4x4 outputs per thread.
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, int lda,
+                                                       const float* __restrict__ W, float* __restrict__ C, int M,
+                                                       int N, int K) {
+  __shared__ float As[16][64 + 1];
+  __shared__ float Ws[16][64 + 1];
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+      const int r = i >> 4, kk = i & 15;
+      const int gm = m0 + r, gn = n0 + r, gk = k0 + kk;
+      As[kk][r] = (gm < M && gk < K) ? A[(size_t)gm * lda + gk] : 0.f;
+      Ws[kk][r] = (gn < N && gk < K) ? W[(size_t)gn * K + gk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = Ws[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < M && n < N) C[(size_t)m * N + n] = acc[i][j];
+    }
+}
+void gemm_f32(const float* A, int lda, const float* W, float* C, int M, int N, int K, hipStream_t st) {
+  hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, A, lda, W, C, M, N, K);
+}
+
+// qkv [T, 3d] float32 -> rotated q [T, d], rotated k and plain v into the cache.
+__global__ void rope_kv_f32_kernel(const float* __restrict__ qkv, RopeKv o) {
+  const int t = blockIdx.x;
+  const int d = o.d_model, hd = o.head_dim, half = hd >> 1;
+  const int pos = o.tok_pos[t], slot = o.tok_seq[t];
+  const float* row = qkv + (size_t)t * 3 * d;
+  for (int idx = threadIdx.x; idx < d / 2; idx += blockDim.x) {
+    const int head = idx / half, i = idx - head * half;
+    const float cs = o.rope_cos[pos * half + i], sn = o.rope_sin[pos * half + i];
+    const int c0 = head * hd + i, c1 = c0 + half;
+    const size_t kv = (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * hd;
+    const float q0 = row[c0], q1 = row[c1], k0 = row[d + c0], k1 = row[d + c1];
+    float* q = (float*)o.q + (size_t)t * d;
+    q[c0] = q0 * cs - q1 * sn;
+    q[c1] = q1 * cs + q0 * sn;
+    ((float*)o.k_cache)[kv + i] = k0 * cs - k1 * sn;
+    ((float*)o.k_cache)[kv + i + half] = k1 * cs + k0 * sn;
+    ((float*)o.v_cache)[kv + i] = row[2 * d + c0];
+    ((float*)o.v_cache)[kv + i + half] = row[2 * d + c1];
+  }
+}
+void rope_kv_f32(const float* qkv, int T, const RopeKv& o, hipStream_t st) {
+  hipLaunchKernelGGL(rope_kv_f32_kernel, dim3(T), dim3(128), 0, st, qkv, o);
+}
+
+__global__ void resid_add_kernel(float* x, const float* c, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) x[i] += c[i];
+}
+void resid_add_f32(float* x, const float* c, size_t n, hipStream_t st) {
+  hipLaunchKernelGGL(resid_add_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, c, n);
+}
+
+// gu [T, 2f] = [gate | up] -> act [T, f] = silu(gate) * up
+__global__ void swiglu_f32_kernel(const float* __restrict__ gu, float* __restrict__ act, int f, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const size_t t = i / f;
+  const int j = (int)(i - t * f);
+  const float g = gu[t * 2 * f + j], u = gu[t * 2 * f + f + j];
+  act[i] = g / (1.0f + expf(-g)) * u;
+}
+void swiglu_f32(const float* gu, float* act, int T, int f, hipStream_t st) {
+  const size_t n = (size_t)T * f;
+  hipLaunchKernelGGL(swiglu_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, gu, act, f, n);
+}
+
+}  // namespace vla

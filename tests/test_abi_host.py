@@ -1,0 +1,67 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, and validates configurations."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import workloads as W
+from paper_2603_18464_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "vla.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vla_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_config_validation_and_sizes():
+    wl = W.get_workload("C3")
+    cfg = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
+    arena, kv, work = B.vla_query_sizes(cfg)
+    s = wl.shape
+    assert kv == 2 * s.n_layers * wl.batch * s.n_heads * wl.max_seq * s.head_dim * 2
+    assert arena >= 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model)
+    assert arena < 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model) + (4 << 20)   # head is slimmed: no second [V,d] matrix
+    ctx = B.vla_create(cfg)
+    B.vla_destroy(ctx)
+    for field, value in [("n_heads", 31), ("dtype", 5), ("n_action_bins", 0), ("n_action_bins", 40000),
+                         ("max_seq", 0), ("head_dim", 100), ("rope_theta", 0.0)]:
+        bad = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
+        setattr(bad, field, value)
+        with pytest.raises(B.VlaError) as e:
+            B.vla_create(bad)
+        assert e.value.code == -2, field
+        with pytest.raises(B.VlaError):
+            B.vla_query_sizes(bad)
+
+
+def test_null_arguments_and_unbound_state():
+    L = B.lib()
+    assert L.vla_create(None, None) == -1
+    assert L.vla_destroy(None) == -1
+    assert L.vla_prefill(None, 1, None, None, None, None, None, None) == -1
+    wl = W.get_workload("C1")
+    ctx = B.vla_create(B.make_config(wl.shape, 4, 64, 256))
+    with pytest.raises(B.VlaError) as e:
+        B.vla_bind_buffers(ctx, None, None, None)
+    assert e.value.code == -1
+    # nothing bound yet: every compute entry point refuses
+    cu = (C.c_int32 * 2)(0, 1)
+    assert L.vla_prefill(ctx, 1, None, cu, None, cu, None, None) == -5
+    assert L.vla_decode_step(ctx, 1, None, None, None) == -5
+    assert L.vla_load_weights(ctx, None, 0, None) == -1
+    assert "bound" in B.vla_last_error(ctx) or "NULL" in B.vla_last_error(ctx)
+    assert B.vla_prof_count() == 7
+    B.vla_destroy(ctx)
