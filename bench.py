@@ -1,0 +1,173 @@
+"""Benchmark of the whole policy step (prefill + K-1 decode steps + selection) on one MI355X.
+
+Prints ONE JSON line: actions/sec of the policy step on the 7B-shaped workload C3 (bf16, batch 64,
+256 patches + 34 instruction tokens, 7 greedy action tokens), with the roofline of the dominant
+kernel (the prefill gate/up GEMM, timed with HIP events on the launch stream) and the fp64 oracle
+timed on the host cores for a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads as W  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def model_numbers(wl, cu_seq):
+    s = wl.shape
+    d, f, L = s.d_model, s.d_ffn, s.n_layers
+    S = np.diff(cu_seq).astype(np.int64)
+    T = int(S.sum())
+    P = s.n_matrix_params
+    es = 2 if s.dtype == "bf16" else 4
+    prefill_flops = 2 * P * T + L * int((2 * S * S * d).sum()) + 2 * s.n_action_bins * d * wl.batch
+    kv_pos_bytes = 2 * d * L * es                      # K and V of one position, all layers
+    decode_bytes = []
+    for k in range(1, wl.n_tokens):                    # step k reads ctx = S + k positions (incl. the new one)
+        decode_bytes.append(P * es + int((S + k).sum()) * kv_pos_bytes + wl.batch * kv_pos_bytes)
+    return dict(T=T, P=P, prefill_flops=prefill_flops, decode_bytes=decode_bytes,
+                gateup_flops=2 * T * 2 * f * d, qkv_flops=2 * T * 3 * d * d, o_flops=2 * T * d * d,
+                down_flops=2 * T * d * f)
+
+
+def cpu_baseline(wl, weights_fn, obs, sample_layers):
+    """Oracle ("cached" mode) on one sequence through `sample_layers` of the layers, scaled linearly
+    to the full depth (every layer costs the same)."""
+    from threadpoolctl import threadpool_info
+    from oracle import vla_oracle as O
+    names = ["embed", "final_norm", "lm_head"] + [n for n in W.weight_names(wl.shape)
+                                                  if n.startswith("layers.") and int(n.split(".")[1]) < sample_layers]
+    weights = weights_fn(names)
+    pol = O.OraclePolicy(wl.shape, weights)
+    pe = [obs["patch_emb"][obs["cu_patch"][0]:obs["cu_patch"][1]]]
+    ids = [obs["instr_ids"][obs["cu_instr"][0]:obs["cu_instr"][1]]]
+    t0 = time.perf_counter()
+    pol.policy_step(pe, ids, wl.n_tokens, mode="cached", n_layers=sample_layers)
+    dt = time.perf_counter() - t0
+    full = dt * wl.shape.n_layers / sample_layers
+    cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    return {"value": (wl.n_tokens / wl.action_dim) / full, "unit": "actions/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"1 of {wl.batch} sequences, {sample_layers} of {wl.shape.n_layers} layers, "
+                      f"{dt:.1f} s measured, scaled linearly to all layers"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch (0 = the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--prof-mask", type=lambda v: int(v, 0), default=0x1fff)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the policy shards by "
+              "sequence with full weight replicas and no exchange); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2603_18464_amd as P
+    from paper_2603_18464_amd import VlaPolicy
+
+    wl = W.get_workload(args.workload)
+    if args.batch:
+        wl = wl.scaled(batch=args.batch)
+    t0 = time.perf_counter()
+    weights = W.make_weights(wl.shape, wl.seed, threads=16)
+    obs = W.make_observations(wl)
+    gum = W.make_gumbel(wl) if wl.sampling == "gumbel" else None
+    cu_seq = obs["cu_patch"] + obs["cu_instr"]
+    nums = model_numbers(wl, cu_seq)
+    pol = VlaPolicy(wl.shape, wl.batch, wl.max_seq, nums["T"])
+    pol.load_weights(weights)
+    keep = {n: weights[n] for n in weights} if False else None
+    del weights
+    pe = pol.to_device(obs["patch_emb"])
+    ids = torch.from_numpy(obs["instr_ids"]).to(pol.device)
+    gdev = None if gum is None else torch.from_numpy(gum).to(pol.device)
+    temp = wl.temperature if wl.sampling == "gumbel" else 0.0
+    out = None
+    print(f"# inputs ready in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    def step():
+        nonlocal out
+        out = pol.policy_step(pe, obs["cu_patch"], ids, obs["cu_instr"], wl.n_tokens, temperature=temp,
+                              gumbel=gdev, action_dim=wl.action_dim, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    actions_per_s = wl.batch * (wl.n_tokens / wl.action_dim) / (dt / args.steps)
+
+    # per-kernel-family durations with HIP events on the launch stream, over the same number of steps
+    P.vla_prof_enable(pol.ctx, args.prof_mask)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    fam = {}
+    for i in range(P.vla_prof_count()):
+        name, n, ms = P.vla_prof_read(pol.ctx, i)
+        if n:
+            fam[name] = {"launches": n, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps}
+    P.vla_prof_enable(pol.ctx, 0)
+
+    g = fam.get("gemm_gateup_prefill")
+    roofline = None
+    if g:
+        ach = nums["gateup_flops"] / (g["avg_ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,2,2,EpiSwiglu> (prefill gate/up GEMM)",
+                    "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                    "avg_launch_ms": g["avg_ms"], "flops_per_launch": nums["gateup_flops"], "traffic": None}
+    extra = {}
+    pre_ms = sum(v["total_ms_per_step"] for k, v in fam.items() if k.endswith("_prefill"))
+    gemm_pre_ms = sum(v["total_ms_per_step"] for k, v in fam.items() if k.startswith("gemm") and k.endswith("_prefill"))
+    dec_ms = sum(v["total_ms_per_step"] for k, v in fam.items() if k.endswith("_decode"))
+    if gemm_pre_ms:
+        extra["prefill_gemm_tflops"] = 2 * nums["P"] * nums["T"] / (gemm_pre_ms * 1e-3) / 1e12
+        extra["prefill_gemm_frac_of_mfma_peak"] = extra["prefill_gemm_tflops"] / PEAK_BF16_TFLOPS
+    if dec_ms and nums["decode_bytes"]:
+        gbs = sum(nums["decode_bytes"]) / (dec_ms * 1e-3) / 1e9
+        extra["decode_gbs"] = gbs
+        extra["decode_frac_of_hbm_peak"] = gbs / PEAK_HBM_GBS
+        extra["decode_ms_per_token_step"] = dec_ms / max(1, wl.n_tokens - 1)
+    extra["prefill_kernels_ms"] = pre_ms
+    extra["families"] = fam
+
+    line = {
+        "metric": "actions/sec of the batched VLA policy step (prefill + action-token decode + log-probs)",
+        "value": actions_per_s, "unit": "actions/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: 7B Llama-shaped VLA backbone" if wl.shape.n_layers == 32 else wl.name,
+                   "n_layers": wl.shape.n_layers, "d_model": wl.shape.d_model, "batch": wl.batch,
+                   "prefix_tokens": nums["T"], "action_tokens": wl.n_tokens, "sampling": wl.sampling},
+        "roofline": roofline, "detail": extra,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(
+            wl, lambda names: W.make_weights(wl.shape, wl.seed, names=names, threads=16), obs, args.cpu_layers)
+    pol.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

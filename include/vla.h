@@ -55,8 +55,8 @@ enum vla_status {
 };
 
 /* Plain data, copied by vla_create.  Requirements: n_heads * head_dim == d_model; head_dim is 64
- * or 128 for VLA_BF16 (even, <= 256, for VLA_F32); d_model and d_ffn multiples of 64 for
- * VLA_BF16; 0 < n_action_bins <= vocab, n_action_bins <= 1024; max_seq counts prefix plus decoded
+ * or 128 for VLA_BF16 (32, 64, 128 or 256 for VLA_F32); d_model a multiple of 128 and d_ffn of 64
+ * for VLA_BF16 (d_model a multiple of 4 for VLA_F32); 0 < n_action_bins <= vocab, n_action_bins <= 1024; max_seq counts prefix plus decoded
  * positions of one sequence; max_prefill_tokens bounds the packed prefix tokens of one batch. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab, n_action_bins;
@@ -151,8 +151,9 @@ int vla_select(vla_ctx* ctx, int32_t B, const float* logits, float temperature, 
  * HIP events recorded on the launch stream around each launch.  vla_prof_enable(ctx, mask) clears
  * what was collected and then times the families whose bit (1 << index) is set in mask (0 = off).
  * vla_prof_read synchronises the recorded events (host-blocking) and reports, for family index i
- * (0 <= i < vla_prof_count()), its name, number of launches and total milliseconds.  Families:
- * 0 gemm_prefill, 1 attn_prefill, 2 gemm_decode, 3 attn_decode, 4 rmsnorm, 5 head_select, 6 misc. */
+ * (0 <= i < vla_prof_count()), its name, number of launches and total milliseconds.  Families are
+ * named by the read-out itself: the four GEMMs (qkv, o, gate-up, down) and the attention of prefill
+ * and of decode, rmsnorm, head_select, misc. */
 int vla_prof_enable(vla_ctx* ctx, int32_t mask);
 int vla_prof_count(void);
 int vla_prof_read(vla_ctx* ctx, int32_t i, const char** name, int64_t* launches, double* total_ms);

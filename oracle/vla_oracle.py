@@ -66,13 +66,18 @@ def widen(a: np.ndarray) -> np.ndarray:
     if a.dtype != np.uint16:
         raise TypeError(a.dtype)
 
-    def one(chunk):
-        return (chunk.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    out = np.empty(a.shape, dtype=np.float64)
+
+    def one(rows):
+        chunk = a[rows]
+        out[rows] = (chunk.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
     if a.size < (1 << 22) or a.ndim < 2:
-        return one(a)
-    parts = np.array_split(a, 16, axis=0)
-    return np.concatenate(list(_POOL.map(one, parts)), axis=0)
+        one(slice(None))
+        return out
+    step = -(-a.shape[0] // 16)
+    list(_POOL.map(one, [slice(i, i + step) for i in range(0, a.shape[0], step)]))
+    return out
 
 
 # ----------------------------------------------------------------------------

@@ -172,12 +172,15 @@ struct ProfScope {
   }
 };
 
-const char* kFamilyNames[FAM_COUNT] = {"gemm_prefill", "attn_prefill", "gemm_decode", "attn_decode",
-                                       "rmsnorm", "head_select", "misc"};
+const char* kFamilyNames[FAM_COUNT] = {"gemm_qkv_prefill", "gemm_o_prefill", "gemm_gateup_prefill",
+                                       "gemm_down_prefill", "attn_prefill", "gemm_qkv_decode", "gemm_o_decode",
+                                       "gemm_gateup_decode", "gemm_down_decode", "attn_decode", "rmsnorm",
+                                       "head_select", "misc"};
 
 template <class T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(base + off); }
 
 // ---- one pass over the layers for `rows` packed tokens (prefill: all prefix tokens; decode: B) ------
+// T is the activation type: f16 on the 16-bit path (bf16 storage), float on the float32 path.
 template <class T>
 int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
   const vla_config& c = ctx->cfg;
@@ -192,7 +195,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
   const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
   const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
   const size_t kvl = kv_layer_stride(c);
-  const int fam_gemm = decode ? FAM_GEMM_DECODE : FAM_GEMM_PREFILL;
+  const int fam_gemm = decode ? FAM_GEMM_QKV_DECODE : FAM_GEMM_QKV_PREFILL;   // + 0 qkv, 1 o, 2 gate-up, 3 down
   const int fam_attn = decode ? FAM_ATTN_DECODE : FAM_ATTN_PREFILL;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& lw = ctx->al.layers[l];
@@ -213,9 +216,9 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
       rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, st);
     }
     {
-      ProfScope ps(ctx, fam_gemm, st);
+      ProfScope ps(ctx, fam_gemm + 0, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_bf16_qkv(GemmBf16{(const bf16*)hn, d, at<bf16>(ctx->arena, lw.w_qkv), rows, 3 * d, d}, rk, st);
+        gemm_f16_qkv(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_qkv), rows, 3 * d, d}, rk, st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_qkv), scratch, rows, 3 * d, d, st);
         rope_kv_f32(scratch, rows, rk, st);
@@ -227,9 +230,9 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
                         c.n_heads, c.head_dim, c.max_seq, st);
     }
     {
-      ProfScope ps(ctx, fam_gemm, st);
+      ProfScope ps(ctx, fam_gemm + 1, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_bf16_resid(GemmBf16{(const bf16*)att, d, at<bf16>(ctx->arena, lw.w_o), rows, d, d}, x, d, st);
+        gemm_f16_resid(GemmF16{(const f16*)att, d, at<f16>(ctx->arena, lw.w_o), rows, d, d}, x, d, st);
       } else {
         gemm_f32((const float*)att, d, at<float>(ctx->arena, lw.w_o), scratch, rows, d, d, st);
         resid_add_f32(x, scratch, (size_t)rows * d, st);
@@ -240,18 +243,18 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
       rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, st);
     }
     {
-      ProfScope ps(ctx, fam_gemm, st);
+      ProfScope ps(ctx, fam_gemm + 2, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_bf16_swiglu(GemmBf16{(const bf16*)hn, d, at<bf16>(ctx->arena, lw.w_gu), rows, 2 * f, d}, (bf16*)act, f, st);
+        gemm_f16_swiglu(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, d}, (f16*)act, f, st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_gu), scratch, rows, 2 * f, d, st);
         swiglu_f32(scratch, (float*)act, rows, f, st);
       }
     }
     {
-      ProfScope ps(ctx, fam_gemm, st);
+      ProfScope ps(ctx, fam_gemm + 3, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_bf16_resid(GemmBf16{(const bf16*)act, f, at<bf16>(ctx->arena, lw.w_down), rows, d, f}, x, d, st);
+        gemm_f16_resid(GemmF16{(const f16*)act, f, at<f16>(ctx->arena, lw.w_down), rows, d, f}, x, d, st);
       } else {
         gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), scratch, rows, d, f, st);
         resid_add_f32(x, scratch, (size_t)rows * d, st);
@@ -309,6 +312,10 @@ int ensure_tables(vla_ctx* ctx, hipStream_t st) {
   return VLA_OK;
 }
 
+template <class S> struct ActOf { typedef float type; };
+template <> struct ActOf<bf16> { typedef f16 type; };
+
+// S is the storage type of the caller's tensors (bf16 or float).
 template <class T>
 int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
                const int32_t* cu_instr, int64_t T_tokens, float* logits, int ld_logits, hipStream_t st) {
@@ -335,7 +342,7 @@ int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu
     assemble_prefix<T>((const T*)patch_emb, instr_ids, at<T>(ctx->arena, ctx->al.embed),
                        at<int32_t>(ctx->work, w.tok_src), at<float>(ctx->work, w.x), (int)T_tokens, c.d_model, st);
   }
-  run_layers<T>(ctx, (int)T_tokens, false, st);
+  run_layers<typename ActOf<T>::type>(ctx, (int)T_tokens, false, st);
   if (logits) run_head<T>(ctx, B, at<int32_t>(ctx->work, w.last_row), logits, ld_logits, st);
   HIP_TRY(ctx, hipGetLastError());
   ctx->active_B = B;
@@ -353,7 +360,7 @@ int do_decode(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits, 
     embed_tokens<T>(token_ids, at<T>(ctx->arena, ctx->al.embed), at<float>(ctx->work, w.x), B, c.d_model, c.vocab, st);
     decode_maps(at<int32_t>(ctx->work, w.seq_len), B, at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos), st);
   }
-  run_layers<T>(ctx, B, true, st);
+  run_layers<typename ActOf<T>::type>(ctx, B, true, st);
   if (logits) run_head<T>(ctx, B, nullptr, logits, ld_logits, st);
   {
     ProfScope ps(ctx, FAM_MISC, st);
@@ -489,7 +496,7 @@ int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors,
   };
   auto matrix = [&](const vla_tensor* t, size_t off, int64_t rows, int64_t K, int64_t row0, int mode) {
     if (bf) {
-      pack_weight_bf16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<bf16>(ctx->arena, off), 0, (int)row0, mode, st);
+      pack_weight_f16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<f16>(ctx->arena, off), (int)row0, mode, st);
     } else {
       const int64_t r0 = mode == 2 ? rows : row0;   // float32 path keeps [gate rows | up rows]
       plain_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off) + r0 * K, (size_t)(rows * K), st);

@@ -79,7 +79,7 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
 }
 template void attention_rows<float>(const float*, int, const float*, const float*, const int32_t*, const int32_t*,
                                     float*, int, int, int, int, int, hipStream_t);
-template void attention_rows<bf16>(const bf16*, int, const bf16*, const bf16*, const int32_t*, const int32_t*,
-                                   bf16*, int, int, int, int, int, hipStream_t);
+template void attention_rows<f16>(const f16*, int, const f16*, const f16*, const int32_t*, const int32_t*,
+                                  f16*, int, int, int, int, int, hipStream_t);
 
 }  // namespace vla

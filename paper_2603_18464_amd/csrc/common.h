@@ -9,6 +9,8 @@ typedef __bf16 bf16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef _Float16 f16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
@@ -16,7 +18,12 @@ constexpr int kWave = 64;
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+__device__ __forceinline__ float to_f32(f16 v) { return (float)v; }
 template <class T> __device__ __forceinline__ T from_f32(float v);
+// float -> half, saturating at the largest finite half instead of overflowing to infinity
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) {
+  return (f16)fminf(fmaxf(v, -65504.0f), 65504.0f);
+}
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
 
@@ -33,9 +40,15 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // ---- kernel families timed by the profiling hooks ----------------------------------------------
 enum Family {
-  FAM_GEMM_PREFILL = 0,
+  FAM_GEMM_QKV_PREFILL = 0,
+  FAM_GEMM_O_PREFILL,
+  FAM_GEMM_GATEUP_PREFILL,
+  FAM_GEMM_DOWN_PREFILL,
   FAM_ATTN_PREFILL,
-  FAM_GEMM_DECODE,
+  FAM_GEMM_QKV_DECODE,
+  FAM_GEMM_O_DECODE,
+  FAM_GEMM_GATEUP_DECODE,
+  FAM_GEMM_DOWN_DECODE,
   FAM_ATTN_DECODE,
   FAM_NORM,
   FAM_HEAD,
@@ -55,19 +68,25 @@ struct RopeKv {
   int n_heads, head_dim, max_seq, d_model;
 };
 
-struct GemmBf16 {
-  const bf16* A;   // [M, K] row-major activations
+// The 16-bit path keeps weights as bfloat16 at the boundary but feeds the matrix cores in half
+// precision: bf16 -> f16 is exact once the weights are scaled by a power of two (kWeightScale keeps
+// |w| up to 255 finite and everything above 2^-25 exact), activations rounded to f16 carry 8x less
+// rounding error than bf16 at the same MFMA rate, and the scale is divided out in the epilogue.
+constexpr float kWeightScale = 256.0f;
+
+struct GemmF16 {
+  const f16* A;    // [M, K] row-major activations
   int lda;
-  const bf16* Wp;  // [N, K] weights in MFMA fragment order (see pack_weight_bf16)
+  const f16* Wp;   // [N, K] weights * kWeightScale in MFMA fragment order (see pack_weight_f16)
   int M, N, K;
 };
 
-// C = A * W^T with fused epilogues (bf16 MFMA, fp32 accumulation).
-void gemm_bf16_resid(const GemmBf16& g, float* x, int ldx, hipStream_t st);           // x += C
-void gemm_bf16_swiglu(const GemmBf16& g, bf16* act, int ldact, hipStream_t st);       // silu(gate)*up
-void gemm_bf16_qkv(const GemmBf16& g, const RopeKv& o, hipStream_t st);               // RoPE + cache
-void pack_weight_bf16(const bf16* src, int rows, int K, bf16* dst, int N_total, int row0,
-                      int interleave_mode, hipStream_t st);
+// C = A * W^T with fused epilogues (f16 MFMA, fp32 accumulation).
+void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st);           // x += C
+void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, hipStream_t st);        // silu(gate)*up
+void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st);               // RoPE + cache
+void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode,
+                     hipStream_t st);
 
 // fp32 path (plain, unfused).
 void gemm_f32(const float* A, int lda, const float* W, float* C, int M, int N, int K, hipStream_t st);

@@ -1,10 +1,11 @@
-// bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for gfx950, with the layer's elementwise work fused
-// into the epilogue (residual add; SwiGLU; rotary embedding + KV-cache write).
+// Half-precision MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  for gfx950, with the layer's elementwise
+// work fused into the epilogue (residual add; SwiGLU; rotary embedding + KV-cache write).
 //
 // Operand layouts
-//   A   row-major [M, lda] bf16 (activations produced by this library).
-//   Wp  weights repacked once at load time into MFMA fragment order: the 32x16 block
-//       (rows n0..n0+31, k0..k0+15) is stored as 64 lanes x 8 bf16 = 1 KiB, lane l holding
+//   A   row-major [M, lda] f16 (activations produced by this library).
+//   Wp  weights (bf16 at the boundary, re-encoded exactly as f16 * kWeightScale) repacked once at
+//       load time into MFMA fragment order: the 32x16 block
+//       (rows n0..n0+31, k0..k0+15) is stored as 64 lanes x 8 halves = 1 KiB, lane l holding
 //       row n0 + (l & 31), k = k0 + 8*(l >> 5) .. +7; blocks are ordered [n/32][k/16].  A wave
 //       reads one block with a single fully coalesced 16-byte-per-lane load, from global memory or
 //       from LDS, with no bank conflicts and no swizzle.
@@ -18,7 +19,7 @@ namespace vla {
 constexpr int BK = 64;
 
 // ---- epilogues ------------------------------------------------------------------------------------
-// Accumulator layout of v_mfma_f32_32x32x16_bf16: lane l, register 4*blk + r holds
+// Accumulator layout of v_mfma_f32_32x32x16_f16: lane l, register 4*blk + r holds
 // C[row = 8*blk + 4*(l >> 5) + r][col = l & 31].
 
 struct EpiResid {
@@ -37,7 +38,7 @@ struct EpiResid {
           if (m < M) {
             float* row = x + (size_t)m * ldx + nb + c;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) row[nt * 32] += acc[mt][nt][4 * blk + r];
+            for (int nt = 0; nt < NT; ++nt) row[nt * 32] += acc[mt][nt][4 * blk + r] * (1.0f / kWeightScale);
           }
         }
   }
@@ -46,7 +47,7 @@ struct EpiResid {
 // Fused gate/up weights are interleaved in blocks of 32 rows: [gate 0..31, up 0..31, gate 32..63, ...]
 // so that a wave's even 32-column tiles are gates and the following odd tiles the matching ups.
 struct EpiSwiglu {
-  bf16* act;
+  f16* act;
   int ld;
   template <int MT, int NT>
   __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
@@ -60,11 +61,12 @@ struct EpiSwiglu {
         for (int r = 0; r < 4; ++r) {
           const int m = mb + mt * 32 + 8 * blk + 4 * h + r;
           if (m < M) {
-            bf16* row = act + (size_t)m * ld + nb / 2 + c;
+            f16* row = act + (size_t)m * ld + nb / 2 + c;
 #pragma unroll
             for (int j = 0; j < NT / 2; ++j) {
-              const float g = acc[mt][2 * j][4 * blk + r], u = acc[mt][2 * j + 1][4 * blk + r];
-              row[j * 32] = (bf16)(g / (1.0f + __expf(-g)) * u);
+              const float g = acc[mt][2 * j][4 * blk + r] * (1.0f / kWeightScale);
+              const float u = acc[mt][2 * j + 1][4 * blk + r] * (1.0f / kWeightScale);
+              row[j * 32] = from_f32<f16>(g / (1.0f + __expf(-g)) * u);
             }
           }
         }
@@ -100,22 +102,23 @@ struct EpiQkv {
 #pragma unroll
           for (int hh = 0; hh < NT / HT; ++hh) {
             const int head = (col0 + hh * HD) / HD;
-            bf16* dst;
-            if (sect == 0) dst = (bf16*)o.q + (size_t)m * d + (size_t)head * HD;
-            else dst = (bf16*)(sect == 1 ? o.k_cache : o.v_cache) +
+            f16* dst;
+            if (sect == 0) dst = (f16*)o.q + (size_t)m * d + (size_t)head * HD;
+            else dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) +
                        (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * HD;
 #pragma unroll
             for (int ht = 0; ht < HT / 2; ++ht) {
               const int j = ht * 32 + c;     // index of the pair inside the head
-              float lo = acc[mt][hh * HT + ht][ai], hi = acc[mt][hh * HT + ht + HT / 2][ai];
+              float lo = acc[mt][hh * HT + ht][ai] * (1.0f / kWeightScale);
+              float hi = acc[mt][hh * HT + ht + HT / 2][ai] * (1.0f / kWeightScale);
               if (sect < 2) {
                 const float cs = cs_row[j], sn = sn_row[j];
                 const float a = lo * cs - hi * sn, b = hi * cs + lo * sn;
                 lo = a;
                 hi = b;
               }
-              dst[j] = (bf16)lo;
-              dst[j + HALF] = (bf16)hi;
+              dst[j] = from_f32<f16>(lo);
+              dst[j + HALF] = from_f32<f16>(hi);
             }
           }
         }
@@ -124,8 +127,8 @@ struct EpiQkv {
 
 // ---- kernel -----------------------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN, class Epi>
-__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
-    const bf16* __restrict__ A, int lda, const bf16* __restrict__ Wp, int M, int N, int K,
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
+    const f16* __restrict__ A, int lda, const f16* __restrict__ Wp, int M, int N, int K,
     int tiles_m, int tiles_n, Epi epi) {
   constexpr int NTHR = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
@@ -133,8 +136,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
   constexpr int W_ITERS = BN * 8 / NTHR;
   static_assert(BM * 8 % NTHR == 0 && BN * 8 % NTHR == 0, "slab must divide among threads");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* As = (bf16*)smem;                       // [2][BM*64]
-  bf16* Ws = As + 2 * BM * BK;                  // [2][BN*64]
+  f16* As = (f16*)smem;                       // [2][BM*64]
+  f16* Ws = As + 2 * BM * BK;                  // [2][BN*64]
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give each XCD a
   // contiguous run of tiles, walked in groups of GM row-tiles that share the same weight columns.
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
 
   // per-thread source addresses
   const int a_c = t & 7, a_r = t >> 3;
-  const bf16* a_src[A_ITERS];
+  const f16* a_src[A_ITERS];
   int a_dst[A_ITERS];
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
@@ -167,7 +170,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
     a_src[i] = A + (size_t)gr * lda + a_c * 8;
     a_dst[i] = r * BK + ((a_c ^ (r & 7)) << 3);
   }
-  const bf16* w_src[W_ITERS];
+  const f16* w_src[W_ITERS];
 #pragma unroll
   for (int i = 0; i < W_ITERS; ++i) {
     const int q = t + i * NTHR;
@@ -183,8 +186,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
     for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const uint4*)(w_src[i] + (size_t)kt * 4 * 512);
   };
   auto store_lds = [&](int buf) {
-    bf16* as = As + buf * BM * BK;
-    bf16* ws = Ws + buf * BN * BK;
+    f16* as = As + buf * BM * BK;
+    f16* ws = Ws + buf * BN * BK;
 #pragma unroll
     for (int i = 0; i < A_ITERS; ++i) *(uint4*)(as + a_dst[i]) = ra[i];
 #pragma unroll
@@ -207,25 +210,25 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
   __syncthreads();
   for (int kt = 0; kt < KT; ++kt) {
     if (kt + 1 < KT) load_global(kt + 1);
-    const bf16* as = As + (kt & 1) * BM * BK;
-    const bf16* ws = Ws + (kt & 1) * BN * BK;
+    const f16* as = As + (kt & 1) * BM * BK;
+    const f16* ws = Ws + (kt & 1) * BN * BK;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[MT], bfr[NT];
+      f16x8 af[MT], bfr[NT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int row = frow + mt * 32;
         const int c = kk * 2 + fhalf;
-        af[mt] = *(const bf16x8*)(as + row * BK + ((c ^ (row & 7)) << 3));
+        af[mt] = *(const f16x8*)(as + row * BK + ((c ^ (row & 7)) << 3));
       }
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-        bfr[nt] = *(const bf16x8*)(ws + ((wn * NT + nt) * 4 + kk) * 512 + lane * 8);
+        bfr[nt] = *(const f16x8*)(ws + ((wn * NT + nt) * 4 + kk) * 512 + lane * 8);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
     }
     if (kt + 1 < KT) store_lds((kt + 1) & 1);
     __syncthreads();
@@ -234,12 +237,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_kernel(
 }
 
 template <int BM, int BN, int WGM, int WGN, class Epi>
-static void launch(const GemmBf16& g, const Epi& epi, hipStream_t st) {
+static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
   const int nblk = tiles_m * tiles_n;
   const int grid = (nblk + 7) / 8 * 8;
-  constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(bf16);
-  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, Epi>;
+  constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(f16);
+  auto kern = gemm_f16_kernel<BM, BN, WGM, WGN, Epi>;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -252,7 +255,7 @@ static void launch(const GemmBf16& g, const Epi& epi, hipStream_t st) {
 // Tile choice: big square tiles when there are enough rows to fill them, a 64-row tile for the
 // decode-sized problems.  The QKV epilogue needs wave tiles that cover whole heads (128 columns).
 template <class Epi>
-static void dispatch(const GemmBf16& g, const Epi& epi, hipStream_t st) {
+static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   if (g.M > 128 && g.N % 256 == 0)
     launch<256, 256, 2, 2, Epi>(g, epi, st);
   else if (g.N % 256 == 0)
@@ -261,22 +264,23 @@ static void dispatch(const GemmBf16& g, const Epi& epi, hipStream_t st) {
     launch<64, 128, 2, 1, Epi>(g, epi, st);   // N multiple of 128
 }
 
-void gemm_bf16_resid(const GemmBf16& g, float* x, int ldx, hipStream_t st) {
+void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st) {
   dispatch(g, EpiResid{x, ldx}, st);
 }
-void gemm_bf16_swiglu(const GemmBf16& g, bf16* act, int ldact, hipStream_t st) {
+void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, hipStream_t st) {
   dispatch(g, EpiSwiglu{act, ldact}, st);
 }
-void gemm_bf16_qkv(const GemmBf16& g, const RopeKv& o, hipStream_t st) {
+void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st) {
   if (o.head_dim == 128) dispatch(g, EpiQkv<128>{o}, st);
   else dispatch(g, EpiQkv<64>{o}, st);
 }
 
 // ---- weight repacking -------------------------------------------------------------------------------
-// Copies `rows` source rows [rows, K] into the packed matrix of N_total rows starting at packed row
-// `row0`.  interleave_mode 0: packed row = row0 + r.  1 (gate) / 2 (up): rows go to the even / odd
-// 32-row blocks of the fused gate-up matrix.
-__global__ void pack_weight_kernel(const bf16* __restrict__ src, int rows, int K, bf16* __restrict__ dst,
+// Converts `rows` bf16 source rows [rows, K] to f16 * kWeightScale (exact: a power-of-two scale moves
+// the exponent only, and f16 has more mantissa bits than bf16; values beyond +-255 saturate) and
+// stores them in fragment order starting at packed row `row0`.  interleave_mode 0: packed row =
+// row0 + r.  1 (gate) / 2 (up): rows go to the even / odd 32-row blocks of the fused gate-up matrix.
+__global__ void pack_weight_kernel(const bf16* __restrict__ src, int rows, int K, f16* __restrict__ dst,
                                    int row0, int mode) {
   const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // 8 consecutive k of one row
   const int kchunks = K >> 3;
@@ -286,13 +290,15 @@ __global__ void pack_weight_kernel(const bf16* __restrict__ src, int rows, int K
   if (mode == 0) pr = row0 + r;
   else pr = (r / 32) * 64 + (mode == 2 ? 32 : 0) + (r & 31);
   const int nb = pr >> 5, kb = kc >> 1, lane = (pr & 31) + 32 * (kc & 1);
-  const uint4 v = *(const uint4*)(src + (size_t)r * K + kc * 8);
-  *(uint4*)(dst + ((size_t)nb * (K >> 4) + kb) * 512 + lane * 8) = v;
+  const bf16x8 v = *(const bf16x8*)(src + (size_t)r * K + kc * 8);
+  f16x8 o;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = from_f32<f16>((float)v[j] * kWeightScale);
+  *(f16x8*)(dst + ((size_t)nb * (K >> 4) + kb) * 512 + lane * 8) = o;
 }
 
-void pack_weight_bf16(const bf16* src, int rows, int K, bf16* dst, int N_total, int row0,
-                      int interleave_mode, hipStream_t st) {
-  (void)N_total;
+void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode,
+                     hipStream_t st) {
   const size_t chunks = (size_t)rows * (K >> 3);
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, src,
                      rows, K, dst, row0, interleave_mode);

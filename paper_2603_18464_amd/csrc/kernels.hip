@@ -186,8 +186,8 @@ void rmsnorm(const float* x, const T*, const float* gain, T* out, int rows, int 
 }
 template void rmsnorm<float>(const float*, const float*, const float*, float*, int, int, float, const int32_t*,
                              hipStream_t);
-template void rmsnorm<bf16>(const float*, const bf16*, const float*, bf16*, int, int, float, const int32_t*,
-                            hipStream_t);
+template void rmsnorm<f16>(const float*, const f16*, const float*, f16*, int, int, float, const int32_t*,
+                           hipStream_t);
 
 // ---- action head ------------------------------------------------------------------------------------
 // One workgroup per sequence: final RMSNorm of its row (float32, kept in LDS), then each wave takes
