@@ -159,40 +159,21 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
   const int wm = wave / WGN, wn = wave % WGN;
   const int KB16 = K >> 4, KT = K / BK;
 
-  // per-thread source addresses
+  // Global -> register -> LDS staging.  Thread t moves 16-byte chunks: chunk (t & 7) of rows
+  // (t >> 3) + i * NTHR/8 of the A slab (XOR-swizzled on the way into LDS), and the linear chunks
+  // t + i * NTHR of the weight slab (fragment order needs no swizzle).
   const int a_c = t & 7, a_r = t >> 3;
-  const f16* a_src[A_ITERS];
-  int a_dst[A_ITERS];
+  const f16* a_ptr[A_ITERS];
 #pragma unroll
-  for (int i = 0; i < A_ITERS; ++i) {
-    const int r = a_r + i * (NTHR / 8);
-    const int gr = min(m0 + r, M - 1);
-    a_src[i] = A + (size_t)gr * lda + a_c * 8;
-    a_dst[i] = r * BK + ((a_c ^ (r & 7)) << 3);
-  }
-  const f16* w_src[W_ITERS];
+  for (int i = 0; i < A_ITERS; ++i)
+    a_ptr[i] = A + (size_t)min(m0 + a_r + i * (NTHR / 8), M - 1) * lda + a_c * 8;
+  const int a_dst = a_r * BK + ((a_c ^ (a_r & 7)) << 3);      // rows advance by multiples of 8: same swizzle
+  const f16* w_ptr[W_ITERS];
 #pragma unroll
   for (int i = 0; i < W_ITERS; ++i) {
     const int q = t + i * NTHR;
-    const int nb = q >> 8, off = q & 255;
-    w_src[i] = Wp + ((size_t)(n0 / 32 + nb) * KB16) * 512 + off * 8;
+    w_ptr[i] = Wp + ((size_t)(n0 / 32 + (q >> 8)) * KB16) * 512 + (q & 255) * 8;
   }
-
-  uint4 ra[A_ITERS], rw[W_ITERS];
-  auto load_global = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const uint4*)(a_src[i] + kt * BK);
-#pragma unroll
-    for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const uint4*)(w_src[i] + (size_t)kt * 4 * 512);
-  };
-  auto store_lds = [&](int buf) {
-    f16* as = As + buf * BM * BK;
-    f16* ws = Ws + buf * BN * BK;
-#pragma unroll
-    for (int i = 0; i < A_ITERS; ++i) *(uint4*)(as + a_dst[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < W_ITERS; ++i) *(uint4*)(ws + (t + i * NTHR) * 8) = rw[i];
-  };
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -202,35 +183,63 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+  // fragment addresses inside a slab (elements)
   const int frow = wm * WTM + (lane & 31);
   const int fhalf = lane >> 5;
+  int a_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) a_off[kk] = frow * BK + (((kk * 2 + fhalf) ^ (frow & 7)) << 3);
+  const int w_off = wn * NT * 4 * 512 + lane * 8;
 
-  load_global(0);
-  store_lds(0);
+  u32x4 ra[A_ITERS], rw[W_ITERS];
+#pragma unroll
+  for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const u32x4*)(a_ptr[i]);
+#pragma unroll
+  for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const u32x4*)(w_ptr[i]);
+#pragma unroll
+  for (int i = 0; i < A_ITERS; ++i) *(u32x4*)(As + a_dst + i * (NTHR / 8) * BK) = ra[i];
+#pragma unroll
+  for (int i = 0; i < W_ITERS; ++i) *(u32x4*)(Ws + (t + i * NTHR) * 8) = rw[i];
   __syncthreads();
+
   for (int kt = 0; kt < KT; ++kt) {
-    if (kt + 1 < KT) load_global(kt + 1);
+    const bool more = kt + 1 < KT;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const u32x4*)(a_ptr[i] + (kt + 1) * BK);
+#pragma unroll
+      for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const u32x4*)(w_ptr[i] + (size_t)(kt + 1) * 4 * 512);
+    }
     const f16* as = As + (kt & 1) * BM * BK;
-    const f16* ws = Ws + (kt & 1) * BN * BK;
+    const f16* ws = Ws + (kt & 1) * BN * BK + w_off;
+    f16x8 af[2][MT], bfr[2][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) af[0][mt] = *(const f16x8*)(as + a_off[0] + mt * 32 * BK);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) bfr[0][nt] = *(const f16x8*)(ws + nt * 4 * 512);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      f16x8 af[MT], bfr[NT];
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < 4) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int row = frow + mt * 32;
-        const int c = kk * 2 + fhalf;
-        af[mt] = *(const f16x8*)(as + row * BK + ((c ^ (row & 7)) << 3));
+        for (int mt = 0; mt < MT; ++mt) af[nxt][mt] = *(const f16x8*)(as + a_off[kk + 1] + mt * 32 * BK);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bfr[nxt][nt] = *(const f16x8*)(ws + (nt * 4 + kk + 1) * 512);
       }
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        bfr[nt] = *(const f16x8*)(ws + ((wn * NT + nt) * 4 + kk) * 512 + lane * 8);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][mt], bfr[cur][nt], acc[mt][nt], 0, 0, 0);
     }
-    if (kt + 1 < KT) store_lds((kt + 1) & 1);
+    if (more) {
+      f16* asn = As + ((kt + 1) & 1) * BM * BK;
+      f16* wsn = Ws + ((kt + 1) & 1) * BN * BK;
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i) *(u32x4*)(asn + a_dst + i * (NTHR / 8) * BK) = ra[i];
+#pragma unroll
+      for (int i = 0; i < W_ITERS; ++i) *(u32x4*)(wsn + (t + i * NTHR) * 8) = rw[i];
+    }
     __syncthreads();
   }
   epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
