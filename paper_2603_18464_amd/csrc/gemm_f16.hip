@@ -10,7 +10,7 @@
 //       reads one block with a single fully coalesced 16-byte-per-lane load, from global memory or
 //       from LDS, with no bank conflicts and no swizzle.
 // The kernel keeps a BM x 64 slab of A (XOR-swizzled 16-byte chunks) and a BN x 64 slab of Wp in
-// LDS, double buffered, and each of the 4 waves owns a (BM/WGM) x (BN/WGN) accumulator tile made
+// LDS, double buffered, and each of the WGM x WGN waves owns a (BM/WGM) x (BN/WGN) accumulator tile made
 // of 32x32x16 MFMAs.
 #include "common.h"
 
@@ -203,13 +203,14 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
   __syncthreads();
 
   for (int kt = 0; kt < KT; ++kt) {
-    const bool more = kt + 1 < KT;
-    if (more) {
+    // Prefetch the next slab into registers (the last iteration re-reads its own slab: harmless, and
+    // it keeps the loop body one straight-line block that the scheduler can interleave freely).
+    const int kn = min(kt + 1, KT - 1);
 #pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const u32x4*)(a_ptr[i] + (kt + 1) * BK);
+    for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const u32x4*)(a_ptr[i] + kn * BK);
 #pragma unroll
-      for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const u32x4*)(w_ptr[i] + (size_t)(kt + 1) * 4 * 512);
-    }
+    for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const u32x4*)(w_ptr[i] + (size_t)kn * 4 * 512);
+    __builtin_amdgcn_sched_barrier(0);   // keep the prefetch at the top: its latency hides under the MFMAs
     const f16* as = As + (kt & 1) * BM * BK;
     const f16* ws = Ws + (kt & 1) * BN * BK + w_off;
     f16x8 af[2][MT], bfr[2][NT];
@@ -231,15 +232,22 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
           acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][mt], bfr[cur][nt], acc[mt][nt], 0, 0, 0);
-    }
-    if (more) {
-      f16* asn = As + ((kt + 1) & 1) * BM * BK;
-      f16* wsn = Ws + ((kt + 1) & 1) * BN * BK;
+      // Scheduling hint: spread the LDS reads of the next k-step between the MFMAs of this one.
+      if (kk + 1 < 4) {
 #pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) *(u32x4*)(asn + a_dst + i * (NTHR / 8) * BK) = ra[i];
-#pragma unroll
-      for (int i = 0; i < W_ITERS; ++i) *(u32x4*)(wsn + (t + i * NTHR) * 8) = rw[i];
+        for (int i = 0; i < MT + NT; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, (MT * NT) / (MT + NT), 0);   // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                       // DS read
+        }
+      }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    f16* asn = As + ((kt + 1) & 1) * BM * BK;
+    f16* wsn = Ws + ((kt + 1) & 1) * BN * BK;
+#pragma unroll
+    for (int i = 0; i < A_ITERS; ++i) *(u32x4*)(asn + a_dst + i * (NTHR / 8) * BK) = ra[i];
+#pragma unroll
+    for (int i = 0; i < W_ITERS; ++i) *(u32x4*)(wsn + (t + i * NTHR) * 8) = rw[i];
     __syncthreads();
   }
   epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
@@ -266,7 +274,7 @@ static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
 template <class Epi>
 static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   if (g.M > 128 && g.N % 256 == 0)
-    launch<256, 256, 2, 2, Epi>(g, epi, st);
+    launch<256, 256, 4, 2, Epi>(g, epi, st);
   else if (g.N % 256 == 0)
     launch<64, 256, 2, 2, Epi>(g, epi, st);
   else
