@@ -122,6 +122,7 @@ struct vla_ctx {
   char* work = nullptr;
   bool bound = false, weights = false, tables = false;
   int active_B = 0;                  // batch of the last prefill (0: none)
+  int run_B = 0, run_max_len = 0;    // batch and longest prefix of the prefill being enqueued
   std::vector<int32_t> len;          // host copy of the sequence lengths
   std::string err;
   // pinned staging ring for the host offset arrays
@@ -226,8 +227,18 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
     }
     {
       ProfScope ps(ctx, fam_attn, st);
-      attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
-                        c.n_heads, c.head_dim, c.max_seq, st);
+      if constexpr (sizeof(T) == 2) {
+        if (!decode)
+          flash_prefill((const f16*)q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache,
+                        at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), (f16*)att, d,
+                        ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim, c.max_seq, st);
+        else
+          attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
+                            c.n_heads, c.head_dim, c.max_seq, st);
+      } else {
+        attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
+                          c.n_heads, c.head_dim, c.max_seq, st);
+      }
     }
     {
       ProfScope ps(ctx, fam_gemm + 1, st);
@@ -341,6 +352,12 @@ int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu
                      at<int32_t>(ctx->work, w.seq_len), st);
     assemble_prefix<T>((const T*)patch_emb, instr_ids, at<T>(ctx->arena, ctx->al.embed),
                        at<int32_t>(ctx->work, w.tok_src), at<float>(ctx->work, w.x), (int)T_tokens, c.d_model, st);
+  }
+  ctx->run_B = B;
+  ctx->run_max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    const int S = (cu_patch[b + 1] - cu_patch[b]) + (cu_instr[b + 1] - cu_instr[b]);
+    if (S > ctx->run_max_len) ctx->run_max_len = S;
   }
   run_layers<typename ActOf<T>::type>(ctx, (int)T_tokens, false, st);
   if (logits) run_head<T>(ctx, B, at<int32_t>(ctx->work, w.last_row), logits, ld_logits, st);

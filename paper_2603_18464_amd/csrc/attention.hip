@@ -56,6 +56,177 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
   }
 }
 
+// ---- prefill: causal flash attention on the matrix cores --------------------------------------------
+// One workgroup = 4 waves = 128 consecutive query positions of one (sequence, head); each wave owns
+// 32 queries.  Keys/values are walked in tiles of 64 positions staged in LDS.
+//   S^T = K Q^T  : A operand = K rows (key-major, straight from the cache layout, XOR-swizzled 16-byte
+//                  chunks in LDS), B operand = the wave's Q rows kept in registers.  In the 32x32
+//                  accumulator layout every lane then owns ONE query (column l & 31) and 16 of the 32
+//                  keys of a sub-tile, so the softmax statistics are per-lane scalars plus one exchange
+//                  with lane ^ 32.
+//   O^T += V^T P^T: B operand = P^T taken directly from the S^T accumulators (the contraction index
+//                  may be permuted freely as long as both operands agree), A operand = V^T read from an
+//                  LDS tile that was transposed while staging, with the key order inside each group of
+//                  16 arranged so that a lane's 8 keys are contiguous.
+template <int HD>
+__global__ __launch_bounds__(256) void flash_prefill_kernel(
+    const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
+    const int32_t* __restrict__ cu_patch, const int32_t* __restrict__ cu_instr, f16* __restrict__ out, int ldo,
+    int n_heads, int max_seq) {
+  constexpr int KS = HD / 16;          // k-steps of the QK^T contraction
+  constexpr int DT = HD / 32;          // 32-row tiles of O^T
+  constexpr int KCH = HD / 8;          // 16-byte chunks per key row
+  constexpr int VPITCH = 64 + 8;       // halves per V^T row (padding keeps b128 reads conflict free)
+  __shared__ __attribute__((aligned(16))) f16 Ks[64 * HD];
+  __shared__ __attribute__((aligned(16))) f16 Vt[HD * VPITCH];
+
+  const int b = blockIdx.y, head = blockIdx.z;
+  const int row0 = cu_patch[b] + cu_instr[b];
+  const int S = cu_patch[b + 1] + cu_instr[b + 1] - row0;
+  const int q0 = blockIdx.x * 128;
+  if (q0 >= S) return;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int qpos = q0 + wave * 32 + col;                 // this lane's query position
+  const int qrow = row0 + min(qpos, S - 1);               // clamped: rows past the end are never stored
+  const f16* kbase = k_cache + ((size_t)b * n_heads + head) * max_seq * HD;
+  const f16* vbase = v_cache + ((size_t)b * n_heads + head) * max_seq * HD;
+
+  f16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    qf[ks] = *(const f16x8*)(q + (size_t)qrow * ldq + head * HD + ks * 16 + half * 8);
+
+  f32x16 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float scale = rsqrtf((float)HD);
+
+  const int kend = min(S, q0 + 128);                      // keys needed by this workgroup
+  const int wave_last = q0 + wave * 32 + 31;              // last query position of this wave
+  for (int k0 = 0; k0 < kend; k0 += 64) {
+    __syncthreads();                                      // previous tile fully consumed
+    // K tile: 64 keys x KCH chunks, chunk c of key kk stored at slot c ^ (kk & 7) (low 3 bits)
+#pragma unroll
+    for (int i = 0; i < 64 * KCH / 256; ++i) {
+      const int item = t + 256 * i;
+      const int c = item % KCH, kk = item / KCH;
+      const int kp = min(k0 + kk, S - 1);
+      const u32x4 v = *(const u32x4*)(kbase + (size_t)kp * HD + c * 8);
+      *(u32x4*)(Ks + kk * HD + ((c ^ (kk & 7)) << 3)) = v;
+    }
+    // V tile, transposed: Vt[dim][pos(key)], two keys per 32-bit store
+#pragma unroll
+    for (int i = 0; i < 32 * KCH / 256; ++i) {
+      const int item = t + 256 * i;
+      const int u = item & 31, c = item >> 5;
+      const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
+      const f16x8 va = *(const f16x8*)(vbase + (size_t)ka * HD + c * 8);
+      const f16x8 vb = *(const f16x8*)(vbase + (size_t)kb * HD + c * 8);
+      const int g = (2 * u) & 15;                         // position of the key inside its group of 16
+      const int pos = ((2 * u) & ~15) + ((g >> 2) & 1) * 8 + (g >> 3) * 4 + (g & 3);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+        f16x2 pr;
+        pr[0] = va[j];
+        pr[1] = vb[j];
+        *(f16x2*)(Vt + (c * 8 + j) * VPITCH + pos) = pr;
+      }
+    }
+    __syncthreads();
+    if (k0 > wave_last) continue;                         // tile entirely above this wave's diagonal
+
+    // S^T for the two 32-key sub-tiles
+    f32x16 sacc[2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[st][e] = 0.f;
+      const int kk = st * 32 + col;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const f16x8 kf = *(const f16x8*)(Ks + kk * HD + (((ks * 2 + half) ^ (kk & 7)) << 3));
+        sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ks], sacc[st], 0, 0, 0);
+      }
+    }
+    // mask, running max
+    float m_tile = -INFINITY;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kp = k0 + st * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+        const float v = (kp <= qpos && kp < S) ? sacc[st][e] * scale : -INFINITY;
+        sacc[st][e] = v;
+        m_tile = fmaxf(m_tile, v);
+      }
+    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+    const float m_new = fmaxf(m_run, m_tile);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;  // fully masked so far: keep everything at zero
+    const float alpha = __expf(m_run - m_use);              // exp(-inf) = 0 on the first live tile
+    float l_tile = 0.f;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = __expf(sacc[st][e] - m_use);
+        sacc[st][e] = p;
+        l_tile += p;
+      }
+    l_tile += __shfl_xor(l_tile, 32, 64);
+    l_run = l_run * alpha + l_tile;
+    m_run = m_new;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+    // O^T += V^T P^T
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int ip = 0; ip < 2; ++ip) {
+        f16x8 pf;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) pf[j] = (f16)sacc[st][8 * ip + j];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const f16x8 vf = *(const f16x8*)(Vt + (dt * 32 + col) * VPITCH + st * 32 + ip * 16 + half * 8);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[dt], 0, 0, 0);
+        }
+      }
+  }
+  if (qpos < S) {
+    const float inv = 1.0f / l_run;
+    f16* orow = out + (size_t)(row0 + qpos) * ldo + head * HD;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+        f16x4 w;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w[r] = from_f32<f16>(o[dt][4 * i + r] * inv);
+        *(f16x4*)(orow + dt * 32 + 8 * i + 4 * half) = w;
+      }
+  }
+}
+
+void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* cu_patch,
+                   const int32_t* cu_instr, f16* out, int ldo, int B, int max_len, int n_heads, int head_dim,
+                   int max_seq, hipStream_t st) {
+  const dim3 grid((max_len + 127) / 128, B, n_heads);
+  if (head_dim == 128)
+    hipLaunchKernelGGL(flash_prefill_kernel<128>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, cu_patch,
+                       cu_instr, out, ldo, n_heads, max_seq);
+  else
+    hipLaunchKernelGGL(flash_prefill_kernel<64>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, cu_patch,
+                       cu_instr, out, ldo, n_heads, max_seq);
+}
+
 template <class T>
 void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, const int32_t* tok_seq,
                     const int32_t* tok_pos, T* out, int ldo, int n_tok, int n_heads, int head_dim, int max_seq,

@@ -111,6 +111,12 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
                     const int32_t* tok_pos, T* out, int ldo, int n_tok, int n_heads, int head_dim,
                     int max_seq, hipStream_t st);
 
+// Prefill attention for the 16-bit path: causal flash attention over whole prefixes (MFMA).
+// cu_patch / cu_instr are the device copies of the cumulative offsets; max_len = longest prefix.
+void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* cu_patch,
+                   const int32_t* cu_instr, f16* out, int ldo, int B, int max_len, int n_heads, int head_dim,
+                   int max_seq, hipStream_t st);
+
 // Action head: final RMSNorm + action rows of the LM head -> logits [B, A] float32.
 template <class T>
 void head_logits(const float* x, const int32_t* row_index, const float* gain, const T* w_head,
