@@ -27,7 +27,7 @@ struct ArenaLayout {
   std::vector<LayerW> layers;
 };
 struct WorkLayout {
-  size_t x, hn, q, att, act, scratch, rope_cos, rope_sin, tok_seq, tok_pos, tok_src, last_row, seq_len,
+  size_t x, hn, q, att, act, scratch, part, rope_cos, rope_sin, tok_seq, tok_pos, tok_src, last_row, seq_len,
       cu_patch, cu_instr, cur_ids, logits, total;
 };
 
@@ -60,8 +60,10 @@ size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one l
 size_t kv_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
 
 size_t max_rows(const vla_config& c) {
-  return (size_t)(c.max_prefill_tokens > c.max_batch ? c.max_prefill_tokens : c.max_batch);
+  const size_t b32 = ((size_t)c.max_batch + 31) / 32 * 32;   // fragment-order activations come in 32-row blocks
+  return (size_t)c.max_prefill_tokens > b32 ? (size_t)c.max_prefill_tokens : b32;
 }
+constexpr int kSkinnyMaxRows = 128;   // decode batches up to this many rows use the weight-streaming GEMMs
 
 WorkLayout work_layout(const vla_config& c) {
   WorkLayout w;
@@ -75,6 +77,8 @@ WorkLayout work_layout(const vla_config& c) {
   w.act = take(T * f * es);
   const size_t widest = 3 * d > 2 * f ? 3 * d : 2 * f;
   w.scratch = take(c.dtype == VLA_F32 ? T * widest * 4 : 0);
+  const size_t part_rows = B < (size_t)kSkinnyMaxRows ? B : (size_t)kSkinnyMaxRows;
+  w.part = take(c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * part_rows * widest * 4 : 0);
   w.rope_cos = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
   w.rope_sin = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
   w.tok_seq = take(T * 4);
@@ -234,10 +238,10 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
                         ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim, c.max_seq, st);
         else
           attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
-                            c.n_heads, c.head_dim, c.max_seq, st);
+                            c.n_heads, c.head_dim, c.max_seq, false, st);
       } else {
         attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
-                          c.n_heads, c.head_dim, c.max_seq, st);
+                          c.n_heads, c.head_dim, c.max_seq, false, st);
       }
     }
     {
@@ -270,6 +274,71 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
         gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), scratch, rows, d, f, st);
         resid_add_f32(x, scratch, (size_t)rows * d, st);
       }
+    }
+  }
+  return VLA_OK;
+}
+
+// Decode step of the 16-bit path for batches of at most kSkinnyMaxRows rows: weight-streaming split-K
+// GEMMs, each followed by the kernel that sums the K slices and applies the elementwise step.
+int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
+  const vla_config& c = ctx->cfg;
+  const WorkLayout& w = ctx->wl;
+  const int d = c.d_model, f = c.d_ffn;
+  float* x = at<float>(ctx->work, w.x);
+  f16* hn = at<f16>(ctx->work, w.hn);
+  f16* q = at<f16>(ctx->work, w.q);
+  f16* att = at<f16>(ctx->work, w.att);
+  f16* act = at<f16>(ctx->work, w.act);
+  float* part = at<float>(ctx->work, w.part);
+  const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
+  const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
+  const size_t kvl = kv_layer_stride(c);
+  const int ks_qkv = skinny_ksplit(3 * d, d), ks_o = skinny_ksplit(d, d), ks_gu = skinny_ksplit(2 * f, d),
+            ks_dn = skinny_ksplit(d, f);
+  {
+    ProfScope ps(ctx, FAM_NORM, st);
+    rmsnorm_frag(x, B, d, at<float>(ctx->arena, ctx->al.layers[0].g_attn), c.rms_eps, hn, st);
+  }
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW& lw = ctx->al.layers[l];
+    RopeKv rk;
+    rk.q = q;
+    rk.k_cache = at<f16>(ctx->kv, 0) + (size_t)(2 * l) * kvl;
+    rk.v_cache = at<f16>(ctx->kv, 0) + (size_t)(2 * l + 1) * kvl;
+    rk.tok_seq = tok_seq;
+    rk.tok_pos = tok_pos;
+    rk.rope_cos = at<float>(ctx->work, w.rope_cos);
+    rk.rope_sin = at<float>(ctx->work, w.rope_sin);
+    rk.n_heads = c.n_heads;
+    rk.head_dim = c.head_dim;
+    rk.max_seq = c.max_seq;
+    rk.d_model = d;
+    {
+      ProfScope ps(ctx, FAM_GEMM_QKV_DECODE, st);
+      skinny_gemm(hn, at<f16>(ctx->arena, lw.w_qkv), part, B, 3 * d, d, ks_qkv, st);
+      reduce_qkv_rope(part, skinny_effective_ksplit(d, ks_qkv), B, rk, st);
+    }
+    {
+      ProfScope ps(ctx, FAM_ATTN_DECODE, st);
+      attention_rows<f16>(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, d, B,
+                          c.n_heads, c.head_dim, c.max_seq, true, st);
+    }
+    {
+      ProfScope ps(ctx, FAM_GEMM_O_DECODE, st);
+      skinny_gemm(att, at<f16>(ctx->arena, lw.w_o), part, B, d, d, ks_o, st);
+      reduce_resid_norm(part, skinny_effective_ksplit(d, ks_o), B, d, x, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, st);
+    }
+    {
+      ProfScope ps(ctx, FAM_GEMM_GATEUP_DECODE, st);
+      skinny_gemm(hn, at<f16>(ctx->arena, lw.w_gu), part, B, 2 * f, d, ks_gu, st);
+      reduce_swiglu(part, skinny_effective_ksplit(d, ks_gu), B, f, act, st);
+    }
+    {
+      ProfScope ps(ctx, FAM_GEMM_DOWN_DECODE, st);
+      skinny_gemm(act, at<f16>(ctx->arena, lw.w_down), part, B, d, f, ks_dn, st);
+      const float* next_gain = l + 1 < c.n_layers ? at<float>(ctx->arena, ctx->al.layers[l + 1].g_attn) : nullptr;
+      reduce_resid_norm(part, skinny_effective_ksplit(f, ks_dn), B, d, x, next_gain, c.rms_eps, hn, st);
     }
   }
   return VLA_OK;
@@ -377,7 +446,8 @@ int do_decode(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits, 
     embed_tokens<T>(token_ids, at<T>(ctx->arena, ctx->al.embed), at<float>(ctx->work, w.x), B, c.d_model, c.vocab, st);
     decode_maps(at<int32_t>(ctx->work, w.seq_len), B, at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos), st);
   }
-  run_layers<typename ActOf<T>::type>(ctx, B, true, st);
+  if (sizeof(T) == 2 && B <= kSkinnyMaxRows) run_layers_decode_f16(ctx, B, st);
+  else run_layers<typename ActOf<T>::type>(ctx, B, true, st);
   if (logits) run_head<T>(ctx, B, nullptr, logits, ld_logits, st);
   {
     ProfScope ps(ctx, FAM_MISC, st);

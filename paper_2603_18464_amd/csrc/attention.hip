@@ -12,7 +12,7 @@ template <class T, int HD>
 __global__ __launch_bounds__(256) void attention_rows_kernel(
     const T* __restrict__ q, int ldq, const T* __restrict__ k_cache, const T* __restrict__ v_cache,
     const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos, T* __restrict__ out, int ldo,
-    int n_items, int n_heads, int max_seq) {
+    int n_items, int n_heads, int max_seq, bool out_frag) {
   extern __shared__ float smem[];                    // per wave: [HD] query + [max_seq] scores
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int item = blockIdx.x * 4 + wave;            // (token, head)
@@ -52,7 +52,13 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
   for (int i = lane; i < HD; i += 64) {
     float acc = 0.f;
     for (int key = 0; key < ctx; ++key) acc = fmaf(sc[key], to_f32(vbase[(size_t)key * HD + i]), acc);
-    orow[i] = from_f32<T>(acc * inv);
+    if (out_frag) {   // [m/32][k/16][lane][8] fragment order with K = ldo (input of the decode GEMMs)
+      const int m = tok, k = head * HD + i;
+      out[((size_t)(m >> 5) * (ldo >> 4) + (k >> 4)) * 512 + ((m & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7)] =
+          from_f32<T>(acc * inv);
+    } else {
+      orow[i] = from_f32<T>(acc * inv);
+    }
   }
 }
 
@@ -230,14 +236,14 @@ void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache
 template <class T>
 void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, const int32_t* tok_seq,
                     const int32_t* tok_pos, T* out, int ldo, int n_tok, int n_heads, int head_dim, int max_seq,
-                    hipStream_t st) {
+                    bool out_frag, hipStream_t st) {
   const int n_items = n_tok * n_heads;
   const int blocks = (n_items + 3) / 4;
   const size_t smem = 4 * (size_t)(head_dim + max_seq) * sizeof(float);
 #define VLA_ATTN_CASE(HD)                                                                                   \
   case HD:                                                                                                  \
     hipLaunchKernelGGL((attention_rows_kernel<T, HD>), dim3(blocks), dim3(256), smem, st, q, ldq, k_cache,  \
-                       v_cache, tok_seq, tok_pos, out, ldo, n_items, n_heads, max_seq);                     \
+                       v_cache, tok_seq, tok_pos, out, ldo, n_items, n_heads, max_seq, out_frag);                     \
     break;
   switch (head_dim) {
     VLA_ATTN_CASE(32)
@@ -249,8 +255,8 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
 #undef VLA_ATTN_CASE
 }
 template void attention_rows<float>(const float*, int, const float*, const float*, const int32_t*, const int32_t*,
-                                    float*, int, int, int, int, int, hipStream_t);
+                                    float*, int, int, int, int, int, bool, hipStream_t);
 template void attention_rows<f16>(const f16*, int, const f16*, const f16*, const int32_t*, const int32_t*,
-                                  f16*, int, int, int, int, int, hipStream_t);
+                                  f16*, int, int, int, int, int, bool, hipStream_t);
 
 }  // namespace vla

@@ -74,6 +74,7 @@ struct RopeKv {
 // |w| up to 255 finite and everything above 2^-25 exact), activations rounded to f16 carry 8x less
 // rounding error than bf16 at the same MFMA rate, and the scale is divided out in the epilogue.
 constexpr float kWeightScale = 256.0f;
+constexpr int kMaxKSplit = 8;   // most K slices a decode GEMM is split into
 
 struct GemmF16 {
   const f16* A;    // [M, K] row-major activations
@@ -109,13 +110,25 @@ void embed_tokens(const int32_t* ids, const T* embed, float* x, int B, int d, in
 template <class T>
 void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, const int32_t* tok_seq,
                     const int32_t* tok_pos, T* out, int ldo, int n_tok, int n_heads, int head_dim,
-                    int max_seq, hipStream_t st);
+                    int max_seq, bool out_frag, hipStream_t st);
 
 // Prefill attention for the 16-bit path: causal flash attention over whole prefixes (MFMA).
 // cu_patch / cu_instr are the device copies of the cumulative offsets; max_len = longest prefix.
 void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* cu_patch,
                    const int32_t* cu_instr, f16* out, int ldo, int B, int max_len, int n_heads, int head_dim,
                    int max_seq, hipStream_t st);
+
+// Decode-step GEMMs (M <= 128): weight-streaming split-K kernel writing partial sums, and the kernels
+// that add the partials in a fixed order and apply the elementwise step that follows each GEMM.
+// Activations named *_frag are [M, K] in MFMA fragment order: [m/32][k/16][lane][8].
+int skinny_ksplit(int N, int K);
+int skinny_effective_ksplit(int K, int ksplit);
+void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int K, int ksplit, hipStream_t st);
+void reduce_resid_norm(const float* part, int ksplit, int M, int d, float* x, const float* gain, float eps,
+                       f16* hn_frag, hipStream_t st);
+void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f16* hn_frag, hipStream_t st);
+void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, hipStream_t st);
+void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, hipStream_t st);
 
 // Action head: final RMSNorm + action rows of the LM head -> logits [B, A] float32.
 template <class T>
