@@ -321,8 +321,12 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
     }
     {
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
-      attention_rows<f16>(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, d, B,
-                          c.n_heads, c.head_dim, c.max_seq, true, st);
+      if (c.max_seq <= decode_attention_max_ctx(c.head_dim))
+        decode_attention(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_pos, att, B, d, c.n_heads,
+                         c.head_dim, c.max_seq, st);
+      else
+        attention_rows<f16>(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, d, B,
+                            c.n_heads, c.head_dim, c.max_seq, true, st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_O_DECODE, st);

@@ -233,6 +233,112 @@ void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache
                        cu_instr, out, ldo, n_heads, max_seq);
 }
 
+// ---- decode: one new query per (sequence, head) against the whole cache -------------------------------
+// HBM-bound: the keys and values of a (slot, head) are one contiguous [position][HD] block each, and the
+// kernel streams them once with 16-byte-per-lane loads (a wave instruction covers 64*16/(2*HD) whole
+// rows).  One workgroup = 4 waves per (sequence, head); wave w takes every 4th group of rows.  A lane
+// owns 8 head dimensions of one row at a time: scores are reduced across the HD/8 lanes of a row with
+// shuffles, the probability-weighted values stay in 8 per-lane accumulators, and the partial softmax
+// statistics and outputs of the waves are merged through LDS at the end.
+template <int HD>
+__global__ __launch_bounds__(256) void decode_attention_kernel(
+    const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
+    const int32_t* __restrict__ tok_pos, f16* __restrict__ out_frag, int d_model, int n_heads, int max_seq) {
+  constexpr int LPR = HD / 8;            // lanes per row
+  constexpr int RPI = 64 / LPR;          // rows per wave instruction
+  constexpr int MAXR = 40;               // score slots per lane: covers (ctx / (4*RPI)) rows per wave
+  __shared__ float s_m[4], s_l[4];
+  __shared__ float s_o[4][HD];
+  const int b = blockIdx.x, head = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane / LPR, c = lane % LPR;          // row inside the instruction, 8-dim chunk
+  const int ctx = tok_pos[b] + 1;
+  const f16* kb = k_cache + ((size_t)b * n_heads + head) * max_seq * HD;
+  const f16* vb = v_cache + ((size_t)b * n_heads + head) * max_seq * HD;
+  const f16x8 qv = *(const f16x8*)(q + (size_t)b * ldq + head * HD + c * 8);
+  float qf[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) qf[j] = (float)qv[j];
+  const float scale = rsqrtf((float)HD);
+
+  // pass 1: scores of this wave's rows (row = (it*4 + wave)*RPI + sub), kept in registers
+  float sc[MAXR];
+  float mx = -INFINITY;
+  const int n_it = (ctx + 4 * RPI - 1) / (4 * RPI);
+#pragma unroll
+  for (int it = 0; it < MAXR; ++it) {
+    sc[it] = -INFINITY;
+    if (it < n_it) {
+      const int row = (it * 4 + wave) * RPI + sub;
+      const f16x8 kv = *(const f16x8*)(kb + (size_t)min(row, ctx - 1) * HD + c * 8);
+      float s = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s = fmaf(qf[j], (float)kv[j], s);
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      s = row < ctx ? s * scale : -INFINITY;
+      sc[it] = s;
+      mx = fmaxf(mx, s);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= LPR; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));   // over the rows of the wave
+  const float m_use = mx == -INFINITY ? 0.f : mx;
+  // pass 2: probabilities and weighted values
+  float acc[8] = {};
+  float lsum = 0.f;
+#pragma unroll
+  for (int it = 0; it < MAXR; ++it) {
+    if (it < n_it) {
+      const int row = (it * 4 + wave) * RPI + sub;
+      const float p = __expf(sc[it] - m_use);              // exp(-inf) = 0 for rows past the end
+      const f16x8 vv = *(const f16x8*)(vb + (size_t)min(row, ctx - 1) * HD + c * 8);
+      lsum += p;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] = fmaf(p, (float)vv[j], acc[j]);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= LPR; o >>= 1) {
+    lsum += __shfl_xor(lsum, o, 64);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += __shfl_xor(acc[j], o, 64);
+  }
+  if (sub == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s_o[wave][c * 8 + j] = acc[j];
+    if (c == 0) { s_m[wave] = mx; s_l[wave] = lsum; }
+  }
+  __syncthreads();
+  if (threadIdx.x < HD) {
+    const int i = threadIdx.x;
+    const float m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = s_m[w] == -INFINITY ? 0.f : __expf(s_m[w] - m);
+      l += s_l[w] * f;
+      o += s_o[w][i] * f;
+    }
+    const int k = head * HD + i;
+    out_frag[((size_t)(b >> 5) * (d_model >> 4) + (k >> 4)) * 512 + ((b & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7)] =
+        from_f32<f16>(o / l);
+  }
+}
+
+// Rows are the slots 0..B-1 themselves (decode keeps token b in slot b).  ctx <= 4 * RPI * 40 rows.
+void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_pos,
+                      f16* out_frag, int B, int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
+  const dim3 grid(B, n_heads);
+  if (head_dim == 128)
+    hipLaunchKernelGGL(decode_attention_kernel<128>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_pos,
+                       out_frag, d_model, n_heads, max_seq);
+  else
+    hipLaunchKernelGGL(decode_attention_kernel<64>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_pos,
+                       out_frag, d_model, n_heads, max_seq);
+}
+int decode_attention_max_ctx(int head_dim) { return 4 * (64 / (head_dim / 8)) * 40; }
+
 template <class T>
 void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, const int32_t* tok_seq,
                     const int32_t* tok_pos, T* out, int ldo, int n_tok, int n_heads, int head_dim, int max_seq,

@@ -141,9 +141,13 @@ __global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float* __r
   float ss = 0.f;
   for (int i = threadIdx.x * 4; i < d; i += 1024) {
     float4 v = *(const float4*)(row + i);
-    for (int ks = 0; ks < ksplit; ++ks) {
-      const float4 p = *(const float4*)(part + ((size_t)ks * M + m) * d + i);
-      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    float4 p[kMaxKSplit];
+#pragma unroll
+    for (int ks = 0; ks < kMaxKSplit; ++ks)            // all loads in flight first; summed in slice order
+      p[ks] = ks < ksplit ? *(const float4*)(part + ((size_t)ks * M + m) * d + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int ks = 0; ks < kMaxKSplit; ++ks) {
+      v.x += p[ks].x; v.y += p[ks].y; v.z += p[ks].z; v.w += p[ks].w;
     }
     *(float4*)(row + i) = v;
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;

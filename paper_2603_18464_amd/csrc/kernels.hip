@@ -190,8 +190,11 @@ template void rmsnorm<f16>(const float*, const f16*, const float*, f16*, int, in
                            hipStream_t);
 
 // ---- action head ------------------------------------------------------------------------------------
-// One workgroup per sequence: final RMSNorm of its row (float32, kept in LDS), then each wave takes
-// action rows of the slimmed head in turn, lanes striding over d, and reduces across the wave.
+// Workgroup (b, g): final RMSNorm of sequence b's row (float32, kept in LDS), then 32 action rows of
+// the slimmed head, 8 per wave, lanes striding over d with a wave reduction per row.  The norm is
+// recomputed by each of the A/32 workgroups of a sequence: that is 16 KiB from L2, and it spreads the
+// head over B * A/32 workgroups instead of B.
+constexpr int kHeadRows = 32;
 template <class T>
 __global__ __launch_bounds__(256) void head_kernel(const float* __restrict__ x, const int32_t* __restrict__ row_index,
                                                    const float* __restrict__ gain, const T* __restrict__ w_head,
@@ -201,19 +204,27 @@ __global__ __launch_bounds__(256) void head_kernel(const float* __restrict__ x, 
   const int b = blockIdx.x;
   const float* row = x + (size_t)(row_index ? row_index[b] : b) * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    const float v = row[i];
-    ss += v * v;
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {
+    const float4 v = *(const float4*)(row + i);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) hrow[i] = row[i] * inv * gain[i];
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {
+    const float4 v = *(const float4*)(row + i);
+    const float4 g = *(const float4*)(gain + i);
+    *(float4*)(hrow + i) = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
+  }
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int j = wave; j < A; j += 4) {
+  const int j0 = blockIdx.y * kHeadRows;
+  for (int j = j0 + wave; j < min(j0 + kHeadRows, A); j += 4) {
     const T* w = w_head + (size_t)j * d;
     float acc = 0.f;
-    for (int i = lane; i < d; i += 64) acc += to_f32(w[i]) * hrow[i];
+    for (int i = lane * 4; i < d; i += 256) {
+      const float4 h = *(const float4*)(hrow + i);
+      acc += to_f32(w[i]) * h.x + to_f32(w[i + 1]) * h.y + to_f32(w[i + 2]) * h.z + to_f32(w[i + 3]) * h.w;
+    }
     acc = wave_sum(acc);
     if (lane == 0) logits[(size_t)b * ld_logits + j] = acc;
   }
@@ -221,8 +232,8 @@ __global__ __launch_bounds__(256) void head_kernel(const float* __restrict__ x, 
 template <class T>
 void head_logits(const float* x, const int32_t* row_index, const float* gain, const T* w_head, float* logits,
                  int ld_logits, int B, int d, int A, float eps, hipStream_t st) {
-  hipLaunchKernelGGL(head_kernel<T>, dim3(B), dim3(256), d * sizeof(float), st, x, row_index, gain, w_head,
-                     logits, ld_logits, d, A, eps);
+  hipLaunchKernelGGL(head_kernel<T>, dim3(B, (A + kHeadRows - 1) / kHeadRows), dim3(256), d * sizeof(float), st, x,
+                     row_index, gain, w_head, logits, ld_logits, d, A, eps);
 }
 template void head_logits<float>(const float*, const int32_t*, const float*, const float*, float*, int, int, int,
                                  int, float, hipStream_t);
