@@ -40,6 +40,15 @@ def model_numbers(wl, cu_seq):
                 down_flops=2 * T * d * f)
 
 
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (profiles/traffic.json), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    entry = json.load(open(path)).get(f"{kernel}:{workload}")
+    return None if entry is None else entry.get("hbm_bytes_per_launch")
+
+
 def cpu_baseline(wl, weights_fn, obs, sample_layers):
     """Oracle ("cached" mode) on one sequence through `sample_layers` of the layers, scaled linearly
     to the full depth (every layer costs the same)."""
@@ -70,7 +79,7 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--prof-mask", type=lambda v: int(v, 0), default=0x1fff)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -93,7 +102,6 @@ def main():
     nums = model_numbers(wl, cu_seq)
     pol = VlaPolicy(wl.shape, wl.batch, wl.max_seq, nums["T"])
     pol.load_weights(weights)
-    keep = {n: weights[n] for n in weights} if False else None
     del weights
     pe = pol.to_device(obs["patch_emb"])
     ids = torch.from_numpy(obs["instr_ids"]).to(pol.device)
@@ -134,9 +142,10 @@ def main():
     roofline = None
     if g:
         ach = nums["gateup_flops"] / (g["avg_ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,2,2,EpiSwiglu> (prefill gate/up GEMM)",
+        roofline = {"bound": "mfma", "kernel": "gemm_f16_kernel<256,256,4,2,EpiSwiglu> (prefill gate/up GEMM)",
                     "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                    "avg_launch_ms": g["avg_ms"], "flops_per_launch": nums["gateup_flops"], "traffic": None}
+                    "avg_launch_ms": g["avg_ms"], "flops_per_launch": nums["gateup_flops"],
+                    "traffic": measured_traffic("gemm_gateup_prefill", wl.name)}
     extra = {}
     pre_ms = sum(v["total_ms_per_step"] for k, v in fam.items() if k.endswith("_prefill"))
     gemm_pre_ms = sum(v["total_ms_per_step"] for k, v in fam.items() if k.startswith("gemm") and k.endswith("_prefill"))
@@ -156,10 +165,12 @@ def main():
         "metric": "actions/sec of the batched VLA policy step (prefill + action-token decode + log-probs)",
         "value": actions_per_s, "unit": "actions/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.shape.dtype, "data": "synthetic",
+        "dtype": "f16" if wl.shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: 7B Llama-shaped VLA backbone" if wl.shape.n_layers == 32 else wl.name,
                    "n_layers": wl.shape.n_layers, "d_model": wl.shape.d_model, "batch": wl.batch,
-                   "prefix_tokens": nums["T"], "action_tokens": wl.n_tokens, "sampling": wl.sampling},
+                   "prefix_tokens": nums["T"], "action_tokens": wl.n_tokens, "sampling": wl.sampling,
+                   "weights": "bf16 at the boundary, re-encoded exactly as f16*2^8 for the matrix cores; "
+                              "f16 activations and KV cache, f32 accumulation" if wl.shape.dtype == "bf16" else "f32"},
         "roofline": roofline, "detail": extra,
     }
     if not args.no_cpu_baseline:

@@ -9,7 +9,8 @@
 //       row n0 + (l & 31), k = k0 + 8*(l >> 5) .. +7; blocks are ordered [n/32][k/16].  A wave
 //       reads one block with a single fully coalesced 16-byte-per-lane load, from global memory or
 //       from LDS, with no bank conflicts and no swizzle.
-// The kernel keeps a BM x 64 slab of A (XOR-swizzled 16-byte chunks) and a BN x 64 slab of Wp in
+// The kernel keeps a BM x 64 slab of A (16-byte chunk c of row r sits in slot c ^ ((r >> 1) & 7), so
+// that any 16 consecutive rows of one chunk column cover all 64 LDS banks) and a BN x 64 slab of Wp in
 // LDS, double buffered, and each of the WGM x WGN waves owns a (BM/WGM) x (BN/WGN) accumulator tile made
 // of 32x32x16 MFMAs.
 #include "common.h"
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i)
     a_ptr[i] = A + (size_t)min(m0 + a_r + i * (NTHR / 8), M - 1) * lda + a_c * 8;
-  const int a_dst = a_r * BK + ((a_c ^ (a_r & 7)) << 3);      // rows advance by multiples of 8: same swizzle
+  const int a_dst = a_r * BK + ((a_c ^ ((a_r >> 1) & 7)) << 3);   // rows advance by multiples of 16: same swizzle
   const f16* w_ptr[W_ITERS];
 #pragma unroll
   for (int i = 0; i < W_ITERS; ++i) {
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
   const int fhalf = lane >> 5;
   int a_off[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) a_off[kk] = frow * BK + (((kk * 2 + fhalf) ^ (frow & 7)) << 3);
+  for (int kk = 0; kk < 4; ++kk) a_off[kk] = frow * BK + (((kk * 2 + fhalf) ^ ((frow >> 1) & 7)) << 3);
   const int w_off = wn * NT * 4 * 512 + lane * 8;
 
   u32x4 ra[A_ITERS], rw[W_ITERS];

@@ -39,10 +39,10 @@ def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, of
     if scale is not None:
         from oracle.vla_oracle import detokenise
         ora["actions"] = detokenise(ora["tokens"], wl.shape.n_action_bins, wl.action_dim, scale, offset)
-    tol = P.TOL[wl.shape.dtype]
+    tol = P.tolerances(wl)
     stats = P.check_free_running(wl, gpu, ora, rows, tol)
-    tf_err = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
-    print(f"\n[{wl.name}] free-running {stats}; teacher-forced max logit err {tf_err:.3e}")
+    tf_err, tf_rms = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
+    print(f"\n[{wl.name}] free-running {stats}; teacher-forced logit err max {tf_err:.3e} rms {tf_rms:.3e}")
     pol.close()
     return stats, gpu, ora
 
@@ -132,11 +132,11 @@ def test_7b_workloads_against_stored_oracle_rows(name):
     assert np.isfinite(gpu["logits"]).all() and np.isfinite(gpu["logp"]).all()
     assert (gpu["tokens"] >= 0).all() and (gpu["tokens"] < wl.shape.n_action_bins).all()
     assert (gpu["logp"] <= 0).all()
-    tol = P.TOL["bf16"]
+    tol = P.tolerances(wl)
     stats = P.check_free_running(wl, gpu, ora, rows, tol)
     print(f"[{name}] teacher-forced pass", flush=True)
-    tf_err = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
-    print(f"[{name}] free-running {stats}; teacher-forced max logit err {tf_err:.3e}")
+    tf_err, tf_rms = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
+    print(f"[{name}] free-running {stats}; teacher-forced logit err max {tf_err:.3e} rms {tf_rms:.3e}")
     pol.close()
 
 
