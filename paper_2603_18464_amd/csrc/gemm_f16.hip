@@ -29,19 +29,29 @@ struct EpiResid {
   template <int MT, int NT>
   __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
     const int h = lane >> 5, c = lane & 31;
+    // Read-modify-write of the float32 residual stream.  All loads of a 32-row tile are issued before
+    // its first store (a store followed by a load of the same array would otherwise serialise on the
+    // memory latency); rows past M are read from row M-1 and not stored.
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+      float old[16][NT];
 #pragma unroll
-      for (int blk = 0; blk < 4; ++blk)
+      for (int e = 0; e < 16; ++e) {
+        const int m = min(mb + mt * 32 + 8 * (e >> 2) + 4 * h + (e & 3), M - 1);
+        const float* row = x + (size_t)m * ldx + nb + c;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int m = mb + mt * 32 + 8 * blk + 4 * h + r;
-          if (m < M) {
-            float* row = x + (size_t)m * ldx + nb + c;
+        for (int nt = 0; nt < NT; ++nt) old[e][nt] = row[nt * 32];
+      }
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) row[nt * 32] += acc[mt][nt][4 * blk + r] * (1.0f / kWeightScale);
-          }
+      for (int e = 0; e < 16; ++e) {
+        const int m = mb + mt * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+        if (m < M) {
+          float* row = x + (size_t)m * ldx + nb + c;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) row[nt * 32] = old[e][nt] + acc[mt][nt][e] * (1.0f / kWeightScale);
         }
+      }
+    }
   }
 };
 
@@ -254,6 +264,142 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
   epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
 }
 
+// ---- variant with direct global->LDS loads -----------------------------------------------------------
+// Same tiling and LDS layout, but the slabs go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l of a wave instruction deposits its 16 bytes at the wave-uniform
+// LDS base + 16*l), so there is no register staging and no ds_write.  For the row-major A slab one
+// instruction covers 8 rows x 128 bytes and the swizzle is applied on the source side: the lane that
+// fills slot s of row r fetches chunk s ^ ((r >> 1) & 7).  The weight slab is already in fragment
+// order, so it is a linear copy.  Per k-tile every wave first reads ALL its fragments of the current
+// slab into registers, then issues the loads of the next slab into the other buffer, then runs its
+// MFMAs; the loads have the whole MFMA phase to land and are waited for (vmcnt) only before the
+// barrier that opens the next k-tile.
+// 16 bytes per lane from global memory straight into LDS at lds_wave_base + 16 * lane.  The builtin only
+// exists in the device pass; the host pass just needs the kernel's stub.
+__device__ __forceinline__ void load_to_lds_16(const f16* src, f16* lds_wave_base) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(src, lds_wave_base, 16, 0, 0);
+#else
+  (void)src;
+  (void)lds_wave_base;
+#endif
+}
+
+template <int WGM, int WGN, class Epi>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_dma_kernel(
+    const f16* __restrict__ A, int lda, const f16* __restrict__ Wp, int M, int N, int K,
+    int tiles_m, int tiles_n, Epi epi) {
+  constexpr int BM = 256, BN = 256;
+  constexpr int NW = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
+  constexpr int A_INSTR = (BM / 8) / NW;       // wave instructions (8 rows each) per wave for the A slab
+  constexpr int W_INSTR = (BN * BK * 2 / 1024) / NW;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  f16* As = (f16*)smem;                       // [2][BM*64]
+  f16* Ws = As + 2 * BM * BK;                  // [2][BN*64]
+
+  const int nblk = tiles_m * tiles_n;
+  const int per_xcd = gridDim.x >> 3;
+  const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (pid >= nblk) return;
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int grp = pid / per_group;
+  const int first_m = grp * GM;
+  const int gm = min(tiles_m - first_m, GM);
+  const int in_grp = pid - grp * per_group;
+  const int tm = first_m + in_grp % gm;
+  const int tn = in_grp / gm;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int KB16 = K >> 4, KT = K / BK;
+
+  // source pointers of this lane for its wave's load instructions (advance by one k-tile per iteration)
+  const f16* a_src[A_INSTR];
+#pragma unroll
+  for (int i = 0; i < A_INSTR; ++i) {
+    const int g = wave * A_INSTR + i;                    // group of 8 rows
+    const int r = g * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    a_src[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
+  }
+  const f16* w_src[W_INSTR];
+#pragma unroll
+  for (int i = 0; i < W_INSTR; ++i) {
+    const int j = wave * W_INSTR + i;                    // KiB of the slab: block row j/4, k-step j%4
+    w_src[i] = Wp + ((size_t)(n0 / 32 + (j >> 2)) * KB16 + (j & 3)) * 512 + lane * 8;
+  }
+  auto issue = [&](int kt, int buf) {
+    f16* as = As + buf * BM * BK + wave * A_INSTR * 512;
+    f16* ws = Ws + buf * BN * BK + wave * W_INSTR * 512;
+#pragma unroll
+    for (int i = 0; i < A_INSTR; ++i)
+      load_to_lds_16(a_src[i] + (size_t)kt * BK, as + i * 512);
+#pragma unroll
+    for (int i = 0; i < W_INSTR; ++i)
+      load_to_lds_16(w_src[i] + (size_t)kt * 4 * 512, ws + i * 512);
+  };
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  const int frow = wm * WTM + (lane & 31);
+  const int fhalf = lane >> 5;
+  int a_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) a_off[kk] = frow * BK + (((kk * 2 + fhalf) ^ ((frow >> 1) & 7)) << 3);
+  const int w_off = wn * NT * 4 * 512 + lane * 8;
+
+  issue(0, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    __syncthreads();            // own loads of slab kt have landed (the compiler waits vmcnt before it), and
+                                // every wave has finished reading the other buffer
+    const f16* as = As + (kt & 1) * BM * BK;
+    const f16* ws = Ws + (kt & 1) * BN * BK + w_off;
+    f16x8 af[4][MT], bfr[4][NT];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) af[kk][mt] = *(const f16x8*)(as + a_off[kk] + mt * 32 * BK);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bfr[kk][nt] = *(const f16x8*)(ws + (nt * 4 + kk) * 512);
+    }
+    if (kt + 1 < KT) issue(kt + 1, (kt + 1) & 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[kk][mt], bfr[kk][nt], acc[mt][nt], 0, 0, 0);
+  }
+  epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
+}
+
+template <int WGM, int WGN, class Epi>
+static void launch_dma(const GemmF16& g, const Epi& epi, hipStream_t st) {
+  const int tiles_m = (g.M + 255) / 256, tiles_n = g.N / 256;
+  const int nblk = tiles_m * tiles_n;
+  const int grid = (nblk + 7) / 8 * 8;
+  constexpr size_t smem = 2 * (size_t)(256 + 256) * BK * sizeof(f16);
+  auto kern = gemm_f16_dma_kernel<WGM, WGN, Epi>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K,
+                     tiles_m, tiles_n, epi);
+}
+
 template <int BM, int BN, int WGM, int WGN, class Epi>
 static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
@@ -275,7 +421,11 @@ static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
 template <class Epi>
 static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   if (g.M > 128 && g.N % 256 == 0)
+#ifdef VLA_GEMM_NO_DMA
     launch<256, 256, 4, 2, Epi>(g, epi, st);
+#else
+    launch_dma<4, 2, Epi>(g, epi, st);
+#endif
   else if (g.N % 256 == 0)
     launch<64, 256, 2, 2, Epi>(g, epi, st);
   else
