@@ -77,7 +77,7 @@ struct EpiSwiglu {
             for (int j = 0; j < NT / 2; ++j) {
               const float g = acc[mt][2 * j][4 * blk + r] * (1.0f / kWeightScale);
               const float u = acc[mt][2 * j + 1][4 * blk + r] * (1.0f / kWeightScale);
-              row[j * 32] = from_f32<f16>(g / (1.0f + __expf(-g)) * u);
+              row[j * 32] = from_f32<f16>(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
             }
           }
         }
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
   const int per_xcd = gridDim.x >> 3;
   const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (pid >= nblk) return;
-  constexpr int GM = 8;
+  constexpr int GM = 4;
   const int per_group = GM * tiles_n;
   const int grp = pid / per_group;
   const int first_m = grp * GM;
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_dma_kernel(
   const int per_xcd = gridDim.x >> 3;
   const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (pid >= nblk) return;
-  constexpr int GM = 8;
+  constexpr int GM = 4;
   const int per_group = GM * tiles_n;
   const int grp = pid / per_group;
   const int first_m = grp * GM;
@@ -384,6 +384,193 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_dma_kernel(
   epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
 }
 
+// ---- 4-stage pipelined variant ------------------------------------------------------------------------
+// 256x256 tiles, k-slabs of 32 (16 KiB of A + 16 KiB of W per stage, four stages = 128 KiB of LDS), loaded
+// straight into LDS three slabs ahead of the MFMAs.  The compiler cannot tell the stages apart and would
+// wait for ALL outstanding LDS loads before any LDS read, so the fragment reads are issued from inline
+// assembly and the waits are explicit: vmcnt(2 * loads-per-slab) leaves the two newest slabs in flight,
+// one barrier per slab publishes the landed slab and retires the oldest buffer, which is refilled at once.
+// A slab layout: 64-byte rows, 16-byte chunk c of row r in slot c ^ ((r >> 2) & 3) (any 16 consecutive
+// rows of a chunk column then cover all 64 banks); one load instruction covers 16 rows.
+constexpr int PK = 32;                       // slab depth
+constexpr int P_STAGES = 4;
+constexpr int P_STAGE_HALVES = 256 * PK;     // per operand
+
+// Issues the 12 fragment reads of one slab (no wait).  The destination registers must not be touched
+// until frags_arrived() has been executed on them.
+template <int MT, int NT>
+__device__ __forceinline__ void read_frags_asm(f16x8 (&af)[2][MT], f16x8 (&bfr)[2][NT], unsigned a0, unsigned a1,
+                                               unsigned w) {
+  static_assert(MT == 2 && NT == 4, "written for the 64x128 wave tile");
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile(
+      "ds_read_b128 %0, %12\n\t"
+      "ds_read_b128 %1, %12 offset:2048\n\t"
+      "ds_read_b128 %4, %14\n\t"
+      "ds_read_b128 %5, %14 offset:2048\n\t"
+      "ds_read_b128 %6, %14 offset:4096\n\t"
+      "ds_read_b128 %7, %14 offset:6144\n\t"
+      "ds_read_b128 %2, %13\n\t"
+      "ds_read_b128 %3, %13 offset:2048\n\t"
+      "ds_read_b128 %8, %14 offset:1024\n\t"
+      "ds_read_b128 %9, %14 offset:3072\n\t"
+      "ds_read_b128 %10, %14 offset:5120\n\t"
+      "ds_read_b128 %11, %14 offset:7168"
+      : "=&v"(af[0][0]), "=&v"(af[0][1]), "=&v"(af[1][0]), "=&v"(af[1][1]), "=&v"(bfr[0][0]), "=&v"(bfr[0][1]),
+        "=&v"(bfr[0][2]), "=&v"(bfr[0][3]), "=&v"(bfr[1][0]), "=&v"(bfr[1][1]), "=&v"(bfr[1][2]), "=&v"(bfr[1][3])
+      : "v"(a0), "v"(a1), "v"(w)
+      : "memory");
+#endif
+}
+
+// Waits for every outstanding LDS read of this wave; the fragments are in/out operands so that nothing
+// that uses them can be scheduled above the wait.
+template <int MT, int NT>
+__device__ __forceinline__ void frags_arrived(f16x8 (&af)[2][MT], f16x8 (&bfr)[2][NT]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(af[0][0]), "+v"(af[0][1]), "+v"(af[1][0]), "+v"(af[1][1]), "+v"(bfr[0][0]), "+v"(bfr[0][1]),
+                 "+v"(bfr[0][2]), "+v"(bfr[0][3]), "+v"(bfr[1][0]), "+v"(bfr[1][1]), "+v"(bfr[1][2]), "+v"(bfr[1][3])
+               :
+               : "memory");
+#endif
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+#endif
+}
+
+template <class Epi>
+__global__ __launch_bounds__(512, 1) void gemm_f16_pipe_kernel(const f16* __restrict__ A, int lda,
+                                                              const f16* __restrict__ Wp, int M, int N, int K,
+                                                              int tiles_m, int tiles_n, Epi epi) {
+  constexpr int BM = 256, BN = 256, WGM = 4, WGN = 2, NW = 8;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
+  constexpr int A_INSTR = (BM / 16) / NW;      // 16 rows per load instruction -> 2 per wave
+  constexpr int W_INSTR = (BN * PK * 2 / 1024) / NW;   // 2 per wave
+  constexpr int LPS = A_INSTR + W_INSTR;       // loads per slab per wave
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  f16* As = (f16*)smem;                        // [4][256*32]
+  f16* Ws = As + P_STAGES * P_STAGE_HALVES;    // [4][256*32]
+
+  const int nblk = tiles_m * tiles_n;
+  const int per_xcd = gridDim.x >> 3;
+  const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (pid >= nblk) return;
+  constexpr int GM = 4;
+  const int per_group = GM * tiles_n;
+  const int grp = pid / per_group;
+  const int first_m = grp * GM;
+  const int gm = min(tiles_m - first_m, GM);
+  const int in_grp = pid - grp * per_group;
+  const int tm = first_m + in_grp % gm;
+  const int tn = in_grp / gm;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int KB16 = K >> 4, KT = K / PK;
+
+  const f16* a_src[A_INSTR];
+#pragma unroll
+  for (int i = 0; i < A_INSTR; ++i) {
+    const int r = (wave * A_INSTR + i) * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((r >> 2) & 3);
+    a_src[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
+  }
+  const f16* w_src[W_INSTR];
+#pragma unroll
+  for (int i = 0; i < W_INSTR; ++i) {
+    const int j = wave * W_INSTR + i;                    // KiB of the slab: block row j/2, k-step j%2
+    w_src[i] = Wp + ((size_t)(n0 / 32 + (j >> 1)) * KB16 + (j & 1)) * 512 + lane * 8;
+  }
+  auto issue = [&](int kt) {                             // slab kt (clamped) into buffer kt % 4
+    const int buf = kt & (P_STAGES - 1);
+    const int ks = min(kt, KT - 1);
+    f16* as = As + buf * P_STAGE_HALVES + wave * A_INSTR * 512;
+    f16* ws = Ws + buf * P_STAGE_HALVES + wave * W_INSTR * 512;
+#pragma unroll
+    for (int i = 0; i < A_INSTR; ++i) load_to_lds_16(a_src[i] + (size_t)ks * PK, as + i * 512);
+#pragma unroll
+    for (int i = 0; i < W_INSTR; ++i) load_to_lds_16(w_src[i] + (size_t)ks * 2 * 512, ws + i * 512);
+  };
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  // LDS byte addresses of this lane's fragments inside buffer 0
+  const unsigned lds0 = (unsigned)(size_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  const int frow = wm * WTM + (lane & 31);
+  const int fhalf = lane >> 5;
+  const unsigned a_k0 = lds0 + 2u * (unsigned)(frow * PK + (((0 + fhalf) ^ ((frow >> 2) & 3)) << 3));
+  const unsigned a_k1 = lds0 + 2u * (unsigned)(frow * PK + (((2 + fhalf) ^ ((frow >> 2) & 3)) << 3));
+  const unsigned w_b = lds0 + 2u * (unsigned)(P_STAGES * P_STAGE_HALVES + wn * NT * 2 * 512 + lane * 8);
+
+  // Fragments are double buffered in registers: while the MFMAs of slab kt run, the reads of slab kt+1
+  // are already in flight, so the LDS latency and the read burst after each barrier hide under MFMA work.
+  f16x8 af[2][2][MT], bfr[2][2][NT];
+  auto stage_off = [&](int kt) { return (unsigned)(kt & (P_STAGES - 1)) * (2u * P_STAGE_HALVES); };
+  auto mfma_half = [&](int f, int kk) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[f][kk][mt], bfr[f][kk][nt], acc[mt][nt], 0, 0, 0);
+  };
+  auto step = [&](int kt, int f) {           // f = kt & 1, passed as a constant by the unrolled caller
+    wait_vmcnt<LPS>();                       // this wave's loads of slab kt+1 have landed (kt+2 may be in flight)
+    __builtin_amdgcn_s_barrier();            // ... everyone's have; everyone holds slab kt in registers
+    {
+      const unsigned so = stage_off(kt + 1);
+      read_frags_asm<MT, NT>(af[f ^ 1], bfr[f ^ 1], a_k0 + so, a_k1 + so, w_b + so);
+    }
+    mfma_half(f, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(kt + 3);                           // refill the buffer slab kt-1 lived in
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_half(f, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    frags_arrived<MT, NT>(af[f ^ 1], bfr[f ^ 1]);
+  };
+  issue(0);
+  issue(1);
+  issue(2);
+  wait_vmcnt<2 * LPS>();
+  __builtin_amdgcn_s_barrier();
+  read_frags_asm<MT, NT>(af[0], bfr[0], a_k0, a_k1, w_b);
+  frags_arrived<MT, NT>(af[0], bfr[0]);
+  for (int kt = 0; kt < KT; kt += 2) {       // K is a multiple of 64: KT is even
+    step(kt, 0);
+    step(kt + 1, 1);
+  }
+  wait_vmcnt<0>();                           // the clamped tail loads still target this workgroup's LDS
+  epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
+}
+
+template <class Epi>
+static void launch_pipe(const GemmF16& g, const Epi& epi, hipStream_t st) {
+  const int tiles_m = (g.M + 255) / 256, tiles_n = g.N / 256;
+  const int nblk = tiles_m * tiles_n;
+  const int grid = (nblk + 7) / 8 * 8;
+  constexpr size_t smem = 2 * (size_t)P_STAGES * P_STAGE_HALVES * sizeof(f16);
+  auto kern = gemm_f16_pipe_kernel<Epi>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, tiles_m, tiles_n, epi);
+}
+
 template <int WGM, int WGN, class Epi>
 static void launch_dma(const GemmF16& g, const Epi& epi, hipStream_t st) {
   const int tiles_m = (g.M + 255) / 256, tiles_n = g.N / 256;
@@ -421,10 +608,12 @@ static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
 template <class Epi>
 static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   if (g.M > 128 && g.N % 256 == 0)
-#ifdef VLA_GEMM_NO_DMA
+#if defined(VLA_GEMM_NO_DMA)
     launch<256, 256, 4, 2, Epi>(g, epi, st);
-#else
+#elif defined(VLA_GEMM_DMA2)
     launch_dma<4, 2, Epi>(g, epi, st);
+#else
+    launch_pipe<Epi>(g, epi, st);
 #endif
   else if (g.N % 256 == 0)
     launch<64, 256, 2, 2, Epi>(g, epi, st);
