@@ -1,5 +1,6 @@
 // Decode-step GEMMs: C[M,N] = A[M,K] * W[N,K]^T with M = batch (<= 128 rows), bound by streaming the
-// weights from HBM once.  No LDS and no barriers: every wave is an independent stream.
+// weights from HBM once.  No LDS and no barriers in the streaming loop: every wave is an independent
+// stream.
 //
 //   * A wave owns two 32-row weight blocks (64 output columns) over one slice of K.  Per k-step of 16
 //     it loads two weight fragments (1 KiB each, fully coalesced, straight from the packed layout into
@@ -8,10 +9,10 @@
 //     that way by the producing kernels), so their loads are coalesced 1 KiB reads that hit in L2.
 //   * Loads run D k-steps ahead of the MFMAs through a register ring (static indices after unrolling),
 //     which keeps D * (2 + M/32) KiB per wave in flight.
-//   * K is split over `ksplit` waves per column pair to put enough waves on the chip; each writes its
-//     partial sums to part[ks][M][N] and the following reduce kernel adds them in a fixed order
-//     (deterministic) and applies the layer's elementwise step: RoPE + KV append, residual add +
-//     RMSNorm for the next GEMM, or SwiGLU.
+//   * K is split into 4 * kgroups slices to put enough waves on the chip.  The four waves of a
+//     workgroup add their partial tiles through LDS; one plane part[kg][M][N] is written per group and
+//     the following reduce kernel adds the planes in a fixed order (deterministic) and applies the
+//     layer's elementwise step: RoPE + KV append, residual add + RMSNorm for the next GEMM, or SwiGLU.
 #include "common.h"
 
 namespace vla {
@@ -19,16 +20,18 @@ namespace vla {
 template <int MT, int D>
 __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict__ Af, const f16* __restrict__ Wp,
                                                           float* __restrict__ part, int M, int N, int K,
-                                                          int ksplit, int kb_per_split) {
-  const int lane = threadIdx.x & 63;
-  const int NP = N >> 6;                                  // column pairs
-  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (unit >= NP * ksplit) return;
-  const int nbp = unit % NP, ks = unit / NP;              // neighbouring waves share the activation slice
+                                                          int kgroups) {
+  // Workgroup = one pair of 32-row weight blocks (64 output columns) x one group of 4 K slices; wave w
+  // streams slice 4*kg + w.  The four partial tiles are added through LDS in the fixed order
+  // (w0 + w2) + (w1 + w3), so one plane part[kg] is written per group, deterministically.
+  extern __shared__ float red[];                          // [2][MT*32 regs][64 lanes]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int NP = N >> 6;
+  const int nbp = blockIdx.x % NP, kg = blockIdx.x / NP;
   const int KB16 = K >> 4;
-  const int kb_begin = ks * kb_per_split;
-  const int kb_end = min(kb_begin + kb_per_split, KB16);
-  if (kb_begin >= kb_end) return;                         // cannot happen for the splits the host picks
+  const int slices = 4 * kgroups, sl = 4 * kg + wave;
+  const int kb_begin = (int)((long long)sl * KB16 / slices);
+  const int kb_end = (int)((long long)(sl + 1) * KB16 / slices);   // non-empty: slices <= KB16
 
   const f16* w0 = Wp + ((size_t)(2 * nbp) * KB16) * 512 + lane * 8;
   const f16* w1 = w0 + (size_t)KB16 * 512;
@@ -42,34 +45,85 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // Each wave walks its slice from a different starting point (rotated by its column pair).  The rows of
+  // the packed matrix are a power-of-two number of bytes apart for K = 4096, so waves marching through k
+  // in lockstep would all hit the same memory channels at the same time.
+  const int len = kb_end - kb_begin;
+  const int rot = (nbp * 5) % len;
+  auto kb_of = [&](int i) {                                // i-th step of this wave, clamped to the slice
+    const int j = min(i, len - 1) + rot;
+    return (size_t)(kb_begin + (j >= len ? j - len : j));
+  };
   f16x8 wq[D][2], aq[D][MT];
 #pragma unroll
   for (int s = 0; s < D; ++s) {
-    const size_t kb = (size_t)min(kb_begin + s, kb_end - 1);
+    const size_t kb = kb_of(s);
     wq[s][0] = *(const f16x8*)(w0 + kb * 512);
     wq[s][1] = *(const f16x8*)(w1 + kb * 512);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) aq[s][mt] = *(const f16x8*)(a0 + ((size_t)mt * KB16 + kb) * 512);
   }
-  for (int base = kb_begin; base < kb_end; base += D) {
+  // Full groups of D k-steps: straight-line body (no branches, so the load counter is tracked exactly and
+  // each MFMA waits only for its own stage); every consumed stage is refilled D steps ahead, clamped to the
+  // last step of the slice.  The remaining steps (< D) sit in the first stages after the last group.
+  const int n_full = len / D;
+  for (int g = 0; g < n_full; ++g) {
+    const int base = g * D;
 #pragma unroll
     for (int s = 0; s < D; ++s) {
-      if (base + s < kb_end) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][0], acc[mt][0], 0, 0, 0);
-          acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][1], acc[mt][1], 0, 0, 0);
-        }
+      for (int mt = 0; mt < MT; ++mt) {
+        acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][0], acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][1], acc[mt][1], 0, 0, 0);
       }
-      const size_t kb = (size_t)min(base + s + D, kb_end - 1);   // tail: re-reads the last step, in bounds
+      const size_t kb = kb_of(base + s + D);
       wq[s][0] = *(const f16x8*)(w0 + kb * 512);
       wq[s][1] = *(const f16x8*)(w1 + kb * 512);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) aq[s][mt] = *(const f16x8*)(a0 + ((size_t)mt * KB16 + kb) * 512);
+      __builtin_amdgcn_sched_barrier(0);   // keep the refills in stage order, or the oldest stage's wait
+                                           // degenerates into a wait for every outstanding load
     }
   }
+  const int rem = len - n_full * D;
+#pragma unroll
+  for (int s = 0; s < D; ++s) {
+    if (s < rem) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][0], acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][1], acc[mt][1], 0, 0, 0);
+      }
+    }
+  }
+  // tree reduction over the four waves
+  constexpr int REGS = MT * 32;
+  auto put = [&](int slot) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[((size_t)slot * REGS + (mt * 2 + j) * 16 + e) * 64 + lane] = acc[mt][j][e];
+  };
+  auto add = [&](int slot) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[mt][j][e] += red[((size_t)slot * REGS + (mt * 2 + j) * 16 + e) * 64 + lane];
+  };
+  if (wave >= 2) put(wave - 2);
+  __syncthreads();
+  if (wave < 2) add(wave);                                  // w0 += w2, w1 += w3
+  __syncthreads();
+  if (wave == 1) put(0);
+  __syncthreads();
+  if (wave != 0) return;
+  add(0);
   const int h = lane >> 5, c = lane & 31;
-  float* out = part + (size_t)ks * M * N + nbp * 64 + c;
+  float* out = part + (size_t)kg * M * N + nbp * 64 + c;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -84,36 +138,46 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
       }
 }
 
+#ifndef VLA_SKINNY_UNITS
+#define VLA_SKINNY_UNITS 1024    // independent streams (waves) a decode GEMM is cut into, at least
+#endif
+// Number of partial planes (groups of 4 K slices) for an [N, K] weight matrix.
 int skinny_ksplit(int N, int K) {
   const int NP = N / 64;
-  int ks = (768 + NP - 1) / NP;
-  if (ks < 1) ks = 1;
-  if (ks > kMaxKSplit) ks = kMaxKSplit;
-  const int KB16 = K / 16;
-  if (ks > KB16) ks = KB16;
-  return ks;
+  int kg = (VLA_SKINNY_UNITS + 4 * NP - 1) / (4 * NP);
+  if (kg < 1) kg = 1;
+  if (kg > kMaxKSplit) kg = kMaxKSplit;
+  while (kg > 1 && 4 * kg > K / 16) --kg;
+  return kg;
 }
 
-void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int K, int ksplit, hipStream_t st) {
-  const int KB16 = K / 16;
-  const int kbps = (KB16 + ksplit - 1) / ksplit;
-  ksplit = (KB16 + kbps - 1) / kbps;                       // drop empty slices
-  const int units = (N / 64) * ksplit;
-  const dim3 grid((units + 3) / 4), block(256);
+void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int K, int kgroups, hipStream_t st) {
+  const dim3 grid((N / 64) * kgroups), block(256);
   const int MT = (M + 31) / 32;
+  const size_t smem = (size_t)2 * MT * 32 * 64 * sizeof(float);
+#define VLA_SKINNY_CASE(MTV, DV)                                                                                  \
+  case MTV: {                                                                                                     \
+    auto kern = skinny_gemm_kernel<MTV, DV>;                                                                      \
+    static bool attr_set = false;                                                                                 \
+    if (!attr_set) {                                                                                              \
+      (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);        \
+      attr_set = true;                                                                                            \
+    }                                                                                                             \
+    hipLaunchKernelGGL(kern, grid, block, smem, st, Afrag, Wp, part, M, N, K, kgroups);                           \
+  } break;
   switch (MT) {
-    case 1: hipLaunchKernelGGL((skinny_gemm_kernel<1, 8>), grid, block, 0, st, Afrag, Wp, part, M, N, K, ksplit, kbps); break;
-    case 2: hipLaunchKernelGGL((skinny_gemm_kernel<2, 6>), grid, block, 0, st, Afrag, Wp, part, M, N, K, ksplit, kbps); break;
-    case 3: hipLaunchKernelGGL((skinny_gemm_kernel<3, 4>), grid, block, 0, st, Afrag, Wp, part, M, N, K, ksplit, kbps); break;
-    case 4: hipLaunchKernelGGL((skinny_gemm_kernel<4, 4>), grid, block, 0, st, Afrag, Wp, part, M, N, K, ksplit, kbps); break;
+    VLA_SKINNY_CASE(1, 8)
+    VLA_SKINNY_CASE(2, 6)
+    VLA_SKINNY_CASE(3, 4)
+    VLA_SKINNY_CASE(4, 4)
     default: break;                                        // callers keep M <= 128
   }
+#undef VLA_SKINNY_CASE
 }
 
 int skinny_effective_ksplit(int K, int ksplit) {
-  const int KB16 = K / 16;
-  const int kbps = (KB16 + ksplit - 1) / ksplit;
-  return (KB16 + kbps - 1) / kbps;
+  (void)K;
+  return ksplit;
 }
 
 // ---- reduce + elementwise kernels ---------------------------------------------------------------------
