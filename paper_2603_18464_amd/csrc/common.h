@@ -74,7 +74,7 @@ struct RopeKv {
 // |w| up to 255 finite and everything above 2^-25 exact), activations rounded to f16 carry 8x less
 // rounding error than bf16 at the same MFMA rate, and the scale is divided out in the epilogue.
 constexpr float kWeightScale = 256.0f;
-constexpr int kMaxKSplit = 8;   // most K slices a decode GEMM is split into
+constexpr int kMaxKSplit = 4;   // most partial planes (groups of 4 K slices) a decode GEMM writes
 
 struct GemmF16 {
   const f16* A;    // [M, K] row-major activations

@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
 }
 
 #ifndef VLA_SKINNY_UNITS
-#define VLA_SKINNY_UNITS 1024    // independent streams (waves) a decode GEMM is cut into, at least
+#define VLA_SKINNY_UNITS 1536    // independent streams (waves) a decode GEMM is cut into, at least
 #endif
 // Number of partial planes (groups of 4 K slices) for an [N, K] weight matrix.
 int skinny_ksplit(int N, int K) {

@@ -23,9 +23,40 @@ constexpr int BK = 64;
 // Accumulator layout of v_mfma_f32_32x32x16_f16: lane l, register 4*blk + r holds
 // C[row = 8*blk + 4*(l >> 5) + r][col = l & 31].
 
+// Staged epilogues (large-tile kernel): a wave first writes a 32 x 128 float accumulator sub-tile to its
+// private LDS region in row-major order (pitch kStagePitch floats: the two half-waves of a store hit
+// disjoint banks), then reads it back as float4 row chunks, so that global memory sees 16-byte accesses
+// that cover whole 128- to 512-byte row segments instead of scattered 2- and 4-byte ones.
+constexpr int kStagePitch = 136;
+constexpr int kStageFloats = 32 * kStagePitch;   // per wave
+
+__device__ __forceinline__ void stage_tile(const f32x16 (&a)[4], float* tile, int lane) {
+  const int h = lane >> 5, c = lane & 31;
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) tile[(8 * (e >> 2) + 4 * h + (e & 3)) * kStagePitch + nt * 32 + c] = a[nt][e];
+}
+
 struct EpiResid {
   float* x;
   int ldx;
+  // rows m_base .. m_base+31, columns nb .. nb+127 of x += tile / kWeightScale
+  __device__ __forceinline__ void consume(const float* tile, int m_base, int nb, int lane, int M) const {
+    const int r0 = lane >> 5, c4 = (lane & 31) * 4;
+    f32x4 v[16], old[16];
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int r = it * 2 + r0;
+      v[it] = *(const f32x4*)(tile + r * kStagePitch + c4);
+      old[it] = *(const f32x4*)(x + (size_t)min(m_base + r, M - 1) * ldx + nb + c4);
+    }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int m = m_base + it * 2 + r0;
+      if (m < M) *(f32x4*)(x + (size_t)m * ldx + nb + c4) = old[it] + v[it] * (1.0f / kWeightScale);
+    }
+  }
   template <int MT, int NT>
   __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
     const int h = lane >> 5, c = lane & 31;
@@ -60,6 +91,21 @@ struct EpiResid {
 struct EpiSwiglu {
   f16* act;
   int ld;
+  // the 128 tile columns are [gate 32 | up 32 | gate 32 | up 32] -> 64 outputs per row
+  __device__ __forceinline__ void consume(const float* tile, int m_base, int nb, int lane, int M) const {
+    typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+    const int rs = lane >> 4, q = lane & 15, jb = q >> 3, c4 = (q & 7) * 4;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 4 + rs, m = m_base + r;
+      const f32x4 g = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + c4) * (1.0f / kWeightScale);
+      const f32x4 u = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + 32 + c4) * (1.0f / kWeightScale);
+      f16x4 o;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[j] = from_f32<f16>(g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j])) * u[j]);
+      if (m < M) *(f16x4*)(act + (size_t)m * ld + nb / 2 + jb * 32 + c4) = o;
+    }
+  }
   template <int MT, int NT>
   __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
     static_assert(NT % 2 == 0, "gate/up tiles come in pairs");
@@ -89,6 +135,45 @@ struct EpiSwiglu {
 template <int HD>
 struct EpiQkv {
   RopeKv o;
+  // the 128 tile columns are 128/HD whole heads of one section (q, k or v)
+  __device__ __forceinline__ void consume(const float* tile, int m_base, int nb, int lane, int M) const {
+    typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+    constexpr int HALF = HD / 2, LPH = HD / 8;      // lanes per head: 16 lanes cover the 128/HD heads of a row
+    const int rs = lane >> 4, q = lane & 15, hh = q / LPH, c4 = (q % LPH) * 4;
+    const int d = o.d_model;
+    const int sect = nb / d;
+    const int head = (nb - sect * d) / HD + hh;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 4 + rs, m = m_base + r;
+      if (m >= M) continue;
+      f32x4 lo = *(const f32x4*)(tile + r * kStagePitch + hh * HD + c4) * (1.0f / kWeightScale);
+      f32x4 hi = *(const f32x4*)(tile + r * kStagePitch + hh * HD + HALF + c4) * (1.0f / kWeightScale);
+      const int pos = o.tok_pos[m];
+      f16* dst;
+      if (sect == 0) {
+        dst = (f16*)o.q + (size_t)m * d + (size_t)head * HD;
+      } else {
+        const int slot = o.tok_seq[m];
+        dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) + (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * HD;
+      }
+      if (sect < 2) {
+        const f32x4 cs = *(const f32x4*)(o.rope_cos + (size_t)pos * HALF + c4);
+        const f32x4 sn = *(const f32x4*)(o.rope_sin + (size_t)pos * HALF + c4);
+        const f32x4 a = lo * cs - hi * sn, b = hi * cs + lo * sn;
+        lo = a;
+        hi = b;
+      }
+      f16x4 l4, h4;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        l4[j] = from_f32<f16>(lo[j]);
+        h4[j] = from_f32<f16>(hi[j]);
+      }
+      *(f16x4*)(dst + c4) = l4;
+      *(f16x4*)(dst + HALF + c4) = h4;
+    }
+  }
   template <int MT, int NT>
   __device__ __forceinline__ void apply(f32x16 (&acc)[MT][NT], int mb, int nb, int lane, int M) const {
     constexpr int HT = HD / 32;              // 32-column tiles per head
@@ -553,7 +638,13 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_pipe_kernel(const f16* __rest
     step(kt + 1, 1);
   }
   wait_vmcnt<0>();                           // the clamped tail loads still target this workgroup's LDS
-  epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
+  __syncthreads();                           // every wave is done with the slabs: LDS becomes epilogue staging
+  float* tile = (float*)smem + wave * kStageFloats;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    stage_tile(acc[mt], tile, lane);
+    epi.consume(tile, m0 + wm * WTM + mt * 32, n0 + wn * WTN, lane, M);
+  }
 }
 
 template <class Epi>
@@ -561,7 +652,9 @@ static void launch_pipe(const GemmF16& g, const Epi& epi, hipStream_t st) {
   const int tiles_m = (g.M + 255) / 256, tiles_n = g.N / 256;
   const int nblk = tiles_m * tiles_n;
   const int grid = (nblk + 7) / 8 * 8;
-  constexpr size_t smem = 2 * (size_t)P_STAGES * P_STAGE_HALVES * sizeof(f16);
+  constexpr size_t slabs = 2 * (size_t)P_STAGES * P_STAGE_HALVES * sizeof(f16);
+  constexpr size_t stage = 8 * (size_t)kStageFloats * sizeof(float);
+  constexpr size_t smem = slabs > stage ? slabs : stage;
   auto kern = gemm_f16_pipe_kernel<Epi>;
   static bool attr_set = false;
   if (!attr_set) {
