@@ -279,8 +279,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
   return VLA_OK;
 }
 
-// Decode step of the 16-bit path for batches of at most kSkinnyMaxRows rows: weight-streaming split-K
-// GEMMs, each followed by the kernel that sums the K slices and applies the elementwise step.
+// Decode step of the 16-bit path: weight-streaming split-K GEMMs, each followed by the kernel that sums the
+// K slices and applies the elementwise step.
 int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
@@ -314,10 +314,16 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
     rk.head_dim = c.head_dim;
     rk.max_seq = c.max_seq;
     rk.d_model = d;
+    // GEMMs and their reduce kernels run on chunks of at most kSkinnyMaxRows rows (the weights are streamed
+    // once per chunk); attention runs on the whole batch.
+    auto frag_rows = [&](f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; };
     {
       ProfScope ps(ctx, FAM_GEMM_QKV_DECODE, st);
-      skinny_gemm(hn, at<f16>(ctx->arena, lw.w_qkv), part, B, 3 * d, d, ks_qkv, st);
-      reduce_qkv_rope(part, skinny_effective_ksplit(d, ks_qkv), B, rk, st);
+      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
+        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
+        skinny_gemm(frag_rows(hn, r0, d), at<f16>(ctx->arena, lw.w_qkv), part, m, 3 * d, d, ks_qkv, st);
+        reduce_qkv_rope(part, ks_qkv, m, rk, r0, st);
+      }
     }
     {
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
@@ -330,19 +336,28 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
     }
     {
       ProfScope ps(ctx, FAM_GEMM_O_DECODE, st);
-      skinny_gemm(att, at<f16>(ctx->arena, lw.w_o), part, B, d, d, ks_o, st);
-      reduce_resid_norm(part, skinny_effective_ksplit(d, ks_o), B, d, x, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, st);
+      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
+        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
+        skinny_gemm(frag_rows(att, r0, d), at<f16>(ctx->arena, lw.w_o), part, m, d, d, ks_o, st);
+        reduce_resid_norm(part, ks_o, m, d, x, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, r0, st);
+      }
     }
     {
       ProfScope ps(ctx, FAM_GEMM_GATEUP_DECODE, st);
-      skinny_gemm(hn, at<f16>(ctx->arena, lw.w_gu), part, B, 2 * f, d, ks_gu, st);
-      reduce_swiglu(part, skinny_effective_ksplit(d, ks_gu), B, f, act, st);
+      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
+        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
+        skinny_gemm(frag_rows(hn, r0, d), at<f16>(ctx->arena, lw.w_gu), part, m, 2 * f, d, ks_gu, st);
+        reduce_swiglu(part, ks_gu, m, f, act, r0, st);
+      }
     }
     {
       ProfScope ps(ctx, FAM_GEMM_DOWN_DECODE, st);
-      skinny_gemm(act, at<f16>(ctx->arena, lw.w_down), part, B, d, f, ks_dn, st);
       const float* next_gain = l + 1 < c.n_layers ? at<float>(ctx->arena, ctx->al.layers[l + 1].g_attn) : nullptr;
-      reduce_resid_norm(part, skinny_effective_ksplit(f, ks_dn), B, d, x, next_gain, c.rms_eps, hn, st);
+      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
+        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
+        skinny_gemm(frag_rows(act, r0, f), at<f16>(ctx->arena, lw.w_down), part, m, d, f, ks_dn, st);
+        reduce_resid_norm(part, ks_dn, m, d, x, next_gain, c.rms_eps, hn, r0, st);
+      }
     }
   }
   return VLA_OK;
@@ -450,7 +465,7 @@ int do_decode(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits, 
     embed_tokens<T>(token_ids, at<T>(ctx->arena, ctx->al.embed), at<float>(ctx->work, w.x), B, c.d_model, c.vocab, st);
     decode_maps(at<int32_t>(ctx->work, w.seq_len), B, at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos), st);
   }
-  if (sizeof(T) == 2 && B <= kSkinnyMaxRows) run_layers_decode_f16(ctx, B, st);
+  if (sizeof(T) == 2) run_layers_decode_f16(ctx, B, st);
   else run_layers<typename ActOf<T>::type>(ctx, B, true, st);
   if (logits) run_head<T>(ctx, B, nullptr, logits, ld_logits, st);
   {

@@ -125,10 +125,10 @@ int skinny_ksplit(int N, int K);
 int skinny_effective_ksplit(int K, int ksplit);
 void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int K, int ksplit, hipStream_t st);
 void reduce_resid_norm(const float* part, int ksplit, int M, int d, float* x, const float* gain, float eps,
-                       f16* hn_frag, hipStream_t st);
+                       f16* hn_frag, int row0, hipStream_t st);
 void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f16* hn_frag, hipStream_t st);
-void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, hipStream_t st);
-void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, hipStream_t st);
+void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, int row0, hipStream_t st);
+void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, int row0, hipStream_t st);
 
 // Decode attention of the 16-bit path (one query per slot); output in fragment order.  Handles contexts
 // up to decode_attention_max_ctx(head_dim) positions.

@@ -195,13 +195,14 @@ __device__ __forceinline__ float block_sum_256d(float v, float* red) {
 }
 
 // x[m,:] += sum_ks part[ks][m,:]; if gain: hn (fragment order) = f16(x * gain / rms(x)).
+// Rows are handled in chunks: part holds rows 0..M-1 of the chunk, which are rows row0.. of x and hn.
 __global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float* __restrict__ part, int ksplit, int M,
                                                                 int d, float* __restrict__ x,
                                                                 const float* __restrict__ gain, float eps,
-                                                                f16* __restrict__ hn_frag) {
+                                                                f16* __restrict__ hn_frag, int row0) {
   __shared__ float red[4];
   const int m = blockIdx.x;
-  float* row = x + (size_t)m * d;
+  float* row = x + (size_t)(row0 + m) * d;
   float ss = 0.f;
   for (int i = threadIdx.x * 4; i < d; i += 1024) {
     float4 v = *(const float4*)(row + i);
@@ -228,13 +229,14 @@ __global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float* __r
     o[1] = from_f32<f16>(v.y * inv * g.y);
     o[2] = from_f32<f16>(v.z * inv * g.z);
     o[3] = from_f32<f16>(v.w * inv * g.w);
-    *(f16x4*)(hn_frag + frag_index(m, i, d)) = o;
+    *(f16x4*)(hn_frag + frag_index(row0 + m, i, d)) = o;
   }
 }
 
 void reduce_resid_norm(const float* part, int ksplit, int M, int d, float* x, const float* gain, float eps,
-                       f16* hn_frag, hipStream_t st) {
-  hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(M), dim3(256), 0, st, part, ksplit, M, d, x, gain, eps, hn_frag);
+                       f16* hn_frag, int row0, hipStream_t st) {
+  hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(M), dim3(256), 0, st, part, ksplit, M, d, x, gain, eps, hn_frag,
+                     row0);
 }
 
 // Plain RMSNorm of x rows into fragment order (first norm of a decode step).
@@ -265,7 +267,7 @@ void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f1
 // act (fragment order, [M, f]) = silu(gate) * up, gate/up summed over the K slices.  The fused
 // gate-up columns are interleaved in blocks of 32: gate j at (j/32)*64 + j%32, up 32 further.
 __global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float* __restrict__ part, int ksplit, int M, int f,
-                                                            f16* __restrict__ act_frag) {
+                                                            f16* __restrict__ act_frag, int row0) {
   const int m = blockIdx.y;
   const int j0 = (blockIdx.x * 256 + threadIdx.x) * 8;      // 8 consecutive outputs (same 32-block)
   if (j0 >= f) return;
@@ -282,18 +284,19 @@ __global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float* __restr
   f16x8 o;
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = from_f32<f16>(g[j] / (1.0f + __expf(-g[j])) * u[j]);
-  *(f16x8*)(act_frag + frag_index(m, j0, f)) = o;
+  *(f16x8*)(act_frag + frag_index(row0 + m, j0, f)) = o;
 }
-void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, hipStream_t st) {
-  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((f / 8 + 255) / 256, M), dim3(256), 0, st, part, ksplit, M, f, act_frag);
+void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, int row0, hipStream_t st) {
+  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((f / 8 + 255) / 256, M), dim3(256), 0, st, part, ksplit, M, f, act_frag,
+                     row0);
 }
 
 // q (row-major [M, d]) and the new K/V cache rows from the summed QKV partials, with RoPE.
 __global__ __launch_bounds__(256) void reduce_qkv_rope_kernel(const float* __restrict__ part, int ksplit, int M,
-                                                              RopeKv o) {
+                                                              RopeKv o, int row0) {
   const int m = blockIdx.x;
   const int d = o.d_model, hd = o.head_dim, half = hd >> 1;
-  const int pos = o.tok_pos[m], slot = o.tok_seq[m];
+  const int pos = o.tok_pos[row0 + m], slot = o.tok_seq[row0 + m];
   const size_t N = 3 * (size_t)d;
   for (int idx = threadIdx.x; idx < d / 2; idx += 256) {
     const int head = idx / half, i = idx - head * half;
@@ -304,7 +307,7 @@ __global__ __launch_bounds__(256) void reduce_qkv_rope_kernel(const float* __res
       v[0] += p[c0]; v[1] += p[c1]; v[2] += p[d + c0]; v[3] += p[d + c1]; v[4] += p[2 * d + c0]; v[5] += p[2 * d + c1];
     }
     const float cs = o.rope_cos[pos * half + i], sn = o.rope_sin[pos * half + i];
-    f16* q = (f16*)o.q + (size_t)m * d;
+    f16* q = (f16*)o.q + (size_t)(row0 + m) * d;
     q[c0] = from_f32<f16>(v[0] * cs - v[1] * sn);
     q[c1] = from_f32<f16>(v[1] * cs + v[0] * sn);
     const size_t kv = (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * hd;
@@ -314,8 +317,8 @@ __global__ __launch_bounds__(256) void reduce_qkv_rope_kernel(const float* __res
     ((f16*)o.v_cache)[kv + i + half] = from_f32<f16>(v[5]);
   }
 }
-void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, hipStream_t st) {
-  hipLaunchKernelGGL(reduce_qkv_rope_kernel, dim3(M), dim3(256), 0, st, part, ksplit, M, o);
+void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, int row0, hipStream_t st) {
+  hipLaunchKernelGGL(reduce_qkv_rope_kernel, dim3(M), dim3(256), 0, st, part, ksplit, M, o, row0);
 }
 
 }  // namespace vla
