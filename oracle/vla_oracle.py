@@ -44,7 +44,8 @@ returns v, cached == recompute, a hand-worked one-layer model, zeroed output
 projections, zeroed queries (running mean of v), rotary shift invariance,
 causality, batch independence, slimming == masking the full vocabulary, chunk
 log-probability, Gumbel-max statistics, a separate pure-Python loop evaluator,
-and the de-tokeniser's closed form.  Agreement with the paper's *trained*
+the de-tokeniser's closed form, and for the value head: uniform pooling, single
+token, GELU constants, bias and permutation invariance, scalar loops.  Agreement with the paper's *trained*
 policy is parity unpinned: its weights and datasets are not available.
 """
 from __future__ import annotations
@@ -168,6 +169,30 @@ def detokenise(tokens: np.ndarray, n_bins: int, action_dim: int = 1,
     return a
 
 
+def gelu(t: np.ndarray) -> np.ndarray:
+    """Exact GELU: t * Phi(t), Phi the standard normal CDF."""
+    from math import erf, sqrt
+    return t * 0.5 * (1.0 + np.vectorize(erf)(t / sqrt(2.0)))
+
+
+def value_head(hidden: np.ndarray, step_t: int, vw: dict) -> float:
+    """State value from the hidden states of the K action-related positions (Appendix "Value Head
+    Design"): scores e_k = w_attn . h_k + b_attn, weights alpha = softmax_k(e), pooled z = sum_k alpha_k h_k,
+    plus the embedding of the episode step, then Linear(d,d) -> GELU -> Linear(d,1).
+
+    hidden: [K, d] float64 (the last hidden layer's output at the positions that emit the K action
+    tokens; the policy's hidden states are inputs only, nothing flows back).
+    vw: "attn_w" [d], "attn_b" scalar, "step_emb" [n_steps, d], "w1" [d, d] (nn.Linear layout), "b1" [d],
+    "w2" [d], "b2" scalar, in storage dtype or float64."""
+    h = np.asarray(hidden, dtype=np.float64)
+    e = h @ widen(np.asarray(vw["attn_w"])).reshape(-1) + float(widen(np.asarray(vw["attn_b"]).reshape(1))[0])
+    alpha = softmax(e)
+    z = alpha @ h
+    u = z + widen(np.asarray(vw["step_emb"]))[int(step_t)]
+    hid = gelu(widen(np.asarray(vw["w1"])) @ u + widen(np.asarray(vw["b1"])).reshape(-1))
+    return float(widen(np.asarray(vw["w2"])).reshape(-1) @ hid + float(widen(np.asarray(vw["b2"]).reshape(1))[0]))
+
+
 # ----------------------------------------------------------------------------
 # the model
 # ----------------------------------------------------------------------------
@@ -254,6 +279,10 @@ class OraclePolicy:
             head = head[s.vocab - s.n_action_bins:]
         return h @ widen(head).T
 
+    def final_hidden(self, x_last: np.ndarray) -> np.ndarray:
+        """The last hidden layer's output for a row: the residual stream after the final RMSNorm."""
+        return rms_norm(x_last, self.W("final_norm"), self.s.rms_eps)
+
     def full_vocab_logits(self, x_last: np.ndarray) -> np.ndarray:
         h = rms_norm(x_last, self.W("final_norm"), self.s.rms_eps)
         return h @ self.W("lm_head").T
@@ -277,6 +306,7 @@ class OraclePolicy:
         logp = np.zeros((B, n_tokens))
         logits = np.zeros((B, n_tokens, A))
         scores = np.zeros((B, n_tokens, A))
+        hidden = np.zeros((B, n_tokens, s.d_model))
         seqs = [self.prefix_rows(pe, ids) for pe, ids in zip(patch_embs, instr_ids)]
         states = [SeqState(s.n_layers) for _ in range(B)]
         new_rows = seqs
@@ -289,6 +319,7 @@ class OraclePolicy:
             else:
                 raise ValueError(mode)
             z = np.stack([self.action_logits(o[-1]) for o in outs])   # [B, A]
+            hidden[:, k] = np.stack([self.final_hidden(o[-1]) for o in outs])
             logits[:, k] = z
             ell = log_softmax(z, tau)
             fed = []
@@ -300,4 +331,4 @@ class OraclePolicy:
             new_rows = [self.token_rows([s.vocab - A + t]) for t in fed]
             seqs = [np.concatenate([sq, r], axis=0) for sq, r in zip(seqs, new_rows)]
         return {"tokens": tokens, "logp": logp, "actions": bin_centre(tokens, A),
-                "logits": logits, "scores": scores}
+                "logits": logits, "scores": scores, "hidden": hidden}

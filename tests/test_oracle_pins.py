@@ -359,3 +359,68 @@ def test_widen_bf16_and_f32_exact():
     assert O.widen(bits).tolist() == [1.0, -1.0, 1.0078125, 0.0, 3.140625]
     x = np.array([0.1], dtype=np.float32)
     assert O.widen(x)[0] == float(x[0])
+
+
+# ---- value head (attention pooling over the action positions + step embedding + GELU MLP) --------------
+
+def value_weights(d, n_steps=5, seed=0):
+    g = np.random.default_rng(seed)
+    return {"attn_w": g.normal(0, 0.5, d), "attn_b": np.array(0.3), "step_emb": g.normal(0, 0.5, (n_steps, d)),
+            "w1": g.normal(0, 0.4, (d, d)), "b1": g.normal(0, 0.1, d), "w2": g.normal(0, 0.4, d), "b2": np.array(-0.2)}
+
+
+def test_gelu_constants():
+    # Phi(1) = 0.841344746068543, Phi(-1) = 0.158655253931457 (standard normal table)
+    assert O.gelu(np.array([0.0]))[0] == 0.0
+    assert O.gelu(np.array([1.0]))[0] == pytest.approx(0.841344746068543, abs=1e-14)
+    assert O.gelu(np.array([-1.0]))[0] == pytest.approx(-0.158655253931457, abs=1e-14)
+    assert O.gelu(np.array([10.0]))[0] == pytest.approx(10.0, abs=1e-12)
+
+
+def test_value_head_special_cases():
+    d, K = 6, 4
+    g = np.random.default_rng(31)
+    h = g.normal(size=(K, d))
+    vw = value_weights(d)
+    # zero attention projection -> uniform pooling -> the mean of the hidden states
+    vw0 = dict(vw, attn_w=np.zeros(d), w1=np.eye(d), b1=np.zeros(d), w2=np.ones(d), b2=np.array(0.0),
+               step_emb=np.zeros((5, d)))
+    z = h.mean(0)
+    assert O.value_head(h, 2, vw0) == pytest.approx(float(sum(t * 0.5 * (1 + math.erf(t / math.sqrt(2))) for t in z)), abs=1e-13)
+    # one token: the pooled vector is that token whatever the scores
+    v1 = O.value_head(h[:1], 1, vw)
+    u = h[0] + vw["step_emb"][1]
+    hid = [sum(vw["w1"][j, i] * u[i] for i in range(d)) + vw["b1"][j] for j in range(d)]
+    ref = sum(vw["w2"][j] * hid[j] * 0.5 * (1 + math.erf(hid[j] / math.sqrt(2))) for j in range(d)) + float(vw["b2"])
+    assert v1 == pytest.approx(ref, abs=1e-13)
+    # the attention bias shifts every score equally: no effect; token order does not matter
+    assert O.value_head(h, 3, dict(vw, attn_b=np.array(5.0))) == pytest.approx(O.value_head(h, 3, vw), abs=1e-12)
+    assert O.value_head(h[::-1], 3, vw) == pytest.approx(O.value_head(h, 3, vw), abs=1e-12)
+    # the step embedding matters
+    assert abs(O.value_head(h, 0, vw) - O.value_head(h, 4, vw)) > 1e-3
+
+
+def test_value_head_against_scalar_loops():
+    d, K = 5, 3
+    g = np.random.default_rng(32)
+    h = g.normal(size=(K, d))
+    vw = value_weights(d, seed=3)
+    e = [sum(h[k, i] * vw["attn_w"][i] for i in range(d)) + float(vw["attn_b"]) for k in range(K)]
+    m = max(e)
+    a = [math.exp(t - m) for t in e]
+    a = [t / sum(a) for t in a]
+    z = [sum(a[k] * h[k, i] for k in range(K)) + vw["step_emb"][2, i] for i in range(d)]
+    hid = [sum(vw["w1"][j, i] * z[i] for i in range(d)) + vw["b1"][j] for j in range(d)]
+    v = sum(vw["w2"][j] * hid[j] * 0.5 * (1 + math.erf(hid[j] / math.sqrt(2))) for j in range(d)) + float(vw["b2"])
+    assert O.value_head(h, 2, vw) == pytest.approx(v, abs=1e-13)
+
+
+def test_policy_step_returns_the_hidden_rows_that_feed_the_head():
+    s = shape()
+    w = rand_weights(s)
+    pol = O.OraclePolicy(s, w)
+    pes, ids = rand_obs(s, 2, 3, [2, 4])
+    r = pol.policy_step(pes, ids, 3, mode="cached")
+    head = w["lm_head"][s.vocab - s.n_action_bins:]
+    assert r["hidden"].shape == (2, 3, s.d_model)
+    assert np.abs(r["hidden"] @ head.T - r["logits"]).max() < 1e-12
