@@ -64,6 +64,7 @@ typedef struct {
   int32_t dtype;              /* enum vla_dtype */
   int32_t max_batch, max_seq;
   int64_t max_prefill_tokens;
+  int32_t value_max_steps;    /* rows of the value head's step-embedding table; 0 = no value head */
 } vla_config;
 
 /* One named tensor handed to vla_load_weights: device pointer, row-major, nn.Linear layout
@@ -137,6 +138,25 @@ int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_
                     float temperature, const float* gumbel, const float* act_scale,
                     const float* act_offset, int32_t action_dim, int32_t* tokens_out,
                     float* logp_out, float* actions_out, float* logits_out, void* hip_stream);
+
+/* Value head on the rollout path (Appendix "Value Head Design": action-aware attention pooling).  Needs
+ * config.value_max_steps > 0.  vla_load_value_head takes, in the storage dtype, "value.attn_w" [d],
+ * "value.attn_b" [1], "value.step_emb" [value_max_steps, d], "value.w1" [d, d] (nn.Linear layout),
+ * "value.b1" [d], "value.w2" [d], "value.b2" [1]; all must be present exactly once.
+ * vla_policy_step_value is vla_policy_step plus the state value of each observation:
+ *   hidden_k = final RMSNorm output at the position that emits action token k (k = 0..K-1);
+ *   alpha = softmax_k(attn_w . hidden_k + attn_b);  z = sum_k alpha_k hidden_k;
+ *   value = w2 . gelu(w1 (z + step_emb[step_t]) + b1) + b2   (exact erf GELU).
+ *   step_t      device, [B] int32 episode step of each observation (clamped to the table)
+ *   values_out  device, [B] float32
+ * The hidden states are only read: nothing of the value head feeds back into the policy outputs. */
+int vla_load_value_head(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream);
+int vla_policy_step_value(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                          const int32_t* instr_ids, const int32_t* cu_instr, int32_t n_tokens,
+                          float temperature, const float* gumbel, const float* act_scale,
+                          const float* act_offset, int32_t action_dim, const int32_t* step_t,
+                          int32_t* tokens_out, float* logp_out, float* actions_out, float* logits_out,
+                          float* values_out, void* hip_stream);
 
 /* Selection alone, for callers that drive vla_prefill / vla_decode_step themselves:
  * logits [B, n_action_bins] (device) -> bin index, log-prob, action, for token index k of the

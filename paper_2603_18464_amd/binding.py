@@ -13,6 +13,7 @@ STATUS = {0: "VLA_OK", -1: "VLA_E_NULL", -2: "VLA_E_CONFIG", -3: "VLA_E_SHAPE", 
           -5: "VLA_E_STATE", -6: "VLA_E_WEIGHTS", -7: "VLA_E_HIP"}
 EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vla_bind_buffers",
            "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_policy_step", "vla_select",
+           "vla_load_value_head", "vla_policy_step_value",
            "vla_prof_enable", "vla_prof_count", "vla_prof_read"]
 
 
@@ -21,7 +22,7 @@ class vla_config(C.Structure):
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("n_action_bins", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float),
                 ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32),
-                ("max_prefill_tokens", C.c_int64)]
+                ("max_prefill_tokens", C.c_int64), ("value_max_steps", C.c_int32)]
 
 
 class vla_tensor(C.Structure):
@@ -62,6 +63,8 @@ def lib() -> C.CDLL:
         L.vla_prefill.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
         L.vla_decode_step.argtypes = [vp, i32, vp, vp, vp]
         L.vla_policy_step.argtypes = [vp, i32, vp, vp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.vla_load_value_head.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
+        L.vla_policy_step_value.argtypes = [vp, i32, vp, vp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.vla_select.argtypes = [vp, i32, vp, f32, vp, i32, i32, vp, vp, i32, vp, vp, vp, i32, vp, vp]
         L.vla_prof_enable.argtypes = [vp, i32]
         L.vla_prof_count.argtypes = []
@@ -123,6 +126,28 @@ def vla_load_weights(ctx, tensors: Dict[str, "object"], dtype: int, stream: int 
     _check(ctx, lib().vla_load_weights(ctx, arr, len(tensors), stream))
 
 
+def vla_load_value_head(ctx, tensors: Dict[str, "object"], dtype: int, stream: int = 0) -> None:
+    arr = (vla_tensor * len(tensors))()
+    for i, (name, t) in enumerate(tensors.items()):
+        arr[i].name = name.encode()
+        arr[i].dev_ptr = t.data_ptr()
+        arr[i].dtype = dtype
+        arr[i].ndim = t.dim()
+        for j, s in enumerate(t.shape):
+            arr[i].shape[j] = s
+    _check(ctx, lib().vla_load_value_head(ctx, arr, len(tensors), stream))
+
+
+def vla_policy_step_value(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature, gumbel,
+                          act_scale, act_offset, action_dim, step_t, tokens_out, logp_out, actions_out, logits_out,
+                          values_out, stream: int = 0) -> None:
+    _check(ctx, lib().vla_policy_step_value(ctx, B, _ptr(patch_emb), _ptr(cu_patch), _ptr(instr_ids),
+                                            _ptr(cu_instr), n_tokens, temperature, _ptr(gumbel), _ptr(act_scale),
+                                            _ptr(act_offset), action_dim, _ptr(step_t), _ptr(tokens_out),
+                                            _ptr(logp_out), _ptr(actions_out), _ptr(logits_out), _ptr(values_out),
+                                            stream))
+
+
 def vla_prefill(ctx, B, patch_emb, cu_patch: np.ndarray, instr_ids, cu_instr: np.ndarray, logits_out,
                 stream: int = 0) -> None:
     _check(ctx, lib().vla_prefill(ctx, B, _ptr(patch_emb), _ptr(cu_patch), _ptr(instr_ids), _ptr(cu_instr),
@@ -165,22 +190,24 @@ def vla_prof_read(ctx, i: int):
 
 # ---- convenience wrapper: owns the torch buffers ------------------------------------------------------
 
-def make_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int) -> vla_config:
+def make_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, value_max_steps: int = 0) -> vla_config:
     return vla_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
                       shape.n_action_bins, shape.rope_theta, shape.rms_eps,
-                      VLA_BF16 if shape.dtype == "bf16" else VLA_F32, max_batch, max_seq, max_prefill_tokens)
+                      VLA_BF16 if shape.dtype == "bf16" else VLA_F32, max_batch, max_seq, max_prefill_tokens,
+                      value_max_steps)
 
 
 class VlaPolicy:
     """Holds a context plus the torch-allocated arena / KV cache / workspace it is bound to."""
 
-    def __init__(self, shape, max_batch: int, max_seq: int, max_prefill_tokens: int, device="cuda:0"):
+    def __init__(self, shape, max_batch: int, max_seq: int, max_prefill_tokens: int, device="cuda:0",
+                 value_max_steps: int = 0):
         import torch
         self.torch = torch
         self.shape = shape
         self.device = torch.device(device)
         self.dtype_code = VLA_BF16 if shape.dtype == "bf16" else VLA_F32
-        self.cfg = make_config(shape, max_batch, max_seq, max_prefill_tokens)
+        self.cfg = make_config(shape, max_batch, max_seq, max_prefill_tokens, value_max_steps)
         self.ctx = vla_create(self.cfg)
         a, k, w = vla_query_sizes(self.cfg)
         self.sizes = (a, k, w)
@@ -219,6 +246,11 @@ class VlaPolicy:
         vla_load_weights(self.ctx, dev, self.dtype_code, self._stream())
         self.torch.cuda.current_stream(self.device).synchronize()   # sources may now be freed
 
+    def load_value_head(self, weights: Dict[str, "object"]):
+        dev = {n: (self.to_device(t) if isinstance(t, np.ndarray) else t) for n, t in weights.items()}
+        vla_load_value_head(self.ctx, dev, self.dtype_code, self._stream())
+        self.torch.cuda.current_stream(self.device).synchronize()
+
     def prefill(self, patch_emb, cu_patch, instr_ids, cu_instr, want_logits=True):
         torch = self.torch
         B = len(cu_patch) - 1
@@ -235,7 +267,8 @@ class VlaPolicy:
         return out
 
     def policy_step(self, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature=0.0, gumbel=None,
-                    act_scale=None, act_offset=None, action_dim=7, want_logits=False, out=None):
+                    act_scale=None, act_offset=None, action_dim=7, want_logits=False, out=None, step_t=None):
+        """step_t (device int32 [B]) switches the value head on: out["values"] [B] is filled as well."""
         torch = self.torch
         B = len(cu_patch) - 1
         A = self.shape.n_action_bins
@@ -246,6 +279,14 @@ class VlaPolicy:
                 "actions": torch.empty((B, n_tokens), dtype=torch.float32, device=self.device),
                 "logits": torch.empty((B, n_tokens, A), dtype=torch.float32, device=self.device) if want_logits else None,
             }
+        if step_t is not None:
+            if out.get("values") is None:
+                out["values"] = torch.empty((B,), dtype=torch.float32, device=self.device)
+            vla_policy_step_value(self.ctx, B, patch_emb, np.ascontiguousarray(cu_patch, dtype=np.int32), instr_ids,
+                                  np.ascontiguousarray(cu_instr, dtype=np.int32), n_tokens, float(temperature),
+                                  gumbel, act_scale, act_offset, action_dim, step_t, out["tokens"], out["logp"],
+                                  out["actions"], out.get("logits"), out["values"], self._stream())
+            return out
         vla_policy_step(self.ctx, B, patch_emb, np.ascontiguousarray(cu_patch, dtype=np.int32), instr_ids,
                         np.ascontiguousarray(cu_instr, dtype=np.int32), n_tokens, float(temperature), gumbel,
                         act_scale, act_offset, action_dim, out["tokens"], out["logp"], out["actions"],

@@ -24,11 +24,12 @@ struct LayerW {
 };
 struct ArenaLayout {
   size_t embed, g_final, head, total;
+  size_t v_attn_w, v_attn_b, v_step_emb, v_w1, v_b1, v_w2, v_b2;   // value head (only if value_max_steps > 0)
   std::vector<LayerW> layers;
 };
 struct WorkLayout {
   size_t x, hn, q, att, act, scratch, part, rope_cos, rope_sin, tok_seq, tok_pos, tok_src, last_row, seq_len,
-      cu_patch, cu_instr, cur_ids, logits, total;
+      cu_patch, cu_instr, cur_ids, logits, vz, vml, vu, vh, total;
 };
 
 size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
@@ -50,6 +51,15 @@ ArenaLayout arena_layout(const vla_config& c) {
   }
   a.g_final = take(d * 4);
   a.head = take((size_t)c.n_action_bins * d * es);
+  if (c.value_max_steps > 0) {
+    a.v_attn_w = take(d * 4);
+    a.v_attn_b = take(4);
+    a.v_step_emb = take((size_t)c.value_max_steps * d * es);
+    a.v_w1 = take(d * d * es);
+    a.v_b1 = take(d * 4);
+    a.v_w2 = take(d * 4);
+    a.v_b2 = take(4);
+  }
   a.total = off;
   return a;
 }
@@ -90,6 +100,11 @@ WorkLayout work_layout(const vla_config& c) {
   w.cu_instr = take((B + 1) * 4);
   w.cur_ids = take(B * 4);
   w.logits = take(B * (size_t)c.n_action_bins * 4);
+  const size_t vrows = c.value_max_steps > 0 ? B : 0;
+  w.vz = take(vrows * d * 4);
+  w.vml = take(vrows * 2 * 4);
+  w.vu = take(vrows * d * 4);
+  w.vh = take(vrows * d * 4);
   w.total = off;
   return w;
 }
@@ -102,6 +117,7 @@ const char* check_config(const vla_config& c) {
   if (c.dtype != VLA_F32 && c.dtype != VLA_BF16) return "dtype must be VLA_F32 or VLA_BF16";
   if (!(c.rope_theta > 0.f) || !(c.rms_eps >= 0.f)) return "rope_theta must be > 0 and rms_eps >= 0";
   if (c.max_batch <= 0 || c.max_seq <= 0 || c.max_prefill_tokens <= 0) return "capacities must be positive";
+  if (c.value_max_steps < 0) return "value_max_steps must be >= 0";
   if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128 && c.head_dim != 256) return "head_dim must be 32, 64, 128 or 256";
   if (c.d_model % 4) return "d_model must be a multiple of 4";
   if (c.dtype == VLA_BF16) {
@@ -124,7 +140,7 @@ struct vla_ctx {
   char* arena = nullptr;
   char* kv = nullptr;
   char* work = nullptr;
-  bool bound = false, weights = false, tables = false;
+  bool bound = false, weights = false, tables = false, value_weights = false;
   int active_B = 0;                  // batch of the last prefill (0: none)
   int run_B = 0, run_max_len = 0;    // batch and longest prefix of the prefill being enqueued
   std::vector<int32_t> len;          // host copy of the sequence lengths
@@ -371,6 +387,14 @@ void run_head(vla_ctx* ctx, int B, const int32_t* row_index, float* logits, int 
                  at<T>(ctx->arena, ctx->al.head), logits, ld, B, c.d_model, c.n_action_bins, c.rms_eps, st);
 }
 
+// One more row per sequence for the value head's attention pooling: the rows the action head just used.
+void run_value_accumulate(vla_ctx* ctx, int B, const int32_t* row_index, bool first, hipStream_t st) {
+  ProfScope ps(ctx, FAM_HEAD, st);
+  value_accumulate(at<float>(ctx->work, ctx->wl.x), row_index, at<float>(ctx->arena, ctx->al.g_final), ctx->cfg.rms_eps,
+                   at<float>(ctx->arena, ctx->al.v_attn_w), at<float>(ctx->arena, ctx->al.v_attn_b), B, ctx->cfg.d_model,
+                   first, at<float>(ctx->work, ctx->wl.vz), at<float>(ctx->work, ctx->wl.vml), st);
+}
+
 int check_ready(vla_ctx* ctx) {
   if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
   if (!ctx->weights) return fail(ctx, VLA_E_STATE, "weights are not loaded (vla_load_weights)");
@@ -540,6 +564,7 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
   ctx->work = (char*)workspace;
   ctx->bound = true;
   ctx->weights = false;
+  ctx->value_weights = false;
   ctx->tables = false;
   ctx->active_B = 0;
   return VLA_OK;
@@ -681,10 +706,11 @@ int vla_select(vla_ctx* ctx, int32_t B, const float* logits, float temperature, 
   return VLA_OK;
 }
 
-int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
-                    const int32_t* cu_instr, int32_t n_tokens, float temperature, const float* gumbel,
-                    const float* act_scale, const float* act_offset, int32_t action_dim, int32_t* tokens_out,
-                    float* logp_out, float* actions_out, float* logits_out, void* hip_stream) {
+static int policy_step_impl(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                            const int32_t* instr_ids, const int32_t* cu_instr, int32_t n_tokens, float temperature,
+                            const float* gumbel, const float* act_scale, const float* act_offset, int32_t action_dim,
+                            const int32_t* step_t, int32_t* tokens_out, float* logp_out, float* actions_out,
+                            float* logits_out, float* values_out, bool with_value, void* hip_stream) {
   if (!ctx) return VLA_E_NULL;
   int rc = check_ready(ctx);
   if (rc) return rc;
@@ -692,6 +718,11 @@ int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_
   if (n_tokens <= 0) return fail(ctx, VLA_E_SHAPE, "n_tokens must be positive");
   if (!(temperature >= 0.f)) return fail(ctx, VLA_E_SHAPE, "temperature must be >= 0");
   if (action_dim < 0) return fail(ctx, VLA_E_SHAPE, "action_dim must be >= 0");
+  if (with_value) {
+    if (ctx->cfg.value_max_steps <= 0) return fail(ctx, VLA_E_CONFIG, "the context was created without a value head");
+    if (!ctx->value_weights) return fail(ctx, VLA_E_STATE, "value head weights are not loaded (vla_load_value_head)");
+    if (!step_t || !values_out) return fail(ctx, VLA_E_NULL, "step_t / values_out is NULL");
+  }
   int64_t T = 0;
   rc = check_prefill(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, &T);
   if (rc) return rc;
@@ -710,11 +741,96 @@ int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_
     else
       rc = bf ? do_decode<bf16>(ctx, B, cur, lg, ld, st) : do_decode<float>(ctx, B, cur, lg, ld, st);
     if (rc) return rc;
+    if (with_value) run_value_accumulate(ctx, B, k == 0 ? at<int32_t>(ctx->work, ctx->wl.last_row) : nullptr, k == 0, st);
     ProfScope ps(ctx, FAM_HEAD, st);
     select_tokens(lg, ld, B, A, temperature, gumbel, k, n_tokens, act_scale, act_offset, action_dim, tokens_out,
                   logp_out, actions_out, n_tokens, cur, id0, st);
   }
+  if (with_value) {
+    ProfScope ps(ctx, FAM_HEAD, st);
+    const ArenaLayout& a = ctx->al;
+    const WorkLayout& w = ctx->wl;
+    if (bf)
+      value_finish<bf16>(at<float>(ctx->work, w.vz), at<float>(ctx->work, w.vml), at<bf16>(ctx->arena, a.v_step_emb),
+                         c.value_max_steps, step_t, at<bf16>(ctx->arena, a.v_w1), at<float>(ctx->arena, a.v_b1),
+                         at<float>(ctx->arena, a.v_w2), at<float>(ctx->arena, a.v_b2), B, c.d_model,
+                         at<float>(ctx->work, w.vu), at<float>(ctx->work, w.vh), values_out, st);
+    else
+      value_finish<float>(at<float>(ctx->work, w.vz), at<float>(ctx->work, w.vml), at<float>(ctx->arena, a.v_step_emb),
+                          c.value_max_steps, step_t, at<float>(ctx->arena, a.v_w1), at<float>(ctx->arena, a.v_b1),
+                          at<float>(ctx->arena, a.v_w2), at<float>(ctx->arena, a.v_b2), B, c.d_model,
+                          at<float>(ctx->work, w.vu), at<float>(ctx->work, w.vh), values_out, st);
+  }
   HIP_TRY(ctx, hipGetLastError());
+  return VLA_OK;
+}
+
+int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
+                    const int32_t* cu_instr, int32_t n_tokens, float temperature, const float* gumbel,
+                    const float* act_scale, const float* act_offset, int32_t action_dim, int32_t* tokens_out,
+                    float* logp_out, float* actions_out, float* logits_out, void* hip_stream) {
+  return policy_step_impl(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature, gumbel, act_scale,
+                          act_offset, action_dim, nullptr, tokens_out, logp_out, actions_out, logits_out, nullptr,
+                          false, hip_stream);
+}
+
+int vla_policy_step_value(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                          const int32_t* instr_ids, const int32_t* cu_instr, int32_t n_tokens, float temperature,
+                          const float* gumbel, const float* act_scale, const float* act_offset, int32_t action_dim,
+                          const int32_t* step_t, int32_t* tokens_out, float* logp_out, float* actions_out,
+                          float* logits_out, float* values_out, void* hip_stream) {
+  return policy_step_impl(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature, gumbel, act_scale,
+                          act_offset, action_dim, step_t, tokens_out, logp_out, actions_out, logits_out, values_out,
+                          true, hip_stream);
+}
+
+int vla_load_value_head(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  if (!tensors) return fail(ctx, VLA_E_NULL, "tensors is NULL");
+  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
+  const vla_config& c = ctx->cfg;
+  if (c.value_max_steps <= 0) return fail(ctx, VLA_E_CONFIG, "the context was created without a value head");
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t d = c.d_model;
+  static const char* kNames[7] = {"value.attn_w", "value.attn_b", "value.step_emb", "value.w1",
+                                  "value.b1",     "value.w2",     "value.b2"};
+  const int64_t rows[7] = {d, 1, c.value_max_steps, d, d, d, 1}, cols[7] = {0, 0, d, d, 0, 0, 0};
+  const vla_tensor* slot[7] = {};
+  for (int i = 0; i < n_tensors; ++i) {
+    const vla_tensor& t = tensors[i];
+    if (!t.name || !t.dev_ptr) return fail(ctx, VLA_E_NULL, "tensor %d has a NULL name or pointer", i);
+    int s = -1;
+    for (int k = 0; k < 7; ++k)
+      if (!strcmp(t.name, kNames[k])) s = k;
+    if (s < 0) return fail(ctx, VLA_E_WEIGHTS, "unknown tensor name '%s'", t.name);
+    if (slot[s]) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' given twice", t.name);
+    if (t.dtype != c.dtype) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' has dtype %d, config has %d", t.name, t.dtype, c.dtype);
+    const bool ok = cols[s] ? (t.ndim == 2 && t.shape[0] == rows[s] && t.shape[1] == cols[s])
+                            : (t.ndim == 1 && t.shape[0] == rows[s]);
+    if (!ok) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' has the wrong shape", t.name);
+    slot[s] = &t;
+  }
+  for (int k = 0; k < 7; ++k)
+    if (!slot[k]) return fail(ctx, VLA_E_WEIGHTS, "missing tensor '%s'", kNames[k]);
+  const ArenaLayout& a = ctx->al;
+  const bool bf = c.dtype == VLA_BF16;
+  auto to_f32_vec = [&](const vla_tensor* t, size_t off, size_t n) {
+    if (bf) convert_copy<bf16>((const bf16*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
+    else convert_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
+  };
+  auto raw = [&](const vla_tensor* t, size_t off, size_t n) {
+    if (bf) plain_copy<bf16>((const bf16*)t->dev_ptr, at<bf16>(ctx->arena, off), n, st);
+    else plain_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
+  };
+  to_f32_vec(slot[0], a.v_attn_w, d);
+  to_f32_vec(slot[1], a.v_attn_b, 1);
+  raw(slot[2], a.v_step_emb, (size_t)c.value_max_steps * d);
+  raw(slot[3], a.v_w1, (size_t)d * d);
+  to_f32_vec(slot[4], a.v_b1, d);
+  to_f32_vec(slot[5], a.v_w2, d);
+  to_f32_vec(slot[6], a.v_b2, 1);
+  HIP_TRY(ctx, hipGetLastError());
+  ctx->value_weights = true;
   return VLA_OK;
 }
 

@@ -145,6 +145,14 @@ void select_tokens(const float* logits, int ld_logits, int B, int A, float tempe
                    int32_t* tokens_out, float* logp_out, float* actions_out, int out_stride,
                    int32_t* next_ids, int id0, hipStream_t st);
 
+// Value head (attention pooling over the rows that feed the action head, step embedding, GELU MLP).
+void value_accumulate(const float* x, const int32_t* row_index, const float* gain, float eps, const float* attn_w,
+                      const float* attn_b, int B, int d, bool first, float* vz, float* vml, hipStream_t st);
+template <class T>
+void value_finish(const float* vz, const float* vml, const T* step_emb, int n_steps, const int32_t* step_t,
+                  const T* w1, const float* b1, const float* w2, const float* b2, int B, int d, float* vu, float* vh,
+                  float* values, hipStream_t st);
+
 // Small utilities.
 void rope_table(float* cos_t, float* sin_t, int max_seq, int head_dim, float theta, hipStream_t st);
 void build_token_maps(const int32_t* cu_patch_dev, const int32_t* cu_instr_dev, int B, int T_tokens,

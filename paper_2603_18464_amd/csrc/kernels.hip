@@ -240,6 +240,105 @@ template void head_logits<float>(const float*, const int32_t*, const float*, con
 template void head_logits<bf16>(const float*, const int32_t*, const float*, const bf16*, float*, int, int, int,
                                 int, float, hipStream_t);
 
+// ---- value head ---------------------------------------------------------------------------------------
+// Action-aware attention pooling over the K hidden rows that feed the action head, done online: after
+// each head evaluation the row's score e = w_attn . h + b_attn updates a running softmax-weighted sum
+// (m, l, z) per sequence, so no hidden state is stored.  h is the final-RMSNorm output in float32.
+__global__ __launch_bounds__(256) void value_accumulate_kernel(const float* __restrict__ x,
+                                                               const int32_t* __restrict__ row_index,
+                                                               const float* __restrict__ gain, float eps,
+                                                               const float* __restrict__ attn_w,
+                                                               const float* __restrict__ attn_b, int d, int first,
+                                                               float* __restrict__ vz, float* __restrict__ vml) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  const float* row = x + (size_t)(row_index ? row_index[b] : b) * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) ss += row[i] * row[i];
+  ss = block_sum_256(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  float e = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) e += row[i] * inv * gain[i] * attn_w[i];
+  e = block_sum_256(e, red) + attn_b[0];
+  const float m_old = first ? -INFINITY : vml[2 * b], l_old = first ? 0.f : vml[2 * b + 1];
+  const float m_new = fmaxf(m_old, e);
+  const float scale = first ? 0.f : expf(m_old - m_new), p = expf(e - m_new);
+  float* z = vz + (size_t)b * d;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float h = row[i] * inv * gain[i];
+    z[i] = (first ? 0.f : z[i] * scale) + p * h;
+  }
+  __syncthreads();                       // every thread has read the old statistics
+  if (threadIdx.x == 0) {
+    vml[2 * b] = m_new;
+    vml[2 * b + 1] = l_old * scale + p;
+  }
+}
+void value_accumulate(const float* x, const int32_t* row_index, const float* gain, float eps, const float* attn_w,
+                      const float* attn_b, int B, int d, bool first, float* vz, float* vml, hipStream_t st) {
+  hipLaunchKernelGGL(value_accumulate_kernel, dim3(B), dim3(256), 0, st, x, row_index, gain, eps, attn_w, attn_b, d,
+                     first ? 1 : 0, vz, vml);
+}
+
+// u[b] = z[b] / l[b] + step_emb[step_t[b]]   (step clamped to the table)
+template <class T>
+__global__ __launch_bounds__(256) void value_pool_kernel(const float* __restrict__ vz, const float* __restrict__ vml,
+                                                         const T* __restrict__ step_emb, int n_steps,
+                                                         const int32_t* __restrict__ step_t, int d,
+                                                         float* __restrict__ vu) {
+  const int b = blockIdx.x;
+  int t = step_t[b];
+  t = t < 0 ? 0 : (t >= n_steps ? n_steps - 1 : t);
+  const float inv_l = 1.0f / vml[2 * b + 1];
+  for (int i = threadIdx.x; i < d; i += 256)
+    vu[(size_t)b * d + i] = vz[(size_t)b * d + i] * inv_l + to_f32(step_emb[(size_t)t * d + i]);
+}
+
+// vh[b][j] = w2[j] * gelu(W1[j,:] . u[b] + b1[j]); one wave per output row j, the row kept in registers.
+template <class T>
+__global__ __launch_bounds__(256) void value_mlp_kernel(const T* __restrict__ w1, const float* __restrict__ b1,
+                                                        const float* __restrict__ w2, const float* __restrict__ vu,
+                                                        int B, int d, float* __restrict__ vh) {
+  const int lane = threadIdx.x & 63, j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= d) return;
+  const T* wr = w1 + (size_t)j * d;
+  for (int b = 0; b < B; ++b) {
+    const float* u = vu + (size_t)b * d;
+    float acc = 0.f;
+    for (int i = lane; i < d; i += 64) acc = fmaf(to_f32(wr[i]), u[i], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      const float t = acc + b1[j];
+      vh[(size_t)b * d + j] = w2[j] * 0.5f * t * (1.0f + erff(t * 0.70710678118654752f));
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void value_sum_kernel(const float* __restrict__ vh, const float* __restrict__ b2,
+                                                        int d, float* __restrict__ values) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) s += vh[(size_t)b * d + i];
+  s = block_sum_256(s, red);
+  if (threadIdx.x == 0) values[b] = s + b2[0];
+}
+
+template <class T>
+void value_finish(const float* vz, const float* vml, const T* step_emb, int n_steps, const int32_t* step_t,
+                  const T* w1, const float* b1, const float* w2, const float* b2, int B, int d, float* vu, float* vh,
+                  float* values, hipStream_t st) {
+  hipLaunchKernelGGL(value_pool_kernel<T>, dim3(B), dim3(256), 0, st, vz, vml, step_emb, n_steps, step_t, d, vu);
+  hipLaunchKernelGGL(value_mlp_kernel<T>, dim3((d + 3) / 4), dim3(256), 0, st, w1, b1, w2, vu, B, d, vh);
+  hipLaunchKernelGGL(value_sum_kernel, dim3(B), dim3(256), 0, st, vh, b2, d, values);
+}
+template void value_finish<float>(const float*, const float*, const float*, int, const int32_t*, const float*,
+                                  const float*, const float*, const float*, int, int, float*, float*, float*,
+                                  hipStream_t);
+template void value_finish<bf16>(const float*, const float*, const bf16*, int, const int32_t*, const bf16*,
+                                 const float*, const float*, const float*, int, int, float*, float*, float*,
+                                 hipStream_t);
+
 // ---- selection ----------------------------------------------------------------------------------------
 // One wave per sequence: scores = logits / tau (+ Gumbel noise); token = lowest index among the
 // maxima; log-prob = log_softmax(logits / tau)[token]; action = bin centre (optionally affine).

@@ -140,6 +140,108 @@ def test_7b_workloads_against_stored_oracle_rows(name):
     pol.close()
 
 
+def _value_case(wl, obs, gumbel, n_steps, tol):
+    """values from vla_policy_step_value against the oracle's value head on the oracle's own hidden rows
+    (oracle forced onto the GPU's tokens so that near-ties cannot fork the two)."""
+    import torch
+    from oracle import vla_oracle as O
+    weights = W.make_weights(wl.shape, wl.seed)
+    vw = W.make_value_weights(wl.shape, wl.seed, n_steps)
+    B = wl.batch
+    pol = VlaPolicyWithValue(wl, weights, vw, n_steps)
+    dev = P.device_inputs(pol, obs, gumbel)
+    temp = wl.temperature if wl.sampling == "gumbel" else 0.0
+    step_np = (np.arange(B, dtype=np.int32) * 3) % n_steps
+    step_t = torch.from_numpy(step_np).to(pol.device)
+    args = (dev["patch_emb"], obs["cu_patch"], dev["instr_ids"], obs["cu_instr"], wl.n_tokens)
+    kw = dict(temperature=temp, gumbel=dev["gumbel"], action_dim=wl.action_dim, want_logits=True)
+    plain = P.to_numpy(pol.policy_step(*args, **kw))
+    both = pol.policy_step(*args, step_t=step_t, **kw)
+    torch.cuda.synchronize()
+    values = both.pop("values").cpu().numpy()
+    both = P.to_numpy(both)
+    for k in ("tokens", "logp", "actions", "logits"):      # the value head only reads
+        assert np.array_equal(plain[k], both[k]), k
+    pes, ids = P.split_obs(obs, list(range(B)))
+    ora = O.OraclePolicy(wl.shape, weights).policy_step(pes, ids, wl.n_tokens, temperature=temp, gumbel=gumbel,
+                                                        mode="cached", forced_tokens=both["tokens"])
+    ovw = {k.split(".", 1)[1]: v for k, v in vw.items()}
+    want = np.array([O.value_head(ora["hidden"][b], int(step_np[b]), ovw) for b in range(B)])
+    err = float(np.abs(values - want).max())
+    print(f"\n[{wl.name}] value head: max err {err:.3e}, |value| up to {np.abs(want).max():.3e}")
+    assert np.abs(want).max() > 10 * tol          # the comparison is not vacuous
+    assert err <= tol
+    # a second call with other step indices changes only the values, by the step embedding's effect
+    step2 = torch.from_numpy(((step_np + 1) % n_steps).astype(np.int32)).to(pol.device)
+    v2 = pol.policy_step(*args, step_t=step2, **kw)["values"].cpu().numpy()
+    want2 = np.array([O.value_head(ora["hidden"][b], int((step_np[b] + 1) % n_steps), ovw) for b in range(B)])
+    assert float(np.abs(v2 - want2).max()) <= tol
+    pol.close()
+
+
+def VlaPolicyWithValue(wl, weights, vw, n_steps):
+    from paper_2603_18464_amd import VlaPolicy
+    B = wl.batch
+    pol = VlaPolicy(wl.shape, B, wl.max_seq, B * (wl.n_patches + wl.instr_len[1]), value_max_steps=n_steps)
+    pol.load_weights(weights)
+    pol.load_value_head(vw)
+    return pol
+
+
+def test_value_head_fp32():
+    wl = W.get_workload("C1")
+    _value_case(wl, W.make_observations(wl), None, n_steps=11, tol=1e-5)
+
+
+def test_value_head_bf16_ragged_sampling():
+    shape = W.PolicyShape(2, 256, 2, 128, 704, 1024, dtype="bf16")
+    lens = [0, 3, 17, 40, 9, 0, 25]
+    nps = [1, 80, 80, 80, 80, 80, 64]
+    wl = W.Workload("Tv", 9, shape, batch=len(lens), n_patches=80, instr_len=(0, 40), n_tokens=5,
+                    sampling="gumbel", temperature=1.1)
+    obs = ragged_obs(wl, nps, lens, seed=79)
+    _value_case(wl, obs, W.make_gumbel(wl), n_steps=7, tol=2e-3)
+
+
+@pytest.mark.timeout(600)
+def test_value_head_c2():
+    wl = W.get_workload("C2")
+    _value_case(wl, W.make_observations(wl), None, n_steps=64, tol=2e-3)
+
+
+def test_value_head_error_paths():
+    from paper_2603_18464_amd import VlaPolicy, VlaError
+    import torch
+    wl = W.get_workload("C1")
+    weights = W.make_weights(wl.shape, wl.seed)
+    vw = W.make_value_weights(wl.shape, wl.seed, 4)
+    obs = W.make_observations(wl)
+    B = wl.batch
+    pol = VlaPolicy(wl.shape, B, wl.max_seq, B * (wl.n_patches + wl.instr_len[1]))
+    pol.load_weights(weights)
+    with pytest.raises(VlaError):
+        pol.load_value_head(vw)                       # context has no value head
+    pol.close()
+    pol = VlaPolicy(wl.shape, B, wl.max_seq, B * (wl.n_patches + wl.instr_len[1]), value_max_steps=4)
+    pol.load_weights(weights)
+    dev = P.device_inputs(pol, obs)
+    step_t = torch.zeros(B, dtype=torch.int32, device=pol.device)
+    args = (dev["patch_emb"], obs["cu_patch"], dev["instr_ids"], obs["cu_instr"], wl.n_tokens)
+    with pytest.raises(VlaError):
+        pol.policy_step(*args, step_t=step_t)         # value weights not loaded yet
+    bad = dict(vw)
+    bad.pop("value.b2")
+    with pytest.raises(VlaError):
+        pol.load_value_head(bad)
+    bad = dict(vw, **{"value.w1": vw["value.w1"][:-1]})
+    with pytest.raises(VlaError):
+        pol.load_value_head(bad)
+    pol.load_value_head(vw)
+    pol.policy_step(*args, step_t=step_t)
+    torch.cuda.synchronize()
+    pol.close()
+
+
 def test_policy_step_is_deterministic_and_matches_stepwise_calls():
     """Two identical policy steps give bit-identical outputs; prefill + select + decode_step called
     one by one reproduce vla_policy_step."""

@@ -9,5 +9,5 @@ from it without sharing any code of the method itself.
 from .configs import PolicyShape, Workload, WORKLOADS, get_workload  # noqa: F401
 from .generate import (  # noqa: F401
     bf16_bits_from_f32, f32_from_bf16_bits, tensor_rng, weight_names,
-    make_weights, make_observations, make_gumbel, weight_shape,
+    make_weights, make_observations, make_gumbel, weight_shape, make_value_weights,
 )

@@ -115,3 +115,15 @@ def make_gumbel(wl: Workload) -> np.ndarray:
     u = tensor_rng(wl.seed, "gumbel").random((wl.batch, wl.n_tokens, A), dtype=np.float32)
     u = np.clip(u.astype(np.float64), 2.0 ** -24, 1.0 - 2.0 ** -24)
     return (-np.log(-np.log(u))).astype(np.float32)
+
+
+def make_value_weights(shape: PolicyShape, seed: int, n_steps: int) -> Dict[str, np.ndarray]:
+    """Synthetic value-head weights in the storage dtype: every tensor N(0, 0.02^2)."""
+    d = shape.d_model
+    shapes = {"value.attn_w": (d,), "value.attn_b": (1,), "value.step_emb": (n_steps, d), "value.w1": (d, d),
+              "value.b1": (d,), "value.w2": (d,), "value.b2": (1,)}
+    out = {}
+    for name, shp in shapes.items():
+        x = tensor_rng(seed, name).standard_normal(shp, dtype=np.float32) * np.float32(WEIGHT_STD)
+        out[name] = _store(x, shape.dtype)
+    return out
