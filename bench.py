@@ -71,6 +71,46 @@ def cpu_baseline(wl, weights_fn, obs, sample_layers):
                       f"{dt:.1f} s measured, scaled linearly to all layers"}
 
 
+def weight_update_leg(pol, weights, step, torch):
+    """In-place update of every tensor from device-resident sources (what a broadcast leaves on the inference
+    GPU), enqueued on a second stream: device time with the policy idle, and host-observed latency from the drain
+    signal to the new version being live when a policy step was enqueued just before.  Same weights are written
+    back, so the benchmark's state is unchanged.  Outside the timed region of `value`."""
+    dev_w = {n: pol.to_device(t) for n, t in weights.items()}
+    nbytes = sum(t.numel() * t.element_size() for t in dev_w.values())
+    side = torch.cuda.Stream(device=pol.device)
+    torch.cuda.synchronize()
+    res = {}
+    idle, busy = [], []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pol.drain_begin()
+        pol.update_begin(side)
+        e0.record(side)
+        pol.update_tensors(dev_w, side)
+        pol.update_commit(side)
+        e1.record(side)
+        side.synchronize()
+        idle.append(e0.elapsed_time(e1))
+    for _ in range(3):
+        step()                                   # a whole policy step is in flight when the drain signal comes
+        t0 = time.perf_counter()
+        pol.drain_begin()
+        pol.update_begin(side)
+        pol.update_tensors(dev_w, side)
+        pol.update_commit(side)
+        side.synchronize()
+        busy.append((time.perf_counter() - t0) * 1e3)
+    torch.cuda.synchronize()
+    res["tensors"] = len(dev_w)
+    res["source_bytes"] = nbytes
+    res["device_ms_idle"] = min(idle)
+    res["gbs_read_plus_write"] = 2 * nbytes / (min(idle) * 1e-3) / 1e9
+    res["drain_to_live_ms_with_step_in_flight"] = min(busy)
+    res["version"] = pol.state()[1]
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +121,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--prof-mask", type=lambda v: int(v, 0), default=0x1fff)
+    ap.add_argument("--no-weight-update", action="store_true",
+                    help="skip the (untimed, reported under detail) in-place weight update measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the policy shards by "
@@ -102,7 +144,8 @@ def main():
     nums = model_numbers(wl, cu_seq)
     pol = VlaPolicy(wl.shape, wl.batch, wl.max_seq, nums["T"])
     pol.load_weights(weights)
-    del weights
+    if args.no_weight_update:
+        del weights
     pe = pol.to_device(obs["patch_emb"])
     ids = torch.from_numpy(obs["instr_ids"]).to(pol.device)
     gdev = None if gum is None else torch.from_numpy(gum).to(pol.device)
@@ -142,7 +185,7 @@ def main():
     roofline = None
     if g:
         ach = nums["gateup_flops"] / (g["avg_ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_f16_kernel<256,256,4,2,EpiSwiglu> (prefill gate/up GEMM)",
+        roofline = {"bound": "mfma", "kernel": "gemm_f16_pipe_kernel<EpiSwiglu> (prefill gate/up GEMM)",
                     "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
                     "avg_launch_ms": g["avg_ms"], "flops_per_launch": nums["gateup_flops"],
                     "traffic": measured_traffic("gemm_gateup_prefill", wl.name)}
@@ -160,6 +203,9 @@ def main():
         extra["decode_ms_per_token_step"] = dec_ms / max(1, wl.n_tokens - 1)
     extra["prefill_kernels_ms"] = pre_ms
     extra["families"] = fam
+    if not args.no_weight_update:
+        extra["weight_update"] = weight_update_leg(pol, weights, step, torch)
+        del weights
 
     line = {
         "metric": "actions/sec of the batched VLA policy step (prefill + action-token decode + log-probs)",

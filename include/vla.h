@@ -51,8 +51,12 @@ enum vla_status {
   VLA_E_CAPACITY = -4,  /* max_batch, max_seq or max_prefill_tokens would be exceeded */
   VLA_E_STATE = -5,     /* call out of order (buffers not bound, weights not loaded, no prefill) */
   VLA_E_WEIGHTS = -6,   /* missing, duplicate or mis-shaped tensor in vla_load_weights */
-  VLA_E_HIP = -7        /* a HIP runtime call failed */
+  VLA_E_HIP = -7,       /* a HIP runtime call failed */
+  VLA_E_DRAINING = -8   /* refused because a weight update is pending or open (see vla_drain_begin) */
 };
+
+/* Serving state of a context with respect to weight updates (vla_get_state). */
+enum vla_serving_state { VLA_ACCEPTING = 0, VLA_DRAINING = 1, VLA_UPDATING = 2 };
 
 /* Plain data, copied by vla_create.  Requirements: n_heads * head_dim == d_model; head_dim is 64
  * or 128 for VLA_BF16 (32, 64, 128 or 256 for VLA_F32); d_model a multiple of 128 and d_ffn of 64
@@ -94,9 +98,10 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
  * "layers.<l>.attn_norm" [d], ".wq" ".wk" ".wv" ".wo" [d,d], ".ffn_norm" [d], ".w_gate" ".w_up"
  * [f,d], ".w_down" [d,f]; "final_norm" [d]; "lm_head" [V,d] or already slimmed [A,d].  All must
  * be present exactly once.  Sources may be freed once the stream has completed.  Calling it again
- * overwrites the live weights in place, which is the paper's in-place weight update on the
- * inference GPU (Appendix "High-Performance NCCL-based Weight Synchronization"); the caller must
- * not have a policy step in flight on another stream (the paper's drain). */
+ * replaces the whole set in place as one step: the copies wait, on the device, for every compute
+ * call enqueued before, later compute calls wait for the copies, the version counter goes up and the
+ * batch in flight is dropped (its cached keys and values belong to the old weights).  Refused with
+ * VLA_E_DRAINING while an update opened by vla_update_begin is not committed. */
 int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream);
 
 /* Prefill: sequence slot b (0 <= b < B) gets the prefix
@@ -157,6 +162,33 @@ int vla_policy_step_value(vla_ctx* ctx, int32_t B, const void* patch_emb, const 
                           const float* act_offset, int32_t action_dim, const int32_t* step_t,
                           int32_t* tokens_out, float* logp_out, float* actions_out, float* logits_out,
                           float* values_out, void* hip_stream);
+
+/* In-place weight update with an early drain (Appendix "High-Performance NCCL-based Weight
+ * Synchronization": the received tensors overwrite the inference weights in place, and a drain signal,
+ * sent well before the new parameters are ready, makes the worker stop scheduling new batches, finish
+ * what is running and only then switch to receiving).  On this boundary the received tensors are device
+ * buffers (what a broadcast leaves on the inference GPU) and "overwrite" re-encodes them into the arena.
+ *
+ *   state      accepting --vla_drain_begin--> draining --vla_update_begin--> updating --vla_update_commit--> accepting
+ *   accepting  every call allowed.
+ *   draining   vla_prefill / vla_policy_step(_value) return VLA_E_DRAINING (no new batch); vla_decode_step
+ *              and vla_select of the batch in flight still run, so it can be finished.
+ *   updating   every compute call returns VLA_E_DRAINING; vla_update_tensors may be called any number of
+ *              times, each with any subset of the tensor names of vla_load_weights / vla_load_value_head
+ *              (same layouts, each name at most once per call), e.g. one call per received bucket.
+ *
+ * vla_drain_begin touches host state only and may be repeated.  vla_update_begin (allowed from accepting
+ * too) makes `hip_stream` wait on the device for every compute call enqueued so far, so the overwrite can
+ * be enqueued at once on a second stream without a host synchronisation, and drops the batch in flight.
+ * vla_update_commit records the end of the update on `hip_stream`, adds one to the version and returns it;
+ * every later compute call first makes its own stream wait for that point.  Hence no compute call ever
+ * reads tensors of two versions, whichever streams are used.  Compute calls themselves are expected on
+ * one stream at a time (they share the workspace). */
+int vla_get_state(const vla_ctx* ctx, int32_t* state /* enum vla_serving_state */, int64_t* version);
+int vla_drain_begin(vla_ctx* ctx);
+int vla_update_begin(vla_ctx* ctx, void* hip_stream);
+int vla_update_tensors(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream);
+int vla_update_commit(vla_ctx* ctx, void* hip_stream, int64_t* version_out);
 
 /* Selection alone, for callers that drive vla_prefill / vla_decode_step themselves:
  * logits [B, n_action_bins] (device) -> bin index, log-prob, action, for token index k of the

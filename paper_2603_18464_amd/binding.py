@@ -10,10 +10,13 @@ import numpy as np
 
 VLA_F32, VLA_BF16 = 0, 1
 STATUS = {0: "VLA_OK", -1: "VLA_E_NULL", -2: "VLA_E_CONFIG", -3: "VLA_E_SHAPE", -4: "VLA_E_CAPACITY",
-          -5: "VLA_E_STATE", -6: "VLA_E_WEIGHTS", -7: "VLA_E_HIP"}
+          -5: "VLA_E_STATE", -6: "VLA_E_WEIGHTS", -7: "VLA_E_HIP", -8: "VLA_E_DRAINING"}
+VLA_E_STATE, VLA_E_DRAINING = -5, -8
+VLA_ACCEPTING, VLA_DRAINING, VLA_UPDATING = 0, 1, 2
 EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vla_bind_buffers",
            "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_policy_step", "vla_select",
            "vla_load_value_head", "vla_policy_step_value",
+           "vla_get_state", "vla_drain_begin", "vla_update_begin", "vla_update_tensors", "vla_update_commit",
            "vla_prof_enable", "vla_prof_count", "vla_prof_read"]
 
 
@@ -65,6 +68,11 @@ def lib() -> C.CDLL:
         L.vla_policy_step.argtypes = [vp, i32, vp, vp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         L.vla_load_value_head.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
         L.vla_policy_step_value.argtypes = [vp, i32, vp, vp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.vla_get_state.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]
+        L.vla_drain_begin.argtypes = [vp]
+        L.vla_update_begin.argtypes = [vp, vp]
+        L.vla_update_tensors.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
+        L.vla_update_commit.argtypes = [vp, vp, C.POINTER(C.c_int64)]
         L.vla_select.argtypes = [vp, i32, vp, f32, vp, i32, i32, vp, vp, i32, vp, vp, vp, i32, vp, vp]
         L.vla_prof_enable.argtypes = [vp, i32]
         L.vla_prof_count.argtypes = []
@@ -126,8 +134,8 @@ def vla_load_weights(ctx, tensors: Dict[str, "object"], dtype: int, stream: int 
     _check(ctx, lib().vla_load_weights(ctx, arr, len(tensors), stream))
 
 
-def vla_load_value_head(ctx, tensors: Dict[str, "object"], dtype: int, stream: int = 0) -> None:
-    arr = (vla_tensor * len(tensors))()
+def _tensor_array(tensors: Dict[str, "object"], dtype: int):
+    arr = (vla_tensor * max(len(tensors), 1))()
     for i, (name, t) in enumerate(tensors.items()):
         arr[i].name = name.encode()
         arr[i].dev_ptr = t.data_ptr()
@@ -135,7 +143,35 @@ def vla_load_value_head(ctx, tensors: Dict[str, "object"], dtype: int, stream: i
         arr[i].ndim = t.dim()
         for j, s in enumerate(t.shape):
             arr[i].shape[j] = s
-    _check(ctx, lib().vla_load_value_head(ctx, arr, len(tensors), stream))
+    return arr
+
+
+def vla_load_value_head(ctx, tensors: Dict[str, "object"], dtype: int, stream: int = 0) -> None:
+    _check(ctx, lib().vla_load_value_head(ctx, _tensor_array(tensors, dtype), len(tensors), stream))
+
+
+def vla_get_state(ctx):
+    st, ver = C.c_int32(), C.c_int64()
+    _check(ctx, lib().vla_get_state(ctx, C.byref(st), C.byref(ver)))
+    return st.value, ver.value
+
+
+def vla_drain_begin(ctx) -> None:
+    _check(ctx, lib().vla_drain_begin(ctx))
+
+
+def vla_update_begin(ctx, stream: int = 0) -> None:
+    _check(ctx, lib().vla_update_begin(ctx, stream))
+
+
+def vla_update_tensors(ctx, tensors: Dict[str, "object"], dtype: int, stream: int = 0) -> None:
+    _check(ctx, lib().vla_update_tensors(ctx, _tensor_array(tensors, dtype), len(tensors), stream))
+
+
+def vla_update_commit(ctx, stream: int = 0) -> int:
+    ver = C.c_int64()
+    _check(ctx, lib().vla_update_commit(ctx, stream, C.byref(ver)))
+    return ver.value
 
 
 def vla_policy_step_value(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature, gumbel,
@@ -250,6 +286,23 @@ class VlaPolicy:
         dev = {n: (self.to_device(t) if isinstance(t, np.ndarray) else t) for n, t in weights.items()}
         vla_load_value_head(self.ctx, dev, self.dtype_code, self._stream())
         self.torch.cuda.current_stream(self.device).synchronize()
+
+    # In-place weight update: drain, then overwrite on `stream` (a torch stream, default: the current one).
+    def state(self):
+        return vla_get_state(self.ctx)
+
+    def drain_begin(self):
+        vla_drain_begin(self.ctx)
+
+    def update_begin(self, stream=None):
+        vla_update_begin(self.ctx, stream.cuda_stream if stream is not None else self._stream())
+
+    def update_tensors(self, tensors: Dict[str, "object"], stream=None):
+        """tensors: name -> device tensor in storage dtype (they must stay alive until the stream has passed them)."""
+        vla_update_tensors(self.ctx, tensors, self.dtype_code, stream.cuda_stream if stream is not None else self._stream())
+
+    def update_commit(self, stream=None) -> int:
+        return vla_update_commit(self.ctx, stream.cuda_stream if stream is not None else self._stream())
 
     def prefill(self, patch_emb, cu_patch, instr_ids, cu_instr, want_logits=True):
         torch = self.torch

@@ -141,6 +141,12 @@ struct vla_ctx {
   char* kv = nullptr;
   char* work = nullptr;
   bool bound = false, weights = false, tables = false, value_weights = false;
+  // serving state of the in-place weight update (accepting -> draining -> updating -> accepting)
+  int serving = VLA_ACCEPTING;
+  int64_t version = 0;               // bumped by every completed load / update
+  hipEvent_t ev_work = nullptr;      // recorded after the last compute call, on its stream
+  hipEvent_t ev_update = nullptr;    // recorded when the last load / update was committed, on its stream
+  bool have_work = false, have_update = false;
   int active_B = 0;                  // batch of the last prefill (0: none)
   int run_B = 0, run_max_len = 0;    // batch and longest prefix of the prefill being enqueued
   std::vector<int32_t> len;          // host copy of the sequence lengths
@@ -401,6 +407,27 @@ int check_ready(vla_ctx* ctx) {
   return VLA_OK;
 }
 
+// Gate of every compute call.  A new batch is refused from the moment a drain was requested; steps of
+// the batch in flight still run while draining; nothing runs while tensors are being overwritten.  The
+// stream is made to wait (on the device) for the last committed update, whatever stream that ran on.
+int check_serving(vla_ctx* ctx, bool new_batch) {
+  if (ctx->serving == VLA_UPDATING) return fail(ctx, VLA_E_DRAINING, "weights are being updated (vla_update_commit ends it)");
+  if (ctx->serving == VLA_DRAINING && new_batch)
+    return fail(ctx, VLA_E_DRAINING, "draining for a weight update: no new batch is accepted");
+  return VLA_OK;
+}
+
+int enter_compute(vla_ctx* ctx, hipStream_t st) {
+  if (ctx->have_update) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->ev_update, 0));
+  return VLA_OK;
+}
+
+int leave_compute(vla_ctx* ctx, hipStream_t st) {
+  HIP_TRY(ctx, hipEventRecord(ctx->ev_work, st));
+  ctx->have_work = true;
+  return VLA_OK;
+}
+
 // Validates a prefill request and returns the packed token count.
 int check_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
                   const int32_t* instr_ids, const int32_t* cu_instr, int extra_positions, int64_t* T_out) {
@@ -533,6 +560,8 @@ int vla_destroy(vla_ctx* ctx) {
   if (ctx->stage) (void)hipHostFree(ctx->stage);
   for (int i = 0; i < vla_ctx::kRing; ++i)
     if (ctx->stage_ev[i]) (void)hipEventDestroy(ctx->stage_ev[i]);
+  if (ctx->ev_work) (void)hipEventDestroy(ctx->ev_work);
+  if (ctx->ev_update) (void)hipEventDestroy(ctx->ev_update);
   for (auto& v : ctx->prof)
     for (auto& p : v) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   delete ctx;
@@ -558,6 +587,8 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
   if (!ctx->stage) {
     HIP_TRY(ctx, hipHostMalloc((void**)&ctx->stage, (size_t)vla_ctx::kRing * 2 * (ctx->cfg.max_batch + 1) * sizeof(int32_t), hipHostMallocDefault));
     for (int i = 0; i < vla_ctx::kRing; ++i) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming));
+    HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_work, hipEventDisableTiming));
+    HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_update, hipEventDisableTiming));
   }
   ctx->arena = (char*)weight_arena;
   ctx->kv = (char*)kv;
@@ -567,20 +598,38 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
   ctx->value_weights = false;
   ctx->tables = false;
   ctx->active_B = 0;
+  ctx->serving = VLA_ACCEPTING;
+  ctx->have_work = ctx->have_update = false;
   return VLA_OK;
 }
 
-int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream) {
-  if (!ctx) return VLA_E_NULL;
-  if (!tensors) return fail(ctx, VLA_E_NULL, "tensors is NULL");
-  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
+}  // extern "C"
+
+namespace {
+
+const char* const kLeaves[9] = {"attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"};
+const char* const kValueNames[7] = {"value.attn_w", "value.attn_b", "value.step_emb", "value.w1",
+                                    "value.b1",     "value.w2",     "value.b2"};
+
+// Tensor slots: 0 embed, 1 final_norm, 2 lm_head, 3 + 9*l + leaf, then the seven value-head tensors.
+int policy_slots(const vla_config& c) { return 3 + 9 * c.n_layers; }
+int all_slots(const vla_config& c) { return policy_slots(c) + (c.value_max_steps > 0 ? 7 : 0); }
+
+std::string slot_name(const vla_config& c, int s) {
+  if (s == 0) return "embed";
+  if (s == 1) return "final_norm";
+  if (s == 2) return "lm_head";
+  if (s < policy_slots(c)) return "layers." + std::to_string((s - 3) / 9) + "." + kLeaves[(s - 3) % 9];
+  return kValueNames[s - policy_slots(c)];
+}
+
+// Maps every tensor to its slot and checks dtype and shape; nothing is enqueued.  slot[] must hold
+// all_slots(cfg) null pointers on entry.
+int parse_tensors(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, std::vector<const vla_tensor*>& slot) {
   const vla_config& c = ctx->cfg;
-  hipStream_t st = (hipStream_t)hip_stream;
   const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab, A = c.n_action_bins;
-  static const char* kLeaves[9] = {"attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"};
-  // slot index: 0 embed, 1 final_norm, 2 lm_head, 3 + 9*l + leaf
-  const int n_slots = 3 + 9 * c.n_layers;
-  std::vector<const vla_tensor*> slot(n_slots, nullptr);
+  const int np = policy_slots(c);
+  if (n_tensors < 0) return fail(ctx, VLA_E_SHAPE, "n_tensors is negative");
   for (int i = 0; i < n_tensors; ++i) {
     const vla_tensor& t = tensors[i];
     if (!t.name || !t.dev_ptr) return fail(ctx, VLA_E_NULL, "tensor %d has a NULL name or pointer", i);
@@ -588,7 +637,11 @@ int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors,
     if (!strcmp(t.name, "embed")) s = 0;
     else if (!strcmp(t.name, "final_norm")) s = 1;
     else if (!strcmp(t.name, "lm_head")) s = 2;
-    else {
+    else if (!strncmp(t.name, "value.", 6)) {
+      if (c.value_max_steps <= 0) return fail(ctx, VLA_E_CONFIG, "'%s': the context was created without a value head", t.name);
+      for (int k = 0; k < 7; ++k)
+        if (!strcmp(t.name, kValueNames[k])) s = np + k;
+    } else {
       int l = -1, used = 0;
       if (sscanf(t.name, "layers.%d.%n", &l, &used) == 1 && used > 0 && l >= 0 && l < c.n_layers)
         for (int k = 0; k < 9; ++k)
@@ -601,31 +654,44 @@ int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors,
     if (s == 0) { r = V; k = d; }
     else if (s == 1) { r = d; }
     else if (s == 2) { r = (t.ndim == 2 && t.shape[0] == A) ? A : V; k = d; }
-    else {
+    else if (s < np) {
       switch ((s - 3) % 9) {
         case 0: case 5: r = d; break;
         case 1: case 2: case 3: case 4: r = d; k = d; break;
         case 6: case 7: r = f; k = d; break;
         default: r = d; k = f; break;
       }
+    } else {
+      const int64_t vr[7] = {d, 1, c.value_max_steps, d, d, d, 1}, vk[7] = {0, 0, d, d, 0, 0, 0};
+      r = vr[s - np];
+      k = vk[s - np];
     }
     const bool ok = k ? (t.ndim == 2 && t.shape[0] == r && t.shape[1] == k) : (t.ndim == 1 && t.shape[0] == r);
     if (!ok) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' has the wrong shape", t.name);
     slot[s] = &t;
   }
-  for (int s = 0; s < n_slots; ++s)
-    if (!slot[s]) {
-      if (s < 3) return fail(ctx, VLA_E_WEIGHTS, "missing tensor '%s'", s == 0 ? "embed" : s == 1 ? "final_norm" : "lm_head");
-      return fail(ctx, VLA_E_WEIGHTS, "missing tensor 'layers.%d.%s'", (s - 3) / 9, kLeaves[(s - 3) % 9]);
-    }
+  return VLA_OK;
+}
 
+int require_slots(vla_ctx* ctx, const std::vector<const vla_tensor*>& slot, int first, int last, bool present) {
+  for (int s = first; s < last; ++s)
+    if ((slot[s] != nullptr) != present)
+      return fail(ctx, VLA_E_WEIGHTS, present ? "missing tensor '%s'" : "tensor '%s' does not belong in this call",
+                  slot_name(ctx->cfg, s).c_str());
+  return VLA_OK;
+}
+
+// Enqueues the copy / re-encoding of one tensor into its place in the arena.
+void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
+  const vla_config& c = ctx->cfg;
   const ArenaLayout& a = ctx->al;
+  const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab, A = c.n_action_bins;
   const bool bf = c.dtype == VLA_BF16;
-  auto gain = [&](const vla_tensor* t, size_t off) {
-    if (bf) convert_copy<bf16>((const bf16*)t->dev_ptr, at<float>(ctx->arena, off), d, st);
-    else convert_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), d, st);
+  auto to_f32 = [&](size_t off, size_t n) {
+    if (bf) convert_copy<bf16>((const bf16*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
+    else convert_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
   };
-  auto matrix = [&](const vla_tensor* t, size_t off, int64_t rows, int64_t K, int64_t row0, int mode) {
+  auto matrix = [&](size_t off, int64_t rows, int64_t K, int64_t row0, int mode) {
     if (bf) {
       pack_weight_f16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<f16>(ctx->arena, off), (int)row0, mode, st);
     } else {
@@ -633,32 +699,143 @@ int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors,
       plain_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off) + r0 * K, (size_t)(rows * K), st);
     }
   };
-  auto rows_copy = [&](const void* src, size_t off, size_t n) {
+  auto raw = [&](const void* src, size_t off, size_t n) {
     if (bf) plain_copy<bf16>((const bf16*)src, at<bf16>(ctx->arena, off), n, st);
     else plain_copy<float>((const float*)src, at<float>(ctx->arena, off), n, st);
   };
-  rows_copy(slot[0]->dev_ptr, a.embed, (size_t)(V * d));
-  gain(slot[1], a.g_final);
-  {
-    const vla_tensor* h = slot[2];
-    const size_t skip = h->shape[0] == A ? 0 : (size_t)((V - A) * d) * elem_size(c.dtype);
-    rows_copy((const char*)h->dev_ptr + skip, a.head, (size_t)(A * d));
+  const int np = policy_slots(c);
+  if (s == 0) raw(t->dev_ptr, a.embed, (size_t)(V * d));
+  else if (s == 1) to_f32(a.g_final, d);
+  else if (s == 2) {
+    const size_t skip = t->shape[0] == A ? 0 : (size_t)((V - A) * d) * elem_size(c.dtype);
+    raw((const char*)t->dev_ptr + skip, a.head, (size_t)(A * d));
+  } else if (s < np) {
+    const LayerW& lw = a.layers[(s - 3) / 9];
+    switch ((s - 3) % 9) {
+      case 0: to_f32(lw.g_attn, d); break;
+      case 1: matrix(lw.w_qkv, d, d, 0, 0); break;
+      case 2: matrix(lw.w_qkv, d, d, d, 0); break;
+      case 3: matrix(lw.w_qkv, d, d, 2 * d, 0); break;
+      case 4: matrix(lw.w_o, d, d, 0, 0); break;
+      case 5: to_f32(lw.g_ffn, d); break;
+      case 6: matrix(lw.w_gu, f, d, 0, 1); break;
+      case 7: matrix(lw.w_gu, f, d, 0, 2); break;
+      default: matrix(lw.w_down, d, f, 0, 0); break;
+    }
+  } else {
+    switch (s - np) {
+      case 0: to_f32(a.v_attn_w, d); break;
+      case 1: to_f32(a.v_attn_b, 1); break;
+      case 2: raw(t->dev_ptr, a.v_step_emb, (size_t)c.value_max_steps * d); break;
+      case 3: raw(t->dev_ptr, a.v_w1, (size_t)(d * d)); break;
+      case 4: to_f32(a.v_b1, d); break;
+      case 5: to_f32(a.v_w2, d); break;
+      default: to_f32(a.v_b2, 1); break;
+    }
   }
-  for (int l = 0; l < c.n_layers; ++l) {
-    const vla_tensor* const* t = &slot[3 + 9 * l];
-    const LayerW& lw = a.layers[l];
-    gain(t[0], lw.g_attn);
-    matrix(t[1], lw.w_qkv, d, d, 0, 0);
-    matrix(t[2], lw.w_qkv, d, d, d, 0);
-    matrix(t[3], lw.w_qkv, d, d, 2 * d, 0);
-    matrix(t[4], lw.w_o, d, d, 0, 0);
-    gain(t[5], lw.g_ffn);
-    matrix(t[6], lw.w_gu, f, d, 0, 1);
-    matrix(t[7], lw.w_gu, f, d, 0, 2);
-    matrix(t[8], lw.w_down, d, f, 0, 0);
-  }
+}
+
+// A whole-set load outside an update: ordered after the compute calls enqueued so far and before the
+// ones that follow, on whatever streams those run.
+int load_slots(vla_ctx* ctx, const std::vector<const vla_tensor*>& slot, hipStream_t st) {
+  if (ctx->have_work) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->ev_work, 0));
+  for (size_t s = 0; s < slot.size(); ++s)
+    if (slot[s]) write_slot(ctx, (int)s, slot[s], st);
   HIP_TRY(ctx, hipGetLastError());
+  HIP_TRY(ctx, hipEventRecord(ctx->ev_update, st));
+  ctx->have_update = true;
+  ctx->version += 1;
+  ctx->active_B = 0;     // cached keys / values belong to the old weights
+  return VLA_OK;
+}
+
+int check_loadable(vla_ctx* ctx, const vla_tensor* tensors) {
+  if (!tensors) return fail(ctx, VLA_E_NULL, "tensors is NULL");
+  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
+  if (ctx->serving == VLA_UPDATING) return fail(ctx, VLA_E_DRAINING, "an update is open (vla_update_tensors / vla_update_commit)");
+  return VLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_loadable(ctx, tensors);
+  if (rc) return rc;
+  std::vector<const vla_tensor*> slot(all_slots(ctx->cfg), nullptr);
+  if ((rc = parse_tensors(ctx, tensors, n_tensors, slot))) return rc;
+  if ((rc = require_slots(ctx, slot, 0, policy_slots(ctx->cfg), true))) return rc;
+  if ((rc = require_slots(ctx, slot, policy_slots(ctx->cfg), all_slots(ctx->cfg), false))) return rc;
+  if ((rc = load_slots(ctx, slot, (hipStream_t)hip_stream))) return rc;
   ctx->weights = true;
+  return VLA_OK;
+}
+
+int vla_load_value_head(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_loadable(ctx, tensors);
+  if (rc) return rc;
+  if (ctx->cfg.value_max_steps <= 0) return fail(ctx, VLA_E_CONFIG, "the context was created without a value head");
+  std::vector<const vla_tensor*> slot(all_slots(ctx->cfg), nullptr);
+  if ((rc = parse_tensors(ctx, tensors, n_tensors, slot))) return rc;
+  if ((rc = require_slots(ctx, slot, 0, policy_slots(ctx->cfg), false))) return rc;
+  if ((rc = require_slots(ctx, slot, policy_slots(ctx->cfg), all_slots(ctx->cfg), true))) return rc;
+  if ((rc = load_slots(ctx, slot, (hipStream_t)hip_stream))) return rc;
+  ctx->value_weights = true;
+  return VLA_OK;
+}
+
+int vla_get_state(const vla_ctx* ctx, int32_t* state, int64_t* version) {
+  if (!ctx) return VLA_E_NULL;
+  if (state) *state = ctx->serving;
+  if (version) *version = ctx->version;
+  return VLA_OK;
+}
+
+int vla_drain_begin(vla_ctx* ctx) {
+  if (!ctx) return VLA_E_NULL;
+  if (ctx->serving == VLA_UPDATING) return fail(ctx, VLA_E_DRAINING, "an update is already open");
+  ctx->serving = VLA_DRAINING;
+  return VLA_OK;
+}
+
+int vla_update_begin(vla_ctx* ctx, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
+  if (!ctx->weights) return fail(ctx, VLA_E_STATE, "nothing to update: weights were never loaded (vla_load_weights)");
+  if (ctx->serving == VLA_UPDATING) return fail(ctx, VLA_E_DRAINING, "an update is already open");
+  if (ctx->have_work) HIP_TRY(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, ctx->ev_work, 0));
+  ctx->serving = VLA_UPDATING;
+  ctx->active_B = 0;     // the batch in flight has been enqueued to its end; its cache dies with the old weights
+  return VLA_OK;
+}
+
+int vla_update_tensors(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  if (!tensors) return fail(ctx, VLA_E_NULL, "tensors is NULL");
+  if (ctx->serving != VLA_UPDATING) return fail(ctx, VLA_E_STATE, "no update is open (vla_update_begin)");
+  std::vector<const vla_tensor*> slot(all_slots(ctx->cfg), nullptr);
+  int rc = parse_tensors(ctx, tensors, n_tensors, slot);
+  if (rc) return rc;
+  if (!ctx->value_weights)     // a first value head must arrive whole
+    for (int s = policy_slots(ctx->cfg); s < all_slots(ctx->cfg); ++s)
+      if (slot[s]) return fail(ctx, VLA_E_STATE, "'%s': load the value head once (vla_load_value_head) before updating it", slot_name(ctx->cfg, s).c_str());
+  for (size_t s = 0; s < slot.size(); ++s)
+    if (slot[s]) write_slot(ctx, (int)s, slot[s], (hipStream_t)hip_stream);
+  HIP_TRY(ctx, hipGetLastError());
+  return VLA_OK;
+}
+
+int vla_update_commit(vla_ctx* ctx, void* hip_stream, int64_t* version_out) {
+  if (!ctx) return VLA_E_NULL;
+  if (ctx->serving != VLA_UPDATING) return fail(ctx, VLA_E_STATE, "no update is open (vla_update_begin)");
+  HIP_TRY(ctx, hipEventRecord(ctx->ev_update, (hipStream_t)hip_stream));
+  ctx->have_update = true;
+  ctx->version += 1;
+  ctx->serving = VLA_ACCEPTING;
+  if (version_out) *version_out = ctx->version;
   return VLA_OK;
 }
 
@@ -667,26 +844,34 @@ int vla_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* c
   if (!ctx) return VLA_E_NULL;
   int rc = check_ready(ctx);
   if (rc) return rc;
+  if ((rc = check_serving(ctx, true))) return rc;
   int64_t T = 0;
   rc = check_prefill(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, 0, &T);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
   const int A = ctx->cfg.n_action_bins;
-  if (ctx->cfg.dtype == VLA_BF16) return do_prefill<bf16>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st);
-  return do_prefill<float>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st);
+  rc = ctx->cfg.dtype == VLA_BF16 ? do_prefill<bf16>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st)
+                                  : do_prefill<float>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st);
+  if (rc) return rc;
+  return leave_compute(ctx, st);
 }
 
 int vla_decode_step(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits_out, void* hip_stream) {
   if (!ctx) return VLA_E_NULL;
   int rc = check_ready(ctx);
   if (rc) return rc;
+  if ((rc = check_serving(ctx, false))) return rc;
   if (!token_ids) return fail(ctx, VLA_E_NULL, "token_ids is NULL");
   rc = check_decode(ctx, B, 1);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
   const int A = ctx->cfg.n_action_bins;
-  if (ctx->cfg.dtype == VLA_BF16) return do_decode<bf16>(ctx, B, token_ids, logits_out, A, st);
-  return do_decode<float>(ctx, B, token_ids, logits_out, A, st);
+  rc = ctx->cfg.dtype == VLA_BF16 ? do_decode<bf16>(ctx, B, token_ids, logits_out, A, st)
+                                  : do_decode<float>(ctx, B, token_ids, logits_out, A, st);
+  if (rc) return rc;
+  return leave_compute(ctx, st);
 }
 
 int vla_select(vla_ctx* ctx, int32_t B, const float* logits, float temperature, const float* gumbel, int32_t k,
@@ -714,6 +899,7 @@ static int policy_step_impl(vla_ctx* ctx, int32_t B, const void* patch_emb, cons
   if (!ctx) return VLA_E_NULL;
   int rc = check_ready(ctx);
   if (rc) return rc;
+  if ((rc = check_serving(ctx, true))) return rc;
   if (!tokens_out || !logp_out || !actions_out) return fail(ctx, VLA_E_NULL, "an output pointer is NULL");
   if (n_tokens <= 0) return fail(ctx, VLA_E_SHAPE, "n_tokens must be positive");
   if (!(temperature >= 0.f)) return fail(ctx, VLA_E_SHAPE, "temperature must be >= 0");
@@ -727,6 +913,7 @@ static int policy_step_impl(vla_ctx* ctx, int32_t B, const void* patch_emb, cons
   rc = check_prefill(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, &T);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
   const vla_config& c = ctx->cfg;
   const int A = c.n_action_bins, id0 = c.vocab - A;
   int32_t* cur = at<int32_t>(ctx->work, ctx->wl.cur_ids);
@@ -762,7 +949,7 @@ static int policy_step_impl(vla_ctx* ctx, int32_t B, const void* patch_emb, cons
                           at<float>(ctx->work, w.vu), at<float>(ctx->work, w.vh), values_out, st);
   }
   HIP_TRY(ctx, hipGetLastError());
-  return VLA_OK;
+  return leave_compute(ctx, st);
 }
 
 int vla_policy_step(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
@@ -782,56 +969,6 @@ int vla_policy_step_value(vla_ctx* ctx, int32_t B, const void* patch_emb, const 
   return policy_step_impl(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature, gumbel, act_scale,
                           act_offset, action_dim, step_t, tokens_out, logp_out, actions_out, logits_out, values_out,
                           true, hip_stream);
-}
-
-int vla_load_value_head(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream) {
-  if (!ctx) return VLA_E_NULL;
-  if (!tensors) return fail(ctx, VLA_E_NULL, "tensors is NULL");
-  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
-  const vla_config& c = ctx->cfg;
-  if (c.value_max_steps <= 0) return fail(ctx, VLA_E_CONFIG, "the context was created without a value head");
-  hipStream_t st = (hipStream_t)hip_stream;
-  const int64_t d = c.d_model;
-  static const char* kNames[7] = {"value.attn_w", "value.attn_b", "value.step_emb", "value.w1",
-                                  "value.b1",     "value.w2",     "value.b2"};
-  const int64_t rows[7] = {d, 1, c.value_max_steps, d, d, d, 1}, cols[7] = {0, 0, d, d, 0, 0, 0};
-  const vla_tensor* slot[7] = {};
-  for (int i = 0; i < n_tensors; ++i) {
-    const vla_tensor& t = tensors[i];
-    if (!t.name || !t.dev_ptr) return fail(ctx, VLA_E_NULL, "tensor %d has a NULL name or pointer", i);
-    int s = -1;
-    for (int k = 0; k < 7; ++k)
-      if (!strcmp(t.name, kNames[k])) s = k;
-    if (s < 0) return fail(ctx, VLA_E_WEIGHTS, "unknown tensor name '%s'", t.name);
-    if (slot[s]) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' given twice", t.name);
-    if (t.dtype != c.dtype) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' has dtype %d, config has %d", t.name, t.dtype, c.dtype);
-    const bool ok = cols[s] ? (t.ndim == 2 && t.shape[0] == rows[s] && t.shape[1] == cols[s])
-                            : (t.ndim == 1 && t.shape[0] == rows[s]);
-    if (!ok) return fail(ctx, VLA_E_WEIGHTS, "tensor '%s' has the wrong shape", t.name);
-    slot[s] = &t;
-  }
-  for (int k = 0; k < 7; ++k)
-    if (!slot[k]) return fail(ctx, VLA_E_WEIGHTS, "missing tensor '%s'", kNames[k]);
-  const ArenaLayout& a = ctx->al;
-  const bool bf = c.dtype == VLA_BF16;
-  auto to_f32_vec = [&](const vla_tensor* t, size_t off, size_t n) {
-    if (bf) convert_copy<bf16>((const bf16*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
-    else convert_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
-  };
-  auto raw = [&](const vla_tensor* t, size_t off, size_t n) {
-    if (bf) plain_copy<bf16>((const bf16*)t->dev_ptr, at<bf16>(ctx->arena, off), n, st);
-    else plain_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
-  };
-  to_f32_vec(slot[0], a.v_attn_w, d);
-  to_f32_vec(slot[1], a.v_attn_b, 1);
-  raw(slot[2], a.v_step_emb, (size_t)c.value_max_steps * d);
-  raw(slot[3], a.v_w1, (size_t)d * d);
-  to_f32_vec(slot[4], a.v_b1, d);
-  to_f32_vec(slot[5], a.v_w2, d);
-  to_f32_vec(slot[6], a.v_b2, 1);
-  HIP_TRY(ctx, hipGetLastError());
-  ctx->value_weights = true;
-  return VLA_OK;
 }
 
 int vla_prof_enable(vla_ctx* ctx, int32_t mask) {

@@ -65,3 +65,25 @@ def test_null_arguments_and_unbound_state():
     assert "bound" in B.vla_last_error(ctx) or "NULL" in B.vla_last_error(ctx)
     assert B.vla_prof_count() == 13
     B.vla_destroy(ctx)
+
+
+def test_serving_state_transitions_on_the_host():
+    """Drain / update state machine (Appendix "High-Performance NCCL-based Weight Synchronization"): the
+    transitions that touch no device state."""
+    L = B.lib()
+    wl = W.get_workload("C1")
+    ctx = B.vla_create(B.make_config(wl.shape, 4, 64, 256, value_max_steps=3))
+    assert B.vla_get_state(ctx) == (B.VLA_ACCEPTING, 0)
+    B.vla_drain_begin(ctx)
+    B.vla_drain_begin(ctx)                                   # repeating the signal is harmless
+    assert B.vla_get_state(ctx) == (B.VLA_DRAINING, 0)
+    # no update is open: tensors and commit are refused, and the state does not move
+    dummy = (B.vla_tensor * 1)()
+    assert L.vla_update_tensors(ctx, dummy, 0, None) == B.VLA_E_STATE
+    assert L.vla_update_commit(ctx, None, None) == B.VLA_E_STATE
+    # an update cannot open on a context without bound buffers / loaded weights
+    assert L.vla_update_begin(ctx, None) == B.VLA_E_STATE
+    assert B.vla_get_state(ctx) == (B.VLA_DRAINING, 0)
+    assert L.vla_get_state(None, None, None) == -1
+    assert L.vla_drain_begin(None) == -1
+    B.vla_destroy(ctx)

@@ -242,6 +242,104 @@ def test_value_head_error_paths():
     pol.close()
 
 
+def _step(pol, wl, obs, dev, **kw):
+    out = pol.policy_step(dev["patch_emb"], obs["cu_patch"], dev["instr_ids"], obs["cu_instr"], wl.n_tokens,
+                          action_dim=wl.action_dim, want_logits=True, **kw)
+    return out
+
+
+@pytest.mark.parametrize("name", ["C1", "T16"])
+def test_in_place_weight_update_with_drain(name):
+    """A step enqueued before the update sees only the old weights, a step after it only the new ones, with the
+    overwrite enqueued on a second stream and no host synchronisation in between; bucketed and partial updates
+    equal a fresh load of the same tensors; calls are refused as the state machine says."""
+    import torch
+    from paper_2603_18464_amd import VlaError, VLA_ACCEPTING, VLA_DRAINING, VLA_UPDATING, VLA_E_DRAINING, VLA_E_STATE
+    if name == "C1":
+        wl = W.get_workload("C1")
+    else:
+        shape = W.PolicyShape(3, 256, 2, 128, 704, 1024, dtype="bf16")
+        wl = W.Workload("T16", 11, shape, batch=40, n_patches=48, instr_len=(4, 24), n_tokens=4)
+    obs = W.make_observations(wl)
+    w_old = W.make_weights(wl.shape, wl.seed)
+    w_new = W.make_weights(wl.shape, wl.seed + 1)
+
+    def fresh(weights):
+        pol = make_policy(wl, weights)
+        out = P.to_numpy(_step(pol, wl, obs, P.device_inputs(pol, obs)))
+        pol.close()
+        return out
+    ref_old, ref_new = fresh(w_old), fresh(w_new)
+    assert not np.array_equal(ref_old["logits"], ref_new["logits"])
+    mixed = dict(w_old)
+    part = [n for n in w_new if n.startswith("layers.1.") or n in ("lm_head", "final_norm")]
+    for n in part:
+        mixed[n] = w_new[n]
+    ref_mixed = fresh(mixed)
+
+    pol = make_policy(wl, w_old)
+    dev = P.device_inputs(pol, obs)
+    new_dev = {n: pol.to_device(t) for n, t in w_new.items()}
+    torch.cuda.synchronize()
+    assert pol.state() == (VLA_ACCEPTING, 1)
+    side = torch.cuda.Stream(device=pol.device)
+    out_a = _step(pol, wl, obs, dev)                       # enqueued, not waited for
+    pol.drain_begin()
+    assert pol.state()[0] == VLA_DRAINING
+    with pytest.raises(VlaError) as e:
+        _step(pol, wl, obs, dev)                           # no new batch while draining
+    assert e.value.code == VLA_E_DRAINING
+    pol.update_begin(side)
+    assert pol.state() == (VLA_UPDATING, 1)
+    with pytest.raises(VlaError) as e:
+        _step(pol, wl, obs, dev)
+    assert e.value.code == VLA_E_DRAINING
+    names = list(new_dev)
+    for i in range(0, len(names), 7):                      # buckets, as a broadcast would deliver them
+        pol.update_tensors({n: new_dev[n] for n in names[i:i + 7]}, side)
+    with pytest.raises(VlaError):
+        pol.update_tensors({"layers.99.wq": new_dev["layers.0.wq"]}, side)
+    assert pol.update_commit(side) == 2
+    assert pol.state() == (VLA_ACCEPTING, 2)
+    out_b = _step(pol, wl, obs, dev)                       # main stream again, still no host sync
+    torch.cuda.synchronize()
+    out_a, out_b = P.to_numpy(out_a), P.to_numpy(out_b)
+    for k in ("tokens", "logp", "actions", "logits"):
+        assert np.array_equal(out_a[k], ref_old[k]), f"step before the update: {k}"
+        assert np.array_equal(out_b[k], ref_new[k]), f"step after the update: {k}"
+
+    # the batch in flight may finish while draining, and dies with the old weights
+    pol.prefill(dev["patch_emb"], obs["cu_patch"], dev["instr_ids"], obs["cu_instr"])
+    pol.drain_begin()
+    tok = torch.full((wl.batch,), wl.shape.vocab - 1, dtype=torch.int32, device=pol.device)
+    pol.decode_step(tok)
+    pol.update_begin()
+    with pytest.raises(VlaError) as e:
+        pol.decode_step(tok)
+    assert e.value.code == VLA_E_DRAINING
+    # partial update on the compute stream itself: back to the old weights except one layer and the head
+    back = {n: pol.to_device(mixed[n]) for n in mixed}
+    pol.update_tensors({n: back[n] for n in back if n not in part})
+    pol.update_tensors({n: back[n] for n in part})
+    assert pol.update_commit() == 3
+    with pytest.raises(VlaError) as e:
+        pol.decode_step(tok)                               # the old batch is gone
+    assert e.value.code == VLA_E_STATE
+    out_c = P.to_numpy(_step(pol, wl, obs, dev))
+    for k in ("tokens", "logp", "actions", "logits"):
+        assert np.array_equal(out_c[k], ref_mixed[k]), f"partial update: {k}"
+    # the whole-set load is an update of its own
+    pol.load_weights(w_old)
+    assert pol.state() == (VLA_ACCEPTING, 4)
+    out_d = P.to_numpy(_step(pol, wl, obs, dev))
+    assert np.array_equal(out_d["logits"], ref_old["logits"])
+    # and the updated weights are the oracle's: parity of the post-update step against the oracle on the new set
+    rows = list(range(min(wl.batch, 6)))
+    ora = P.oracle_policy(wl, w_new, obs, None, rows)
+    P.check_free_running(wl, out_b, ora, rows, P.tolerances(wl))
+    pol.close()
+
+
 def test_policy_step_is_deterministic_and_matches_stepwise_calls():
     """Two identical policy steps give bit-identical outputs; prefill + select + decode_step called
     one by one reproduce vla_policy_step."""
