@@ -190,6 +190,33 @@ int vla_update_begin(vla_ctx* ctx, void* hip_stream);
 int vla_update_tensors(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream);
 int vla_update_commit(vla_ctx* ctx, void* hip_stream, int64_t* version_out);
 
+/* Request queue with the dynamic-window trigger of Section 3.2, Eq. 1 (host code; no GPU work):
+ *     Trigger = (|Q| >= target_batch) or (t_now - t_first >= t_max),   t_first = arrival of the oldest request.
+ * Times are seconds on any monotonic clock of the caller's choice, passed in explicitly.  A poll that
+ * triggers hands out the oldest requests in arrival order: at most target_batch, and, if max_tokens > 0,
+ * only while their packed prefix tokens (n_patches + n_instr summed) fit (always at least one); the rest
+ * stay queued with their own arrival times, so the next poll may trigger again at once.  An empty queue
+ * never triggers.  vla_batcher_push may be called from any thread, concurrently with polls; an arrival stamp
+ * older than the previous push's is raised to it (the queue is first-in first-out).
+ *   vla_batcher_create   VLA_E_CONFIG unless target_batch > 0, t_max >= 0 and finite, max_tokens >= 0.
+ *   vla_batcher_push     VLA_E_SHAPE for an empty or negative prefix or a NaN stamp, VLA_E_CAPACITY if the
+ *                        request alone exceeds max_tokens.  The struct is copied; `id` is opaque.
+ *   vla_batcher_poll     out: host array of cap >= target_batch entries (else VLA_E_CAPACITY);
+ *                        *n_out = number handed out (0: not triggered).
+ *   vla_batcher_deadline *t = t_first + t_max, the time at which waiting alone will trigger (+inf if empty). */
+typedef struct vla_batcher vla_batcher;
+typedef struct {
+  uint64_t id;
+  int32_t n_patches, n_instr;
+  double t_arrival;
+} vla_request;
+int vla_batcher_create(int32_t target_batch, double t_max, int64_t max_tokens, vla_batcher** out);
+int vla_batcher_destroy(vla_batcher* b);
+int vla_batcher_push(vla_batcher* b, const vla_request* r);
+int vla_batcher_size(vla_batcher* b, int32_t* n);
+int vla_batcher_deadline(vla_batcher* b, double* t);
+int vla_batcher_poll(vla_batcher* b, double t_now, vla_request* out, int32_t cap, int32_t* n_out);
+
 /* Selection alone, for callers that drive vla_prefill / vla_decode_step themselves:
  * logits [B, n_action_bins] (device) -> bin index, log-prob, action, for token index k of the
  * chunk (k selects the action dimension k mod action_dim and the row [b, k] of gumbel [B, K, A]).

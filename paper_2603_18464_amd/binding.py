@@ -16,6 +16,8 @@ VLA_ACCEPTING, VLA_DRAINING, VLA_UPDATING = 0, 1, 2
 EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vla_bind_buffers",
            "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_policy_step", "vla_select",
            "vla_load_value_head", "vla_policy_step_value",
+           "vla_batcher_create", "vla_batcher_destroy", "vla_batcher_push", "vla_batcher_size",
+           "vla_batcher_deadline", "vla_batcher_poll",
            "vla_get_state", "vla_drain_begin", "vla_update_begin", "vla_update_tensors", "vla_update_commit",
            "vla_prof_enable", "vla_prof_count", "vla_prof_read"]
 
@@ -31,6 +33,10 @@ class vla_config(C.Structure):
 class vla_tensor(C.Structure):
     _fields_ = [("name", C.c_char_p), ("dev_ptr", C.c_void_p), ("dtype", C.c_int32),
                 ("ndim", C.c_int32), ("shape", C.c_int64 * 4)]
+
+
+class vla_request(C.Structure):
+    _fields_ = [("id", C.c_uint64), ("n_patches", C.c_int32), ("n_instr", C.c_int32), ("t_arrival", C.c_double)]
 
 
 class VlaError(RuntimeError):
@@ -73,6 +79,12 @@ def lib() -> C.CDLL:
         L.vla_update_begin.argtypes = [vp, vp]
         L.vla_update_tensors.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
         L.vla_update_commit.argtypes = [vp, vp, C.POINTER(C.c_int64)]
+        L.vla_batcher_create.argtypes = [i32, C.c_double, C.c_int64, C.POINTER(vp)]
+        L.vla_batcher_destroy.argtypes = [vp]
+        L.vla_batcher_push.argtypes = [vp, C.POINTER(vla_request)]
+        L.vla_batcher_size.argtypes = [vp, C.POINTER(C.c_int32)]
+        L.vla_batcher_deadline.argtypes = [vp, C.POINTER(C.c_double)]
+        L.vla_batcher_poll.argtypes = [vp, C.c_double, C.POINTER(vla_request), i32, C.POINTER(C.c_int32)]
         L.vla_select.argtypes = [vp, i32, vp, f32, vp, i32, i32, vp, vp, i32, vp, vp, vp, i32, vp, vp]
         L.vla_prof_enable.argtypes = [vp, i32]
         L.vla_prof_count.argtypes = []
@@ -225,6 +237,49 @@ def vla_prof_read(ctx, i: int):
 
 
 # ---- convenience wrapper: owns the torch buffers ------------------------------------------------------
+
+class Batcher:
+    """Thin wrapper of the native request queue with the dynamic-window trigger (Section 3.2, Eq. 1)."""
+
+    def __init__(self, target_batch: int, t_max: float, max_tokens: int = 0):
+        self.h = C.c_void_p()
+        rc = lib().vla_batcher_create(target_batch, t_max, max_tokens, C.byref(self.h))
+        if rc:
+            raise VlaError(rc, "vla_batcher_create")
+        self.target = target_batch
+        self._buf = (vla_request * target_batch)()
+
+    def close(self):
+        if self.h:
+            lib().vla_batcher_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def push(self, rid: int, n_patches: int, n_instr: int, t_arrival: float) -> None:
+        r = vla_request(rid, n_patches, n_instr, t_arrival)
+        rc = lib().vla_batcher_push(self.h, C.byref(r))
+        if rc:
+            raise VlaError(rc, "vla_batcher_push")
+
+    def __len__(self) -> int:
+        n = C.c_int32()
+        lib().vla_batcher_size(self.h, C.byref(n))
+        return n.value
+
+    def deadline(self) -> float:
+        t = C.c_double()
+        lib().vla_batcher_deadline(self.h, C.byref(t))
+        return t.value
+
+    def poll(self, t_now: float):
+        """[(id, n_patches, n_instr, t_arrival)] of the released batch, [] if the rule did not fire."""
+        n = C.c_int32()
+        rc = lib().vla_batcher_poll(self.h, t_now, self._buf, self.target, C.byref(n))
+        if rc:
+            raise VlaError(rc, "vla_batcher_poll")
+        return [(r.id, r.n_patches, r.n_instr, r.t_arrival) for r in self._buf[:n.value]]
+
 
 def make_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, value_max_steps: int = 0) -> vla_config:
     return vla_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,

@@ -340,6 +340,85 @@ def test_in_place_weight_update_with_drain(name):
     pol.close()
 
 
+def test_inference_worker_serves_a_request_stream():
+    """Requests with ragged prefixes arrive over simulated time; the worker's batches are the ones Eq. 1 (oracle)
+    dictates, every request is answered once, and each answer meets the oracle run on that request alone.  A
+    weight update in the middle is drained for: no batch is started between the drain signal and the commit, and
+    every answer carries the version it was computed with."""
+    import torch
+    from oracle import batcher_oracle as BO
+    from oracle import vla_oracle as O
+    from paper_2603_18464_amd import InferenceWorker, VlaPolicy
+    shape = W.PolicyShape(2, 256, 2, 128, 704, 1024, dtype="bf16")
+    K, Bt, T_max, n_req = 4, 12, 0.020, 70
+    wl = W.Workload("S", 13, shape, batch=Bt, n_patches=64, instr_len=(0, 30), n_tokens=K)
+    w0, w1 = W.make_weights(shape, wl.seed), W.make_weights(shape, wl.seed + 1)
+    g = W.tensor_rng(wl.seed, "stream")
+    t_arr = np.cumsum(g.exponential(0.002, n_req) * g.choice([0.0, 1.0, 6.0], n_req, p=[0.3, 0.6, 0.1]))
+    n_patch = g.choice([16, 48, 64], n_req)
+    n_instr = g.integers(0, 31, n_req)
+    reqs = []
+    for r in range(n_req):
+        pe = W.bf16_bits_from_f32(g.standard_normal((int(n_patch[r]), shape.d_model), dtype=np.float32))
+        ids = g.integers(0, shape.action_id0, size=int(n_instr[r])).astype(np.int32)
+        reqs.append((pe, ids))
+    pol = VlaPolicy(shape, Bt, 64 + 30 + K, Bt * 94, value_max_steps=0)
+    pol.load_weights(w0)
+    worker = InferenceWorker(pol, Bt, T_max, n_tokens=K)
+    w1_dev = {n: pol.to_device(t) for n, t in w1.items()}
+    events, answers, a, t = [], {}, 0, 0.0
+    t_drain, t_commit = 0.060, 0.075
+    drained = committed = False
+    while a < n_req or len(worker.queue):
+        while a < n_req and t_arr[a] <= t:
+            worker.submit(a, pol.to_device(reqs[a][0]), torch.from_numpy(reqs[a][1]).to(pol.device), float(t_arr[a]))
+            events.append(("push", float(t_arr[a]), a, int(n_patch[a] + n_instr[a])))
+            a += 1
+        if not drained and t >= t_drain:
+            pol.drain_begin()
+            drained = True
+        if drained and not committed and t >= t_commit:
+            pol.update_begin()
+            pol.update_tensors(w1_dev)
+            assert pol.update_commit() == 2
+            committed = True
+        res = worker.poll(t)
+        if drained and not committed:
+            assert res is None
+        else:
+            events.append(("poll", t))
+        if res is not None:
+            tok, lp = res["tokens"].cpu().numpy(), res["logp"].cpu().numpy()
+            for i, rid in enumerate(res["ids"]):
+                assert rid not in answers
+                answers[rid] = (t, res["version"], tok[i], lp[i])
+        t += 0.003
+    assert sorted(answers) == list(range(n_req))
+    want = BO.simulate(events, Bt, T_max, Bt * 94)
+    got = {}
+    for rid, (tb, _, _, _) in answers.items():
+        got.setdefault(tb, []).append(rid)
+    assert sorted((tb, sorted(b)) for tb, b in got.items()) == [(tb, sorted(b)) for tb, b in want]
+    versions = {v for _, v, _, _ in answers.values()}
+    assert versions == {1, 2}
+    tol = P.tolerances(wl)
+    checked = 0
+    for rid in list(range(0, n_req, 5)) + [n_req - 1]:
+        tb, ver, tok, lp = answers[rid]
+        assert (ver == 1) == (tb < t_commit)
+        ora = O.OraclePolicy(shape, w0 if ver == 1 else w1).policy_step([reqs[rid][0]], [reqs[rid][1]], K, mode="cached")
+        gaps = P.top2_gap(ora["scores"])[0]
+        for k in range(K):
+            if tok[k] != ora["tokens"][0, k]:
+                assert gaps[k] < tol["tie"]
+                break
+            assert abs(lp[k] - ora["logp"][0, k]) <= tol["logp"]
+            checked += 1
+    assert checked > 40
+    worker.close()
+    pol.close()
+
+
 def test_policy_step_is_deterministic_and_matches_stepwise_calls():
     """Two identical policy steps give bit-identical outputs; prefill + select + decode_step called
     one by one reproduce vla_policy_step."""
