@@ -193,6 +193,17 @@ def value_head(hidden: np.ndarray, step_t: int, vw: dict) -> float:
     return float(widen(np.asarray(vw["w2"])).reshape(-1) @ hid + float(widen(np.asarray(vw["b2"]).reshape(1))[0]))
 
 
+def importance_ratio(logp: np.ndarray, mu_logp: np.ndarray) -> np.ndarray:
+    """Token-level importance ratio rho = pi_theta(a_k | .) / mu(a_k | .) (Appendix "Token-level Policy
+    Optimization"), from the two log-probabilities."""
+    return np.exp(np.asarray(logp, dtype=np.float64) - np.asarray(mu_logp, dtype=np.float64))
+
+
+def gipo_trust_weight(rho: np.ndarray, sigma: float) -> np.ndarray:
+    """Gaussian trust weight omega(rho; sigma) = exp(-(log rho / sigma)^2 / 2) (Section 3.3, GIPO)."""
+    return np.exp(-0.5 * (np.log(np.asarray(rho, dtype=np.float64)) / sigma) ** 2)
+
+
 # ----------------------------------------------------------------------------
 # the model
 # ----------------------------------------------------------------------------
@@ -332,3 +343,65 @@ class OraclePolicy:
             seqs = [np.concatenate([sq, r], axis=0) for sq, r in zip(seqs, new_rows)]
         return {"tokens": tokens, "logp": logp, "actions": bin_centre(tokens, A),
                 "logits": logits, "scores": scores, "hidden": hidden}
+
+    # -- all K action rows in one forward pass ---------------------------------------
+    def chunk_logits(self, patch_embs: List[np.ndarray], instr_ids: List[np.ndarray], fed_ids: np.ndarray,
+                     n_layers: Optional[int] = None) -> np.ndarray:
+        """One causal forward pass over [prefix ; fed_ids[b]] per sequence (fed_ids: [B, K-1] absolute vocabulary
+        ids); returns the action-bin logits [B, K, A] of the last K positions: row k is the position that emits
+        action token k (the last prefix position, then the K-1 fed positions)."""
+        fed_ids = np.asarray(fed_ids).reshape(len(patch_embs), -1)
+        K = fed_ids.shape[1] + 1
+        seqs = [np.concatenate([self.prefix_rows(pe, ids), self.token_rows(list(f))], axis=0) if K > 1
+                else self.prefix_rows(pe, ids) for pe, ids, f in zip(patch_embs, instr_ids, fed_ids)]
+        states = [SeqState(self.s.n_layers) for _ in seqs]
+        outs = self.run_layers(seqs, states, n_layers)
+        return np.stack([np.stack([self.action_logits(o[len(o) - K + k]) for k in range(K)]) for o in outs])
+
+    def policy_step_parallel(self, patch_embs, instr_ids, n_tokens: int, placeholder_id: int,
+                             temperature: float = 0.0, gumbel: Optional[np.ndarray] = None) -> dict:
+        """Parallel decoding: the K action tokens are conditionally independent given the observation (the
+        token-level ratio of Appendix "Token-level Policy Optimization" conditions every token on o_t alone).
+        The K-1 positions after the prefix hold a fixed placeholder token instead of sampled ones, so all K
+        distributions come from one forward pass; each token is then selected on its own."""
+        B, A = len(patch_embs), self.s.n_action_bins
+        fed = np.full((B, n_tokens - 1), placeholder_id, dtype=np.int64)
+        logits = self.chunk_logits(patch_embs, instr_ids, fed)
+        tau = 1.0 if temperature == 0 else temperature
+        tokens = np.zeros((B, n_tokens), dtype=np.int64)
+        logp = np.zeros((B, n_tokens))
+        scores = np.zeros((B, n_tokens, A))
+        for b in range(B):
+            ell = log_softmax(logits[b], tau)
+            for k in range(n_tokens):
+                t, sc = select_token(logits[b, k], temperature, None if gumbel is None else gumbel[b, k])
+                tokens[b, k], scores[b, k], logp[b, k] = t, sc, ell[k, t]
+        return {"tokens": tokens, "logp": logp, "actions": bin_centre(tokens, A), "logits": logits, "scores": scores}
+
+    def score_tokens(self, patch_embs, instr_ids, tokens: np.ndarray, temperature: float = 0.0,
+                     placeholder_id: Optional[int] = None, mu_logp: Optional[np.ndarray] = None,
+                     sigma: float = 1.0) -> dict:
+        """Learner-side evaluation of stored action tokens (bin indices [B, K]) under the current weights:
+        logp[b,k] = log pi(a_k | o, a_<k) when placeholder_id is None (the stored tokens are fed back), or
+        log pi(a_k | o) with the placeholder conditioning of policy_step_parallel.  With the behaviour
+        log-probabilities mu_logp it also gives rho and the GIPO coefficient omega(rho; sigma) * rho that
+        multiplies the advantage (Section 3.3)."""
+        tokens = np.asarray(tokens)
+        B, K = tokens.shape
+        A = self.s.n_action_bins
+        if placeholder_id is None:
+            fed = self.s.vocab - A + tokens[:, :K - 1]
+        else:
+            fed = np.full((B, K - 1), placeholder_id, dtype=np.int64)
+        logits = self.chunk_logits(patch_embs, instr_ids, fed)
+        tau = 1.0 if temperature == 0 else temperature
+        logp = np.zeros((B, K))
+        for b in range(B):
+            ell = log_softmax(logits[b], tau)
+            logp[b] = ell[np.arange(K), tokens[b]]
+        out = {"logp": logp, "logits": logits}
+        if mu_logp is not None:
+            rho = importance_ratio(logp, mu_logp)
+            out["ratio"] = rho
+            out["weight"] = gipo_trust_weight(rho, sigma) * rho
+        return out

@@ -424,3 +424,105 @@ def test_policy_step_returns_the_hidden_rows_that_feed_the_head():
     head = w["lm_head"][s.vocab - s.n_action_bins:]
     assert r["hidden"].shape == (2, 3, s.d_model)
     assert np.abs(r["hidden"] @ head.T - r["logits"]).max() < 1e-12
+
+
+# ---- all K action rows in one pass: parallel decoding, stored-token evaluation, GIPO coefficients --------
+
+def test_gipo_weight_closed_forms():
+    """omega(rho; sigma) = exp(-(log rho / sigma)^2 / 2) (Section 3.3); rho from the two log-probabilities."""
+    assert O.importance_ratio(-1.25, -1.25) == 1.0
+    assert O.importance_ratio(math.log(0.3), math.log(0.6)) == pytest.approx(0.5, abs=1e-15)
+    assert O.gipo_trust_weight(1.0, 0.7) == 1.0                                   # on-policy: no damping
+    for sigma in (0.25, 1.0, 3.0):
+        assert O.gipo_trust_weight(math.exp(sigma), sigma) == pytest.approx(math.exp(-0.5), abs=1e-15)
+        assert O.gipo_trust_weight(math.exp(-2 * sigma), sigma) == pytest.approx(math.exp(-2.0), abs=1e-15)
+    # a number worked by hand: sigma = 0.5, rho = 2: (ln 2 / 0.5)^2 / 2 = 0.960906 -> 0.382546
+    assert O.gipo_trust_weight(2.0, 0.5) == pytest.approx(0.382546, abs=2e-6)
+    rho = np.array([0.1, 0.5, 0.9, 1.1, 2.0, 10.0])
+    w = O.gipo_trust_weight(rho, 0.8)
+    assert np.allclose(w, O.gipo_trust_weight(1.0 / rho, 0.8), rtol=0, atol=1e-15)      # symmetric in log rho
+    assert np.all(w < 1.0) and np.all(np.diff(w[:3]) > 0) and np.all(np.diff(w[3:]) < 0)  # peak at rho = 1
+    assert O.gipo_trust_weight(1e6, 0.5) < 1e-100                                         # extreme ratios vanish smoothly
+
+
+def test_chunk_rows_against_pure_python_prefixes():
+    """Causality pins the chunk pass: row k of one pass over [prefix ; fed] equals the last-position logits of
+    the sequence cut after S + k rows, computed by the pure-Python loops."""
+    s = shape(L=2, d=8, H=2, hd=4, f=6, V=12, A=4)
+    w = rand_weights(s, seed=5, std=0.5)
+    cfg = dict(L=2, d=8, H=2, hd=4, f=6, V=12, A=4, theta=s.rope_theta, eps=s.rms_eps)
+    Wt = {k: v.tolist() for k, v in w.items()}
+    pes, ids = rand_obs(s, 1, 2, [3], seed=31)
+    fed = np.array([[9, 2, 11]])                       # any vocabulary ids, K = 4
+    rows = [r.tolist() for r in pes[0]] + [Wt["embed"][i] for i in ids[0]] + [Wt["embed"][i] for i in fed[0]]
+    S = len(rows) - 3
+    got = O.OraclePolicy(s, w).chunk_logits(pes, ids, fed)
+    assert got.shape == (1, 4, 4)
+    for k in range(4):
+        want = np.array(BF.forward_logits(cfg, Wt, rows[:S + k]))
+        assert np.abs(got[0, k] - want).max() < 1e-12, k
+
+
+def test_parallel_decoding_reductions():
+    s = shape()
+    w = rand_weights(s, seed=2)
+    pol = O.OraclePolicy(s, w)
+    pes, ids = rand_obs(s, 3, 4, [0, 2, 5], seed=8)
+    A, K = s.n_action_bins, 5
+    ph_bin = 3
+    ph = s.vocab - A + ph_bin
+    par = pol.policy_step_parallel(pes, ids, K, ph)
+    # (a) it is the autoregressive path with the placeholder fed back instead of the selected token
+    for mode in ("recompute", "cached"):
+        ar = pol.policy_step(pes, ids, K, mode=mode, forced_tokens=np.full((3, K), ph_bin))
+        assert np.abs(par["logits"] - ar["logits"]).max() < 1e-11
+        assert np.array_equal(par["tokens"], ar["tokens"]) and np.abs(par["logp"] - ar["logp"]).max() < 1e-11
+    # (b) the first token does not depend on the placeholder at all, and K = 1 is the ordinary step
+    other = pol.policy_step_parallel(pes, ids, K, 1)
+    assert np.abs(other["logits"][:, 0] - par["logits"][:, 0]).max() < 1e-12
+    assert np.abs(other["logits"][:, 1:] - par["logits"][:, 1:]).max() > 1e-3
+    one = pol.policy_step_parallel(pes, ids, 1, ph)
+    assert np.abs(one["logits"] - pol.policy_step(pes, ids, 1)["logits"]).max() < 1e-12
+    # (c) conditional independence: noise at one position moves only that position's token
+    g = np.random.default_rng(4).gumbel(size=(3, K, A))
+    base = pol.policy_step_parallel(pes, ids, K, ph, temperature=0.9, gumbel=g)
+    g2 = g.copy()
+    g2[:, 2] = np.random.default_rng(5).gumbel(size=(3, A)) * 5
+    moved = pol.policy_step_parallel(pes, ids, K, ph, temperature=0.9, gumbel=g2)
+    keep = [0, 1, 3, 4]
+    assert np.array_equal(base["tokens"][:, keep], moved["tokens"][:, keep])
+    assert np.array_equal(base["logits"], moved["logits"])
+    assert not np.array_equal(base["tokens"][:, 2], moved["tokens"][:, 2])
+    assert np.all(base["actions"] == O.bin_centre(base["tokens"], A))
+    # log-probs are a normalised distribution at temperature tau over the bins
+    ell = O.log_softmax(base["logits"], 0.9)
+    assert np.abs(np.exp(ell).sum(-1) - 1).max() < 1e-12
+    assert np.abs(np.take_along_axis(ell, base["tokens"][..., None], -1)[..., 0] - base["logp"]).max() < 1e-12
+
+
+def test_score_tokens_reproduces_behaviour_logp_and_gipo():
+    s = shape()
+    w = rand_weights(s, seed=6)
+    pol = O.OraclePolicy(s, w)
+    pes, ids = rand_obs(s, 2, 3, [1, 4], seed=9)
+    A, K = s.n_action_bins, 4
+    g = np.random.default_rng(7).gumbel(size=(2, K, A))
+    beh = pol.policy_step(pes, ids, K, temperature=1.3, gumbel=g, mode="cached")
+    sc = pol.score_tokens(pes, ids, beh["tokens"], temperature=1.3, mu_logp=beh["logp"], sigma=0.4)
+    assert np.abs(sc["logp"] - beh["logp"]).max() < 1e-11          # same weights: learner == behaviour
+    assert np.abs(sc["ratio"] - 1).max() < 1e-10 and np.abs(sc["weight"] - 1).max() < 1e-10
+    assert np.abs(sc["logits"] - beh["logits"]).max() < 1e-11
+    # other weights: rho = exp(logp' - mu), coefficient = omega * rho, token by token
+    pol2 = O.OraclePolicy(s, rand_weights(s, seed=66))
+    sc2 = pol2.score_tokens(pes, ids, beh["tokens"], temperature=1.3, mu_logp=beh["logp"], sigma=0.4)
+    for b in range(2):
+        for k in range(K):
+            rho = math.exp(sc2["logp"][b, k] - beh["logp"][b, k])
+            assert sc2["ratio"][b, k] == pytest.approx(rho, rel=1e-12)
+            assert sc2["weight"][b, k] == pytest.approx(rho * math.exp(-0.5 * (math.log(rho) / 0.4) ** 2), rel=1e-10)
+    assert np.abs(sc2["ratio"] - 1).max() > 0.05
+    # placeholder conditioning scores the tokens of the parallel policy
+    ph = s.vocab - A + 2
+    par = pol.policy_step_parallel(pes, ids, K, ph, temperature=1.3, gumbel=g)
+    scp = pol.score_tokens(pes, ids, par["tokens"], temperature=1.3, placeholder_id=ph)
+    assert np.abs(scp["logp"] - par["logp"]).max() < 1e-11
