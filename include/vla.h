@@ -190,6 +190,41 @@ int vla_update_begin(vla_ctx* ctx, void* hip_stream);
 int vla_update_tensors(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream);
 int vla_update_commit(vla_ctx* ctx, void* hip_stream, int64_t* version_out);
 
+/* All K action rows in one forward pass.  Every sequence is run once over [prefix ; K-1 fed tokens]; row k of
+ * the result (k = 0..K-1) is the position that emits action token k: the last prefix position, then the fed
+ * positions.  1 <= K <= 64; S_b + K - 1 <= max_seq; the packed prefix tokens plus B*(K-1) <= max_prefill_tokens.
+ * Both calls start a new batch (they overwrite the KV cache of slots 0..B-1) and take the prefix arguments of
+ * vla_prefill.
+ *
+ * vla_policy_step_parallel — parallel decoding.  The token-level ratio of Appendix "Token-level Policy
+ *   Optimization" conditions every action token on the observation alone; here the K-1 fed positions hold the
+ *   fixed token `placeholder_id` (any vocabulary id) instead of sampled tokens, so the K distributions come from
+ *   one pass and each token is selected on its own, with the rules and outputs of vla_policy_step ([B, K]
+ *   tokens / log-probs / actions, optional logits [B, K, A]).  It equals vla_policy_step run with the placeholder
+ *   fed back at every step; for K = 1 the two coincide.
+ *
+ * vla_score_tokens — learner-side evaluation of stored action tokens (the trainer's twin of the rollout step):
+ *   tokens      device, [B, K] int32 bin indices (values outside [0, A) are clamped)
+ *   placeholder_id  < 0: autoregressive conditioning, the stored tokens 0..K-2 are fed back, so
+ *               logp[b,k] = log pi(a_k | o, a_<k) as vla_policy_step reports it; >= 0: the conditioning of
+ *               vla_policy_step_parallel with that placeholder.
+ *   logp_out    device, [B, K] float32: log_softmax(logits / temperature)[token] (temperature 0 means 1)
+ *   mu_logp     device, [B, K] behaviour log-probabilities, or NULL.  With it:
+ *   ratio_out   device, [B, K] or NULL: rho = exp(logp - mu)                     (token-level importance ratio)
+ *   weight_out  device, [B, K] or NULL: omega(rho; sigma) * rho with omega = exp(-(log rho / sigma)^2 / 2),
+ *               the GIPO coefficient of the advantage (Section 3.3); sigma > 0.
+ *   logits_out  device, [B, K, A] or NULL. */
+int vla_policy_step_parallel(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                             const int32_t* instr_ids, const int32_t* cu_instr, int32_t n_tokens,
+                             int32_t placeholder_id, float temperature, const float* gumbel,
+                             const float* act_scale, const float* act_offset, int32_t action_dim,
+                             int32_t* tokens_out, float* logp_out, float* actions_out, float* logits_out,
+                             void* hip_stream);
+int vla_score_tokens(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                     const int32_t* instr_ids, const int32_t* cu_instr, int32_t n_tokens, const int32_t* tokens,
+                     int32_t placeholder_id, float temperature, const float* mu_logp, float sigma,
+                     float* logp_out, float* ratio_out, float* weight_out, float* logits_out, void* hip_stream);
+
 /* Request queue with the dynamic-window trigger of Section 3.2, Eq. 1 (host code; no GPU work):
  *     Trigger = (|Q| >= target_batch) or (t_now - t_first >= t_max),   t_first = arrival of the oldest request.
  * Times are seconds on any monotonic clock of the caller's choice, passed in explicitly.  A poll that

@@ -16,6 +16,7 @@ VLA_ACCEPTING, VLA_DRAINING, VLA_UPDATING = 0, 1, 2
 EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vla_bind_buffers",
            "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_policy_step", "vla_select",
            "vla_load_value_head", "vla_policy_step_value",
+           "vla_policy_step_parallel", "vla_score_tokens",
            "vla_batcher_create", "vla_batcher_destroy", "vla_batcher_push", "vla_batcher_size",
            "vla_batcher_deadline", "vla_batcher_poll",
            "vla_get_state", "vla_drain_begin", "vla_update_begin", "vla_update_tensors", "vla_update_commit",
@@ -79,6 +80,8 @@ def lib() -> C.CDLL:
         L.vla_update_begin.argtypes = [vp, vp]
         L.vla_update_tensors.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
         L.vla_update_commit.argtypes = [vp, vp, C.POINTER(C.c_int64)]
+        L.vla_policy_step_parallel.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.vla_score_tokens.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, f32, vp, f32, vp, vp, vp, vp, vp]
         L.vla_batcher_create.argtypes = [i32, C.c_double, C.c_int64, C.POINTER(vp)]
         L.vla_batcher_destroy.argtypes = [vp]
         L.vla_batcher_push.argtypes = [vp, C.POINTER(vla_request)]
@@ -194,6 +197,22 @@ def vla_policy_step_value(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_to
                                             _ptr(act_offset), action_dim, _ptr(step_t), _ptr(tokens_out),
                                             _ptr(logp_out), _ptr(actions_out), _ptr(logits_out), _ptr(values_out),
                                             stream))
+
+
+def vla_policy_step_parallel(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, placeholder_id, temperature,
+                             gumbel, act_scale, act_offset, action_dim, tokens_out, logp_out, actions_out,
+                             logits_out, stream: int = 0) -> None:
+    _check(ctx, lib().vla_policy_step_parallel(ctx, B, _ptr(patch_emb), _ptr(cu_patch), _ptr(instr_ids),
+                                               _ptr(cu_instr), n_tokens, placeholder_id, temperature, _ptr(gumbel),
+                                               _ptr(act_scale), _ptr(act_offset), action_dim, _ptr(tokens_out),
+                                               _ptr(logp_out), _ptr(actions_out), _ptr(logits_out), stream))
+
+
+def vla_score_tokens(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, tokens, placeholder_id, temperature,
+                     mu_logp, sigma, logp_out, ratio_out, weight_out, logits_out, stream: int = 0) -> None:
+    _check(ctx, lib().vla_score_tokens(ctx, B, _ptr(patch_emb), _ptr(cu_patch), _ptr(instr_ids), _ptr(cu_instr),
+                                       n_tokens, _ptr(tokens), placeholder_id, temperature, _ptr(mu_logp), sigma,
+                                       _ptr(logp_out), _ptr(ratio_out), _ptr(weight_out), _ptr(logits_out), stream))
 
 
 def vla_prefill(ctx, B, patch_emb, cu_patch: np.ndarray, instr_ids, cu_instr: np.ndarray, logits_out,
@@ -372,6 +391,41 @@ class VlaPolicy:
         B = token_ids.shape[0]
         out = torch.empty((B, self.shape.n_action_bins), dtype=torch.float32, device=self.device) if want_logits else None
         vla_decode_step(self.ctx, B, token_ids, out, self._stream())
+        return out
+
+    def policy_step_parallel(self, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, placeholder_id,
+                             temperature=0.0, gumbel=None, act_scale=None, act_offset=None, action_dim=7,
+                             want_logits=False, out=None):
+        """All K action tokens from one forward pass (placeholder-fed positions)."""
+        torch = self.torch
+        B = len(cu_patch) - 1
+        A = self.shape.n_action_bins
+        if out is None:
+            out = {
+                "tokens": torch.empty((B, n_tokens), dtype=torch.int32, device=self.device),
+                "logp": torch.empty((B, n_tokens), dtype=torch.float32, device=self.device),
+                "actions": torch.empty((B, n_tokens), dtype=torch.float32, device=self.device),
+                "logits": torch.empty((B, n_tokens, A), dtype=torch.float32, device=self.device) if want_logits else None,
+            }
+        vla_policy_step_parallel(self.ctx, B, patch_emb, np.ascontiguousarray(cu_patch, dtype=np.int32), instr_ids,
+                                 np.ascontiguousarray(cu_instr, dtype=np.int32), n_tokens, int(placeholder_id),
+                                 float(temperature), gumbel, act_scale, act_offset, action_dim, out["tokens"],
+                                 out["logp"], out["actions"], out.get("logits"), self._stream())
+        return out
+
+    def score_tokens(self, patch_emb, cu_patch, instr_ids, cu_instr, tokens, placeholder_id=-1, temperature=0.0,
+                     mu_logp=None, sigma=1.0, want_logits=False):
+        """Log-probabilities of stored tokens [B, K] under the current weights (+ ratio and GIPO coefficient)."""
+        torch = self.torch
+        B, K = tokens.shape
+        A = self.shape.n_action_bins
+        mk = lambda *s: torch.empty(s, dtype=torch.float32, device=self.device)   # noqa: E731
+        out = {"logp": mk(B, K), "ratio": mk(B, K) if mu_logp is not None else None,
+               "weight": mk(B, K) if mu_logp is not None else None, "logits": mk(B, K, A) if want_logits else None}
+        vla_score_tokens(self.ctx, B, patch_emb, np.ascontiguousarray(cu_patch, dtype=np.int32), instr_ids,
+                         np.ascontiguousarray(cu_instr, dtype=np.int32), K, tokens, int(placeholder_id),
+                         float(temperature), mu_logp, float(sigma), out["logp"], out["ratio"], out["weight"],
+                         out["logits"], self._stream())
         return out
 
     def policy_step(self, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature=0.0, gumbel=None,

@@ -29,7 +29,7 @@ struct ArenaLayout {
 };
 struct WorkLayout {
   size_t x, hn, q, att, act, scratch, part, rope_cos, rope_sin, tok_seq, tok_pos, tok_src, last_row, seq_len,
-      cu_patch, cu_instr, cur_ids, logits, vz, vml, vu, vh, total;
+      cu_patch, cu_instr, cur_ids, logits, vz, vml, vu, vh, ids2, tail, chunk_rows, chunk_logits, total;
 };
 
 size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
@@ -73,6 +73,7 @@ size_t max_rows(const vla_config& c) {
   const size_t b32 = ((size_t)c.max_batch + 31) / 32 * 32;   // fragment-order activations come in 32-row blocks
   return (size_t)c.max_prefill_tokens > b32 ? (size_t)c.max_prefill_tokens : b32;
 }
+constexpr int kMaxChunk = 64;         // most action tokens per sequence in the one-pass (chunk) entry points
 constexpr int kSkinnyMaxRows = 128;   // decode batches up to this many rows use the weight-streaming GEMMs
 
 WorkLayout work_layout(const vla_config& c) {
@@ -105,6 +106,10 @@ WorkLayout work_layout(const vla_config& c) {
   w.vml = take(vrows * 2 * 4);
   w.vu = take(vrows * d * 4);
   w.vh = take(vrows * d * 4);
+  w.ids2 = take(T * 4);
+  w.tail = take(B * (size_t)kMaxChunk * 4);
+  w.chunk_rows = take(B * (size_t)kMaxChunk * 4);
+  w.chunk_logits = take(B * (size_t)kMaxChunk * c.n_action_bins * 4);
   w.total = off;
   return w;
 }
@@ -468,7 +473,10 @@ template <> struct ActOf<bf16> { typedef f16 type; };
 // S is the storage type of the caller's tensors (bf16 or float).
 template <class T>
 int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
-               const int32_t* cu_instr, int64_t T_tokens, float* logits, int ld_logits, hipStream_t st) {
+               const int32_t* cu_instr, int64_t T_tokens, float* logits, int ld_logits, hipStream_t st,
+               const int32_t* tail = nullptr, int n_tail = 0) {
+  // With a tail, cu_instr already counts n_tail extra ids per sequence (device array tail[B, n_tail]) and the
+  // id stream the layers see is the merge of instr_ids and tail.
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   // stage the host offset arrays in pinned memory (a slot is reused only after its copy finished)
@@ -489,8 +497,14 @@ int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu
                      at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos),
                      at<int32_t>(ctx->work, w.tok_src), at<int32_t>(ctx->work, w.last_row),
                      at<int32_t>(ctx->work, w.seq_len), st);
+    if (n_tail > 0) {
+      merge_tail_ids(instr_ids, at<int32_t>(ctx->work, w.cu_instr), tail, B, n_tail, cu_instr[B],
+                     at<int32_t>(ctx->work, w.ids2), st);
+      instr_ids = at<int32_t>(ctx->work, w.ids2);
+    }
     assemble_prefix<T>((const T*)patch_emb, instr_ids, at<T>(ctx->arena, ctx->al.embed),
-                       at<int32_t>(ctx->work, w.tok_src), at<float>(ctx->work, w.x), (int)T_tokens, c.d_model, st);
+                       at<int32_t>(ctx->work, w.tok_src), at<float>(ctx->work, w.x), (int)T_tokens, c.d_model,
+                       c.vocab, st);
   }
   ctx->run_B = B;
   ctx->run_max_len = 0;
@@ -525,6 +539,47 @@ int do_decode(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits, 
   }
   HIP_TRY(ctx, hipGetLastError());
   for (int b = 0; b < B; ++b) ctx->len[b] += 1;
+  return VLA_OK;
+}
+
+// One forward pass over [prefix ; K-1 fed tokens] per sequence, action logits [B, K, A] of the K emitting rows.
+// stored == nullptr feeds `placeholder` everywhere, otherwise the vocabulary ids of stored[b, 0..K-2].
+template <class T>
+int do_chunk(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
+             const int32_t* cu_instr, int64_t T_prefix, int K, const int32_t* stored, int placeholder, float* logits,
+             hipStream_t st) {
+  const vla_config& c = ctx->cfg;
+  const WorkLayout& w = ctx->wl;
+  const int n_tail = K - 1, A = c.n_action_bins;
+  std::vector<int32_t> cu2(B + 1);
+  for (int b = 0; b <= B; ++b) cu2[b] = cu_instr[b] + b * n_tail;
+  int32_t* tail = at<int32_t>(ctx->work, w.tail);
+  {
+    ProfScope ps(ctx, FAM_MISC, st);
+    tail_ids(stored, B, K, c.vocab - A, A, placeholder, tail, st);
+  }
+  int rc = do_prefill<T>(ctx, B, patch_emb, cu_patch, instr_ids, cu2.data(), T_prefix + (int64_t)B * n_tail, nullptr, 0,
+                         st, tail, n_tail);
+  if (rc) return rc;
+  int32_t* rows = at<int32_t>(ctx->work, w.chunk_rows);
+  {
+    ProfScope ps(ctx, FAM_MISC, st);
+    chunk_rows(at<int32_t>(ctx->work, w.last_row), B, K, rows, st);
+  }
+  run_head<T>(ctx, B * K, rows, logits, A, st);
+  HIP_TRY(ctx, hipGetLastError());
+  return VLA_OK;
+}
+
+// Shared validation of the one-pass entry points; returns the packed prefix token count.
+int check_chunk(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
+                const int32_t* cu_instr, int32_t K, int64_t* T_out) {
+  if (K <= 0 || K > kMaxChunk) return fail(ctx, VLA_E_SHAPE, "n_tokens must be in [1, %d]", kMaxChunk);
+  int rc = check_prefill(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, K - 1, T_out);
+  if (rc) return rc;
+  if (*T_out + (int64_t)B * (K - 1) > ctx->cfg.max_prefill_tokens)
+    return fail(ctx, VLA_E_CAPACITY, "%lld prefix + %lld fed tokens exceed max_prefill_tokens %lld", (long long)*T_out,
+                (long long)B * (K - 1), (long long)ctx->cfg.max_prefill_tokens);
   return VLA_OK;
 }
 
@@ -969,6 +1024,73 @@ int vla_policy_step_value(vla_ctx* ctx, int32_t B, const void* patch_emb, const 
   return policy_step_impl(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature, gumbel, act_scale,
                           act_offset, action_dim, step_t, tokens_out, logp_out, actions_out, logits_out, values_out,
                           true, hip_stream);
+}
+
+int vla_policy_step_parallel(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch,
+                             const int32_t* instr_ids, const int32_t* cu_instr, int32_t n_tokens,
+                             int32_t placeholder_id, float temperature, const float* gumbel, const float* act_scale,
+                             const float* act_offset, int32_t action_dim, int32_t* tokens_out, float* logp_out,
+                             float* actions_out, float* logits_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if ((rc = check_serving(ctx, true))) return rc;
+  if (!tokens_out || !logp_out || !actions_out) return fail(ctx, VLA_E_NULL, "an output pointer is NULL");
+  if (!(temperature >= 0.f)) return fail(ctx, VLA_E_SHAPE, "temperature must be >= 0");
+  if (action_dim < 0) return fail(ctx, VLA_E_SHAPE, "action_dim must be >= 0");
+  const vla_config& c = ctx->cfg;
+  if (placeholder_id < 0 || placeholder_id >= c.vocab) return fail(ctx, VLA_E_SHAPE, "placeholder_id outside the vocabulary");
+  int64_t T = 0;
+  if ((rc = check_chunk(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, &T))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
+  const int A = c.n_action_bins, K = n_tokens;
+  float* lg = logits_out ? logits_out : at<float>(ctx->work, ctx->wl.chunk_logits);
+  rc = c.dtype == VLA_BF16
+           ? do_chunk<bf16>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, K, nullptr, placeholder_id, lg, st)
+           : do_chunk<float>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, K, nullptr, placeholder_id, lg, st);
+  if (rc) return rc;
+  {
+    ProfScope ps(ctx, FAM_HEAD, st);
+    for (int k = 0; k < K; ++k)
+      select_tokens(lg + (size_t)k * A, K * A, B, A, temperature, gumbel, k, K, act_scale, act_offset, action_dim,
+                    tokens_out, logp_out, actions_out, K, nullptr, c.vocab - A, st);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  return leave_compute(ctx, st);
+}
+
+int vla_score_tokens(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
+                     const int32_t* cu_instr, int32_t n_tokens, const int32_t* tokens, int32_t placeholder_id,
+                     float temperature, const float* mu_logp, float sigma, float* logp_out, float* ratio_out,
+                     float* weight_out, float* logits_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if ((rc = check_serving(ctx, true))) return rc;
+  if (!tokens || !logp_out) return fail(ctx, VLA_E_NULL, "tokens / logp_out is NULL");
+  if (!(temperature >= 0.f)) return fail(ctx, VLA_E_SHAPE, "temperature must be >= 0");
+  if ((ratio_out || weight_out) && !mu_logp) return fail(ctx, VLA_E_NULL, "ratio / weight need mu_logp");
+  if (mu_logp && weight_out && !(sigma > 0.f)) return fail(ctx, VLA_E_SHAPE, "sigma must be positive");
+  const vla_config& c = ctx->cfg;
+  if (placeholder_id >= c.vocab) return fail(ctx, VLA_E_SHAPE, "placeholder_id outside the vocabulary");
+  int64_t T = 0;
+  if ((rc = check_chunk(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, &T))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
+  const int A = c.n_action_bins, K = n_tokens;
+  float* lg = logits_out ? logits_out : at<float>(ctx->work, ctx->wl.chunk_logits);
+  const int32_t* stored = placeholder_id < 0 ? tokens : nullptr;
+  rc = c.dtype == VLA_BF16
+           ? do_chunk<bf16>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, K, stored, placeholder_id, lg, st)
+           : do_chunk<float>(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, T, K, stored, placeholder_id, lg, st);
+  if (rc) return rc;
+  {
+    ProfScope ps(ctx, FAM_HEAD, st);
+    score_rows(lg, B * K, A, temperature, tokens, mu_logp, sigma, logp_out, ratio_out, weight_out, st);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  return leave_compute(ctx, st);
 }
 
 int vla_prof_enable(vla_ctx* ctx, int32_t mask) {

@@ -102,7 +102,7 @@ void rmsnorm(const float* x, const T* /*unused tag*/, const float* gain, T* out,
              float eps, const int32_t* row_index, hipStream_t st);
 template <class T>
 void assemble_prefix(const T* patch_emb, const int32_t* instr_ids, const T* embed,
-                     const int32_t* tok_src, float* x, int T_tokens, int d, hipStream_t st);
+                     const int32_t* tok_src, float* x, int T_tokens, int d, int vocab, hipStream_t st);
 template <class T>
 void embed_tokens(const int32_t* ids, const T* embed, float* x, int B, int d, int vocab, hipStream_t st);
 
@@ -152,6 +152,14 @@ template <class T>
 void value_finish(const float* vz, const float* vml, const T* step_emb, int n_steps, const int32_t* step_t,
                   const T* w1, const float* b1, const float* w2, const float* b2, int B, int d, float* vu, float* vh,
                   float* values, hipStream_t st);
+
+// Chunk pass (all K action rows in one forward): merged id stream, fed-token buffer, emitting rows, scoring.
+void merge_tail_ids(const int32_t* instr_ids, const int32_t* cu2_dev, const int32_t* tail, int B, int n_tail,
+                    int total, int32_t* out, hipStream_t st);
+void tail_ids(const int32_t* tokens, int B, int K, int id0, int A, int placeholder, int32_t* tail, hipStream_t st);
+void chunk_rows(const int32_t* last_row, int B, int K, int32_t* rows, hipStream_t st);
+void score_rows(const float* logits, int rows, int A, float temperature, const int32_t* tokens, const float* mu,
+                float sigma, float* logp_out, float* ratio_out, float* weight_out, hipStream_t st);
 
 // Small utilities.
 void rope_table(float* cos_t, float* sin_t, int max_seq, int head_dim, float theta, hipStream_t st);

@@ -109,23 +109,115 @@ template void plain_copy<bf16>(const bf16*, bf16*, size_t, hipStream_t);
 template <class T>
 __global__ void assemble_kernel(const T* __restrict__ patch_emb, const int32_t* __restrict__ instr_ids,
                                 const T* __restrict__ embed, const int32_t* __restrict__ tok_src,
-                                float* __restrict__ x, int d) {
+                                float* __restrict__ x, int d, int vocab) {
   const int t = blockIdx.x;
   const int src = tok_src[t];
-  const T* row = src >= 0 ? patch_emb + (size_t)src * d : embed + (size_t)instr_ids[-1 - src] * d;
+  int id = src >= 0 ? 0 : instr_ids[-1 - src];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // ids come from device memory: stay in bounds
+  const T* row = src >= 0 ? patch_emb + (size_t)src * d : embed + (size_t)id * d;
   float* out = x + (size_t)t * d;
   for (int i = threadIdx.x; i < d; i += blockDim.x) out[i] = to_f32(row[i]);
 }
 template <class T>
 void assemble_prefix(const T* patch_emb, const int32_t* instr_ids, const T* embed, const int32_t* tok_src,
-                     float* x, int T_tokens, int d, hipStream_t st) {
+                     float* x, int T_tokens, int d, int vocab, hipStream_t st) {
   hipLaunchKernelGGL(assemble_kernel<T>, dim3(T_tokens), dim3(256), 0, st, patch_emb, instr_ids, embed,
-                     tok_src, x, d);
+                     tok_src, x, d, vocab);
 }
 template void assemble_prefix<float>(const float*, const int32_t*, const float*, const int32_t*, float*, int,
-                                     int, hipStream_t);
+                                     int, int, hipStream_t);
 template void assemble_prefix<bf16>(const bf16*, const int32_t*, const bf16*, const int32_t*, float*, int, int,
-                                    hipStream_t);
+                                    int, hipStream_t);
+
+// ---- chunk pass: every sequence is [prefix ; n_tail fed tokens], logits wanted at its last n_tail + 1 rows ----
+// cu2[b] = cu_instr[b] + b * n_tail are the offsets of the merged id stream.
+__global__ void merge_tail_kernel(const int32_t* __restrict__ instr_ids, const int32_t* __restrict__ cu2,
+                                  const int32_t* __restrict__ tail, int B, int n_tail, int total,
+                                  int32_t* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int lo = 0, hi = B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu2[mid] <= i) lo = mid; else hi = mid;
+  }
+  const int b = lo, j = i - cu2[b];
+  const int li = cu2[b + 1] - cu2[b] - n_tail;
+  out[i] = j < li ? instr_ids[cu2[b] - b * n_tail + j] : tail[b * n_tail + (j - li)];
+}
+void merge_tail_ids(const int32_t* instr_ids, const int32_t* cu2_dev, const int32_t* tail, int B, int n_tail,
+                    int total, int32_t* out, hipStream_t st) {
+  if (total <= 0) return;
+  hipLaunchKernelGGL(merge_tail_kernel, dim3((total + 255) / 256), dim3(256), 0, st, instr_ids, cu2_dev, tail, B,
+                     n_tail, total, out);
+}
+
+// tail[b, j] = placeholder (tokens == nullptr) or the vocabulary id of stored bin tokens[b, j], j < K - 1
+__global__ void tail_ids_kernel(const int32_t* __restrict__ tokens, int B, int K, int id0, int A, int placeholder,
+                                int32_t* __restrict__ tail) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * (K - 1)) return;
+  const int b = i / (K - 1), j = i - b * (K - 1);
+  if (tokens) {
+    int t = tokens[b * K + j];
+    t = t < 0 ? 0 : (t >= A ? A - 1 : t);
+    tail[i] = id0 + t;
+  } else {
+    tail[i] = placeholder;
+  }
+}
+void tail_ids(const int32_t* tokens, int B, int K, int id0, int A, int placeholder, int32_t* tail, hipStream_t st) {
+  const int n = B * (K - 1);
+  if (n <= 0) return;
+  hipLaunchKernelGGL(tail_ids_kernel, dim3((n + 255) / 256), dim3(256), 0, st, tokens, B, K, id0, A, placeholder, tail);
+}
+
+// rows[b * K + k] = packed row that emits action token k of sequence b
+__global__ void chunk_rows_kernel(const int32_t* __restrict__ last_row, int B, int K, int32_t* __restrict__ rows) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * K) return;
+  const int b = i / K, k = i - b * K;
+  rows[i] = last_row[b] - (K - 1) + k;
+}
+void chunk_rows(const int32_t* last_row, int B, int K, int32_t* rows, hipStream_t st) {
+  hipLaunchKernelGGL(chunk_rows_kernel, dim3((B * K + 255) / 256), dim3(256), 0, st, last_row, B, K, rows);
+}
+
+// One wave per (sequence, token): log-prob of a given bin under log_softmax(logits / tau), and with the
+// behaviour log-prob mu the importance ratio rho = exp(logp - mu) and rho * exp(-(log rho / sigma)^2 / 2).
+__global__ __launch_bounds__(64) void score_kernel(const float* __restrict__ logits, int A, float temperature,
+                                                   const int32_t* __restrict__ tokens,
+                                                   const float* __restrict__ mu, float sigma,
+                                                   float* __restrict__ logp_out, float* __restrict__ ratio_out,
+                                                   float* __restrict__ weight_out) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  const float* z = logits + (size_t)r * A;
+  const float inv_tau = temperature > 0.f ? 1.0f / temperature : 1.0f;
+  float zmax = -INFINITY;
+  for (int j = lane; j < A; j += 64) zmax = fmaxf(zmax, z[j] * inv_tau);
+  zmax = wave_max(zmax);
+  float se = 0.f;
+  for (int j = lane; j < A; j += 64) se += expf(z[j] * inv_tau - zmax);
+  se = wave_sum(se);
+  if (lane == 0) {
+    int t = tokens[r];
+    t = t < 0 ? 0 : (t >= A ? A - 1 : t);
+    const float logp = z[t] * inv_tau - zmax - logf(se);
+    logp_out[r] = logp;
+    if (mu) {
+      const float lr = logp - mu[r];
+      const float rho = expf(lr);
+      const float q = lr / sigma;
+      if (ratio_out) ratio_out[r] = rho;
+      if (weight_out) weight_out[r] = rho * expf(-0.5f * q * q);
+    }
+  }
+}
+void score_rows(const float* logits, int rows, int A, float temperature, const int32_t* tokens, const float* mu,
+                float sigma, float* logp_out, float* ratio_out, float* weight_out, hipStream_t st) {
+  hipLaunchKernelGGL(score_kernel, dim3(rows), dim3(64), 0, st, logits, A, temperature, tokens, mu, sigma, logp_out,
+                     ratio_out, weight_out);
+}
 
 template <class T>
 __global__ void embed_kernel(const int32_t* __restrict__ ids, const T* __restrict__ embed,

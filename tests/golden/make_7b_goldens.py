@@ -3,7 +3,9 @@
 The full-size parity tests compare the HIP library with these stored values instead of running
 the fp64 oracle on the GPU machine (one 7B sequence costs the oracle about 4 TFLOP of fp64).  This
 script calls only `oracle/` and the seeded input generators; nothing in the files it writes comes
-from the HIP path.  Usage:  python tests/golden/make_7b_goldens.py [C3 C4 C5]
+from the HIP path.  Usage:  python tests/golden/make_7b_goldens.py [C3 C4 C5] [--parallel]
+With --parallel it writes <name>_parallel_oracle.npz instead: the one-pass (placeholder-fed) decoding of
+the same rows, placeholder = the first action id.
 
 For each workload it stores, for the chosen sequence indices `rows` of the seeded batch:
 tokens [n,K], logp [n,K], logits [n,K,A], scores [n,K,A] from the oracle in "cached" mode
@@ -31,7 +33,7 @@ def pick_rows(wl, obs):
     return [0, wl.batch - 1]
 
 
-def main(names):
+def main(names, parallel=False):
     for name in names:
         wl = W.get_workload(name)
         t0 = time.time()
@@ -44,6 +46,16 @@ def main(names):
         pes = [obs["patch_emb"][obs["cu_patch"][b]:obs["cu_patch"][b + 1]] for b in rows]
         ids = [obs["instr_ids"][obs["cu_instr"][b]:obs["cu_instr"][b + 1]] for b in rows]
         temp = wl.temperature if wl.sampling == "gumbel" else 0.0
+        if parallel:
+            ph = wl.shape.vocab - wl.shape.n_action_bins
+            r = pol.policy_step_parallel(pes, ids, wl.n_tokens, ph, temperature=temp,
+                                         gumbel=None if gum is None else gum[rows])
+            np.savez(os.path.join(HERE, f"{name.lower()}_parallel_oracle.npz"), rows=np.array(rows),
+                     tokens=r["tokens"], logp=r["logp"], logits=r["logits"], scores=r["scores"],
+                     actions=r["actions"], seed=np.array(wl.seed), placeholder=np.array(ph))
+            print(name, "parallel done", round(time.time() - t0, 1), "s", flush=True)
+            del weights, pol
+            continue
         r = pol.policy_step(pes, ids, wl.n_tokens, temperature=temp,
                             gumbel=None if gum is None else gum[rows], mode="cached")
         np.savez(os.path.join(HERE, f"{name.lower()}_oracle.npz"), rows=np.array(rows), tokens=r["tokens"],
@@ -54,4 +66,5 @@ def main(names):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1:] or ["C3", "C4", "C5"])
+    args = [a for a in sys.argv[1:] if not a.startswith("--")]
+    main(args or ["C3", "C4", "C5"], parallel="--parallel" in sys.argv)

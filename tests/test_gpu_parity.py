@@ -15,7 +15,8 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 def make_policy(wl, weights, max_batch=None, extra_seq=0):
     from paper_2603_18464_amd import VlaPolicy
     B = max_batch or wl.batch
-    pol = VlaPolicy(wl.shape, B, wl.max_seq + extra_seq, B * (wl.n_patches + wl.instr_len[1]))
+    # token capacity: the longest prefix for every slot, plus the fed positions of the one-pass entry points
+    pol = VlaPolicy(wl.shape, B, wl.max_seq + extra_seq, B * (wl.n_patches + wl.instr_len[1] + wl.n_tokens - 1))
     pol.load_weights(weights)
     return pol
 
@@ -137,6 +138,19 @@ def test_7b_workloads_against_stored_oracle_rows(name):
     print(f"[{name}] teacher-forced pass", flush=True)
     tf_err, tf_rms = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
     print(f"[{name}] free-running {stats}; teacher-forced logit err max {tf_err:.3e} rms {tf_rms:.3e}")
+    ppath = os.path.join(GOLDEN, f"{name.lower()}_parallel_oracle.npz")
+    if os.path.exists(ppath):          # the one-pass decoding of the same rows, same weights
+        gp = np.load(ppath)
+        assert [int(r) for r in gp["rows"]] == rows and int(gp["seed"]) == wl.seed
+        par = P.to_numpy(pol.policy_step_parallel(dev["patch_emb"], obs["cu_patch"], dev["instr_ids"], obs["cu_instr"],
+                                                  wl.n_tokens, int(gp["placeholder"]), temperature=temp,
+                                                  gumbel=dev["gumbel"], action_dim=wl.action_dim, want_logits=True))
+        sub = {k: par[k][rows] for k in ("tokens", "logp", "logits")}
+        n_eq = _compare_selection(wl, sub, {k: gp[k] for k in ("tokens", "logp", "logits", "scores")}, tol)
+        err = np.abs(sub["logits"] - gp["logits"])
+        print(f"[{name}] one-pass decoding: {n_eq} of {len(rows) * wl.n_tokens} tokens equal, logit err max "
+              f"{err.max():.3e} rms {np.sqrt((err ** 2).mean()):.3e}")
+        assert np.isfinite(par["logits"]).all()
     pol.close()
 
 
@@ -416,6 +430,106 @@ def test_inference_worker_serves_a_request_stream():
             checked += 1
     assert checked > 40
     worker.close()
+    pol.close()
+
+
+def _chunk_cases():
+    c1 = W.get_workload("C1")
+    fp32 = replace(c1, batch=6, n_patches=16, instr_len=(0, 30), n_tokens=5, sampling="gumbel", temperature=0.7,
+                   action_dim=3)
+    shape = W.PolicyShape(2, 256, 2, 128, 704, 1024, dtype="bf16")
+    bf = W.Workload("Tc", 17, shape, batch=7, n_patches=80, instr_len=(0, 40), n_tokens=6, sampling="gumbel",
+                    temperature=1.2)
+    return {"fp32": (fp32, [1, 16, 16, 3, 16, 16], [0, 5, 16, 1, 9, 30]),
+            "bf16": (bf, [1, 80, 80, 80, 80, 80, 64], [0, 3, 17, 40, 9, 0, 25])}
+
+
+def _compare_selection(wl, gpu, ora, tol):
+    """Rows are independent here (no token is fed back), so every (sequence, token) is compared on its own."""
+    gaps = P.top2_gap(ora["scores"])
+    n_equal = 0
+    for b in range(gpu["tokens"].shape[0]):
+        for k in range(wl.n_tokens):
+            assert np.abs(gpu["logits"][b, k] - ora["logits"][b, k]).max() <= tol["logit"], (b, k)
+            if gpu["tokens"][b, k] != ora["tokens"][b, k]:
+                assert gaps[b, k] < tol["tie"], (b, k)
+                continue
+            n_equal += 1
+            assert abs(gpu["logp"][b, k] - ora["logp"][b, k]) <= tol["logp"], (b, k)
+    return n_equal
+
+
+@pytest.mark.parametrize("case", ["fp32", "bf16"])
+def test_parallel_decoding_and_token_scoring(case):
+    """vla_policy_step_parallel and vla_score_tokens against the oracle: ragged batch spanning several tiles,
+    sequences of length 1, sampling, both conditionings, ratio and GIPO coefficient."""
+    import torch
+    from oracle import vla_oracle as O
+    wl, nps, lens = _chunk_cases()[case]
+    s = wl.shape
+    K, A = wl.n_tokens, s.n_action_bins
+    obs = ragged_obs(wl, nps, lens, seed=81)
+    gum = W.make_gumbel(wl)
+    weights = W.make_weights(s, wl.seed)
+    pol = make_policy(wl, weights, extra_seq=K)
+    dev = P.device_inputs(pol, obs, gum)
+    pes, ids = P.split_obs(obs, list(range(wl.batch)))
+    opol = O.OraclePolicy(s, weights)
+    tol = P.tolerances(wl)
+    args = (dev["patch_emb"], obs["cu_patch"], dev["instr_ids"], obs["cu_instr"])
+    ph = s.action_id0 + 5
+    # parallel decoding, sampled and greedy
+    for temp, g_dev, g_np in ((wl.temperature, dev["gumbel"], gum), (0.0, None, None)):
+        out = P.to_numpy(pol.policy_step_parallel(*args, K, ph, temperature=temp, gumbel=g_dev,
+                                                  action_dim=wl.action_dim, want_logits=True))
+        ora = opol.policy_step_parallel(pes, ids, K, ph, temperature=temp, gumbel=g_np)
+        n_eq = _compare_selection(wl, out, ora, tol)
+        assert n_eq >= wl.batch * K - 3
+        assert np.allclose(out["actions"], O.bin_centre(out["tokens"], A), rtol=0, atol=1e-6)
+    # it is the autoregressive step with the placeholder fed back: same library, other kernels (decode path)
+    forced = torch.full((wl.batch,), ph, dtype=torch.int32, device=pol.device)
+    lg0 = pol.prefill(*args).cpu().numpy()
+    lg1 = pol.decode_step(forced).cpu().numpy()
+    par = P.to_numpy(pol.policy_step_parallel(*args, K, ph, want_logits=True))
+    assert np.abs(par["logits"][:, 0] - lg0).max() <= (0 if case == "fp32" else tol["logit"])
+    assert np.abs(par["logits"][:, 1] - lg1).max() <= tol["logit"]
+    # scoring of the tokens a free-running autoregressive step chose, under the same weights: rho == 1
+    beh = pol.policy_step(*args, K, temperature=wl.temperature, gumbel=dev["gumbel"], action_dim=wl.action_dim)
+    sc = P.to_numpy(pol.score_tokens(*args, beh["tokens"], temperature=wl.temperature, mu_logp=beh["logp"],
+                                     sigma=0.5, want_logits=True))
+    beh = P.to_numpy(beh)
+    osc = opol.score_tokens(pes, ids, beh["tokens"], temperature=wl.temperature, mu_logp=beh["logp"].astype(np.float64),
+                            sigma=0.5)
+    assert np.abs(sc["logits"] - osc["logits"]).max() <= tol["logit"]
+    assert np.abs(sc["logp"] - osc["logp"]).max() <= tol["logp"]
+    assert np.abs(sc["logp"] - beh["logp"]).max() <= 2 * tol["logp"]
+    assert np.abs(sc["ratio"] - 1).max() <= 3 * tol["logp"] and np.abs(sc["weight"] - 1).max() <= 3 * tol["logp"]
+    # stale behaviour policy: other weights produced tokens and mu; ratio and coefficient against the oracle
+    w_old = W.make_weights(s, wl.seed + 5)
+    pol.load_weights(w_old)
+    old = pol.policy_step(*args, K, temperature=wl.temperature, gumbel=dev["gumbel"], action_dim=wl.action_dim)
+    old_np = P.to_numpy(old)
+    pol.load_weights(weights)
+    for ph_id in (-1, ph):
+        sc = P.to_numpy(pol.score_tokens(*args, old["tokens"], placeholder_id=ph_id, temperature=wl.temperature,
+                                         mu_logp=old["logp"], sigma=0.5))
+        osc = opol.score_tokens(pes, ids, old_np["tokens"], temperature=wl.temperature,
+                                placeholder_id=None if ph_id < 0 else ph_id,
+                                mu_logp=old_np["logp"].astype(np.float64), sigma=0.5)
+        assert np.abs(sc["logp"] - osc["logp"]).max() <= tol["logp"]
+        # rho and omega*rho inherit the log-prob error multiplicatively: d(rho) = rho * d(logp), |d(w)/d(logp)| <= 1.3 rho
+        bound = 1.5 * tol["logp"] * np.maximum(osc["ratio"], 1.0) + 1e-6
+        assert np.all(np.abs(sc["ratio"] - osc["ratio"]) <= bound)
+        assert np.all(np.abs(sc["weight"] - osc["weight"]) <= 2 * bound)
+    assert np.abs(osc["ratio"] - 1).max() > 0.05          # the stale case is not vacuous
+    # error paths of the one-pass entry points
+    from paper_2603_18464_amd import VlaError
+    with pytest.raises(VlaError):
+        pol.policy_step_parallel(*args, 65, ph)
+    with pytest.raises(VlaError):
+        pol.policy_step_parallel(*args, K, s.vocab)
+    with pytest.raises(VlaError):
+        pol.score_tokens(*args, old["tokens"], mu_logp=old["logp"], sigma=0.0)
     pol.close()
 
 
