@@ -120,7 +120,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the batch (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=8)
-    ap.add_argument("--prof-mask", type=lambda v: int(v, 0), default=0x1fff)
+    ap.add_argument("--prof-mask", type=lambda v: int(v, 0), default=0x3fff)
     ap.add_argument("--no-weight-update", action="store_true",
                     help="skip the (untimed, reported under detail) in-place weight update measurement")
     args = ap.parse_args()
@@ -194,7 +194,12 @@ def main():
     gemm_pre_ms = sum(v["total_ms_per_step"] for k, v in fam.items() if k.startswith("gemm") and k.endswith("_prefill"))
     dec_ms = sum(v["total_ms_per_step"] for k, v in fam.items() if k.endswith("_decode"))
     if gemm_pre_ms:
-        extra["prefill_gemm_tflops"] = 2 * nums["P"] * nums["T"] / (gemm_pre_ms * 1e-3) / 1e12
+        # flops actually executed by the tiled prefill GEMMs (the last layer's output projection and feed-forward
+        # run only on the rows that feed the head, in their own family "prefill_tail")
+        per_launch = {"gemm_qkv_prefill": nums["qkv_flops"], "gemm_o_prefill": nums["o_flops"],
+                      "gemm_gateup_prefill": nums["gateup_flops"], "gemm_down_prefill": nums["down_flops"]}
+        done = sum(per_launch[k] * fam[k]["launches"] / args.steps for k in per_launch if k in fam)
+        extra["prefill_gemm_tflops"] = done / (gemm_pre_ms * 1e-3) / 1e12
         extra["prefill_gemm_frac_of_mfma_peak"] = extra["prefill_gemm_tflops"] / PEAK_BF16_TFLOPS
     if dec_ms and nums["decode_bytes"]:
         gbs = sum(nums["decode_bytes"]) / (dec_ms * 1e-3) / 1e9

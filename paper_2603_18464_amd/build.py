@@ -21,7 +21,7 @@ def build_library(verbose: bool = False) -> str:
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
         host_only = src.endswith(".cpp")
-        flags = ["-O2", "-std=c++17", "-fPIC"] if host_only else FLAGS
+        flags = ["-O2", "-std=c++17", "-fPIC"] if host_only else FLAGS + os.environ.get("VLA_EXTRA_HIPCC_FLAGS", "").split()
         cmd = [hipcc, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:

@@ -88,8 +88,7 @@ WorkLayout work_layout(const vla_config& c) {
   w.act = take(T * f * es);
   const size_t widest = 3 * d > 2 * f ? 3 * d : 2 * f;
   w.scratch = take(c.dtype == VLA_F32 ? T * widest * 4 : 0);
-  const size_t part_rows = B < (size_t)kSkinnyMaxRows ? B : (size_t)kSkinnyMaxRows;
-  w.part = take(c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * part_rows * widest * 4 : 0);
+  w.part = take(c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * kSkinnyMaxRows * widest * 4 : 0);
   w.rope_cos = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
   w.rope_sin = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
   w.tok_seq = take(T * 4);
@@ -207,14 +206,18 @@ struct ProfScope {
 const char* kFamilyNames[FAM_COUNT] = {"gemm_qkv_prefill", "gemm_o_prefill", "gemm_gateup_prefill",
                                        "gemm_down_prefill", "attn_prefill", "gemm_qkv_decode", "gemm_o_decode",
                                        "gemm_gateup_decode", "gemm_down_decode", "attn_decode", "rmsnorm",
-                                       "head_select", "misc"};
+                                       "head_select", "misc", "prefill_tail"};
 
 template <class T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(base + off); }
 
 // ---- one pass over the layers for `rows` packed tokens (prefill: all prefix tokens; decode: B) ------
 // T is the activation type: f16 on the 16-bit path (bf16 storage), float on the float32 path.
+void run_tail_f16(vla_ctx* ctx, const LayerW& lw, const int32_t* need, int n_need, hipStream_t st);
+
+// need / n_need (prefill only): the packed rows whose final hidden state is read afterwards.  When they are
+// few, the last layer's output projection and feed-forward run on those rows alone.
 template <class T>
-int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
+int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_t* need = nullptr, int n_need = 0) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const int d = c.d_model, f = c.d_ffn;
@@ -269,6 +272,15 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st) {
       } else {
         attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
                           c.n_heads, c.head_dim, c.max_seq, false, st);
+      }
+    }
+    if constexpr (sizeof(T) == 2) {
+      const size_t pad32 = ((size_t)n_need + 31) / 32 * 32;
+      const bool fits = pad32 <= max_rows(c) &&
+                        align_up(pad32 * f * sizeof(f16)) + (size_t)n_need * d * 4 <= max_rows(c) * (size_t)f * sizeof(f16);
+      if (!decode && l == c.n_layers - 1 && need && n_need > 0 && (size_t)n_need * 2 <= (size_t)rows && fits) {
+        run_tail_f16(ctx, lw, need, n_need, st);
+        break;
       }
     }
     {
@@ -390,6 +402,37 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
   return VLA_OK;
 }
 
+// Output projection and feed-forward of one layer for n_need compact rows with the weight-streaming GEMMs.
+// Buffers that are dead at this point of the last prefill layer hold the compact set: q -> attention output in
+// fragment order, hn -> normalised rows, act -> SwiGLU output followed by the float32 residual rows.
+void run_tail_f16(vla_ctx* ctx, const LayerW& lw, const int32_t* need, int n_need, hipStream_t st) {
+  const vla_config& c = ctx->cfg;
+  const WorkLayout& w = ctx->wl;
+  const int d = c.d_model, f = c.d_ffn;
+  ProfScope ps(ctx, FAM_TAIL, st);
+  float* x = at<float>(ctx->work, w.x);
+  f16* att = at<f16>(ctx->work, w.att);
+  f16* att_frag = at<f16>(ctx->work, w.q);
+  f16* hn = at<f16>(ctx->work, w.hn);
+  f16* act = at<f16>(ctx->work, w.act);
+  float* part = at<float>(ctx->work, w.part);
+  const size_t pad32 = ((size_t)n_need + 31) / 32 * 32;
+  float* x_c = reinterpret_cast<float*>(reinterpret_cast<char*>(act) + align_up(pad32 * f * sizeof(f16)));
+  const int ks_o = skinny_ksplit(d, d), ks_gu = skinny_ksplit(2 * f, d), ks_dn = skinny_ksplit(d, f);
+  auto frag_rows = [&](f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; };
+  gather_tail(att, x, need, n_need, d, att_frag, x_c, st);
+  for (int r0 = 0; r0 < n_need; r0 += kSkinnyMaxRows) {
+    const int m = n_need - r0 < kSkinnyMaxRows ? n_need - r0 : kSkinnyMaxRows;
+    skinny_gemm(frag_rows(att_frag, r0, d), at<f16>(ctx->arena, lw.w_o), part, m, d, d, ks_o, st);
+    reduce_resid_norm(part, ks_o, m, d, x_c, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, r0, st);
+    skinny_gemm(frag_rows(hn, r0, d), at<f16>(ctx->arena, lw.w_gu), part, m, 2 * f, d, ks_gu, st);
+    reduce_swiglu(part, ks_gu, m, f, act, r0, st);
+    skinny_gemm(frag_rows(act, r0, f), at<f16>(ctx->arena, lw.w_down), part, m, d, f, ks_dn, st);
+    reduce_resid_norm(part, ks_dn, m, d, x_c, nullptr, c.rms_eps, hn, r0, st);
+  }
+  scatter_tail(x_c, need, n_need, d, x, st);
+}
+
 template <class T>
 void run_head(vla_ctx* ctx, int B, const int32_t* row_index, float* logits, int ld, hipStream_t st) {
   const vla_config& c = ctx->cfg;
@@ -475,6 +518,7 @@ template <class T>
 int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
                const int32_t* cu_instr, int64_t T_tokens, float* logits, int ld_logits, hipStream_t st,
                const int32_t* tail = nullptr, int n_tail = 0) {
+  const int n_last = n_tail + 1;   // rows per sequence whose final hidden state is read: the last n_tail + 1
   // With a tail, cu_instr already counts n_tail extra ids per sequence (device array tail[B, n_tail]) and the
   // id stream the layers see is the merge of instr_ids and tail.
   const vla_config& c = ctx->cfg;
@@ -512,7 +556,13 @@ int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu
     const int S = (cu_patch[b + 1] - cu_patch[b]) + (cu_instr[b + 1] - cu_instr[b]);
     if (S > ctx->run_max_len) ctx->run_max_len = S;
   }
-  run_layers<typename ActOf<T>::type>(ctx, (int)T_tokens, false, st);
+  const int32_t* need = at<int32_t>(ctx->work, w.last_row);
+  if (n_last > 1) {
+    ProfScope ps(ctx, FAM_MISC, st);
+    chunk_rows(at<int32_t>(ctx->work, w.last_row), B, n_last, at<int32_t>(ctx->work, w.chunk_rows), st);
+    need = at<int32_t>(ctx->work, w.chunk_rows);
+  }
+  run_layers<typename ActOf<T>::type>(ctx, (int)T_tokens, false, st, need, B * n_last);
   if (logits) run_head<T>(ctx, B, at<int32_t>(ctx->work, w.last_row), logits, ld_logits, st);
   HIP_TRY(ctx, hipGetLastError());
   ctx->active_B = B;
@@ -561,11 +611,8 @@ int do_chunk(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_p
   int rc = do_prefill<T>(ctx, B, patch_emb, cu_patch, instr_ids, cu2.data(), T_prefix + (int64_t)B * n_tail, nullptr, 0,
                          st, tail, n_tail);
   if (rc) return rc;
-  int32_t* rows = at<int32_t>(ctx->work, w.chunk_rows);
-  {
-    ProfScope ps(ctx, FAM_MISC, st);
-    chunk_rows(at<int32_t>(ctx->work, w.last_row), B, K, rows, st);
-  }
+  // the emitting rows were listed by do_prefill (K > 1) or are the last rows (K == 1)
+  const int32_t* rows = K > 1 ? at<int32_t>(ctx->work, w.chunk_rows) : at<int32_t>(ctx->work, w.last_row);
   run_head<T>(ctx, B * K, rows, logits, A, st);
   HIP_TRY(ctx, hipGetLastError());
   return VLA_OK;

@@ -54,6 +54,7 @@ enum Family {
   FAM_NORM,
   FAM_HEAD,
   FAM_MISC,
+  FAM_TAIL,      // last prefill layer restricted to the rows that feed the head
   FAM_COUNT
 };
 
@@ -152,6 +153,11 @@ template <class T>
 void value_finish(const float* vz, const float* vml, const T* step_emb, int n_steps, const int32_t* step_t,
                   const T* w1, const float* b1, const float* w2, const float* b2, int B, int d, float* vu, float* vh,
                   float* values, hipStream_t st);
+
+// Last prefill layer, compact rows: gather attention output (to fragment order) and residual rows, scatter back.
+void gather_tail(const f16* att, const float* x, const int32_t* need, int n, int d, f16* att_frag, float* x_c,
+                 hipStream_t st);
+void scatter_tail(const float* x_c, const int32_t* need, int n, int d, float* x, hipStream_t st);
 
 // Chunk pass (all K action rows in one forward): merged id stream, fed-token buffer, emitting rows, scoring.
 void merge_tail_ids(const int32_t* instr_ids, const int32_t* cu2_dev, const int32_t* tail, int B, int n_tail,

@@ -481,12 +481,10 @@ constexpr int PK = 32;                       // slab depth
 constexpr int P_STAGES = 4;
 constexpr int P_STAGE_HALVES = 256 * PK;     // per operand
 
-// Issues the 12 fragment reads of one slab (no wait).  The destination registers must not be touched
-// until frags_arrived() has been executed on them.
-template <int MT, int NT>
-__device__ __forceinline__ void read_frags_asm(f16x8 (&af)[2][MT], f16x8 (&bfr)[2][NT], unsigned a0, unsigned a1,
+// Issues the fragment reads of one slab (no wait).  The destination registers must not be touched
+// until frags_arrived() has been executed on them.  Two wave tiles are supported: 64x128 and 128x128.
+__device__ __forceinline__ void read_frags_asm(f16x8 (&af)[2][2], f16x8 (&bfr)[2][4], unsigned a0, unsigned a1,
                                                unsigned w) {
-  static_assert(MT == 2 && NT == 4, "written for the 64x128 wave tile");
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile(
       "ds_read_b128 %0, %12\n\t"
@@ -507,17 +505,61 @@ __device__ __forceinline__ void read_frags_asm(f16x8 (&af)[2][MT], f16x8 (&bfr)[
       : "memory");
 #endif
 }
+__device__ __forceinline__ void read_frags_asm(f16x8 (&af)[2][4], f16x8 (&bfr)[2][4], unsigned a0, unsigned a1,
+                                               unsigned w) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile(
+      "ds_read_b128 %0, %16\n\t"
+      "ds_read_b128 %1, %16 offset:2048\n\t"
+      "ds_read_b128 %8, %18\n\t"
+      "ds_read_b128 %9, %18 offset:2048\n\t"
+      "ds_read_b128 %2, %16 offset:4096\n\t"
+      "ds_read_b128 %3, %16 offset:6144\n\t"
+      "ds_read_b128 %10, %18 offset:4096\n\t"
+      "ds_read_b128 %11, %18 offset:6144\n\t"
+      "ds_read_b128 %4, %17\n\t"
+      "ds_read_b128 %5, %17 offset:2048\n\t"
+      "ds_read_b128 %12, %18 offset:1024\n\t"
+      "ds_read_b128 %13, %18 offset:3072\n\t"
+      "ds_read_b128 %6, %17 offset:4096\n\t"
+      "ds_read_b128 %7, %17 offset:6144\n\t"
+      "ds_read_b128 %14, %18 offset:5120\n\t"
+      "ds_read_b128 %15, %18 offset:7168"
+      : "=&v"(af[0][0]), "=&v"(af[0][1]), "=&v"(af[0][2]), "=&v"(af[0][3]), "=&v"(af[1][0]), "=&v"(af[1][1]),
+        "=&v"(af[1][2]), "=&v"(af[1][3]), "=&v"(bfr[0][0]), "=&v"(bfr[0][1]), "=&v"(bfr[0][2]), "=&v"(bfr[0][3]),
+        "=&v"(bfr[1][0]), "=&v"(bfr[1][1]), "=&v"(bfr[1][2]), "=&v"(bfr[1][3])
+      : "v"(a0), "v"(a1), "v"(w)
+      : "memory");
+#endif
+}
 
 // Waits for every outstanding LDS read of this wave; the fragments are in/out operands so that nothing
 // that uses them can be scheduled above the wait.
-template <int MT, int NT>
-__device__ __forceinline__ void frags_arrived(f16x8 (&af)[2][MT], f16x8 (&bfr)[2][NT]) {
+__device__ __forceinline__ void frags_arrived(f16x8 (&af)[2][2], f16x8 (&bfr)[2][4]) {
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("s_waitcnt lgkmcnt(0)"
                : "+v"(af[0][0]), "+v"(af[0][1]), "+v"(af[1][0]), "+v"(af[1][1]), "+v"(bfr[0][0]), "+v"(bfr[0][1]),
                  "+v"(bfr[0][2]), "+v"(bfr[0][3]), "+v"(bfr[1][0]), "+v"(bfr[1][1]), "+v"(bfr[1][2]), "+v"(bfr[1][3])
                :
                : "memory");
+#endif
+}
+__device__ __forceinline__ void frags_arrived(f16x8 (&af)[2][4], f16x8 (&bfr)[2][4]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(af[0][0]), "+v"(af[0][1]), "+v"(af[0][2]), "+v"(af[0][3]), "+v"(af[1][0]), "+v"(af[1][1]),
+                 "+v"(af[1][2]), "+v"(af[1][3]), "+v"(bfr[0][0]), "+v"(bfr[0][1]), "+v"(bfr[0][2]), "+v"(bfr[0][3]),
+                 "+v"(bfr[1][0]), "+v"(bfr[1][1]), "+v"(bfr[1][2]), "+v"(bfr[1][3])
+               :
+               : "memory");
+#endif
+}
+
+// One fragment read with a compile-time byte offset (no wait; see frags_arrived).
+template <int OFF>
+__device__ __forceinline__ void read_frag_asm(f16x8& dst, unsigned addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
 #endif
 }
 
@@ -528,11 +570,11 @@ __device__ __forceinline__ void wait_vmcnt() {
 #endif
 }
 
-template <class Epi>
-__global__ __launch_bounds__(512, 1) void gemm_f16_pipe_kernel(const f16* __restrict__ A, int lda,
-                                                              const f16* __restrict__ Wp, int M, int N, int K,
-                                                              int tiles_m, int tiles_n, Epi epi) {
-  constexpr int BM = 256, BN = 256, WGM = 4, WGN = 2, NW = 8;
+template <int WGM, int WGN, class Epi>
+__global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const f16* __restrict__ A, int lda,
+                                                                         const f16* __restrict__ Wp, int M, int N,
+                                                                         int K, int tiles_m, int tiles_n, Epi epi) {
+  constexpr int BM = 256, BN = 256, NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
   constexpr int A_INSTR = (BM / 16) / NW;      // 16 rows per load instruction -> 2 per wave
   constexpr int W_INSTR = (BN * PK * 2 / 1024) / NW;   // 2 per wave
@@ -611,28 +653,112 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_pipe_kernel(const f16* __rest
       for (int nt = 0; nt < NT; ++nt)
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[f][kk][mt], bfr[f][kk][nt], acc[mt][nt], 0, 0, 0);
   };
+  // One workgroup-wide slab step.  With two waves per SIMD (8 waves) the other wave's MFMAs cover this wave's
+  // bursts of fragment reads and load issues; with one wave per SIMD (4 waves, 128x128 wave tile) every read and
+  // every load is slotted between two MFMAs instead, so the matrix pipe never waits for the issue of a burst.
+  auto issue_one = [&](int kt, int i) {      // i-th load instruction of slab kt (A first, then W)
+    const int buf = kt & (P_STAGES - 1);
+    const int ks = min(kt, KT - 1);
+    if (i < A_INSTR)
+      load_to_lds_16(a_src[i] + (size_t)ks * PK, As + buf * P_STAGE_HALVES + (wave * A_INSTR + i) * 512);
+    else
+      load_to_lds_16(w_src[i - A_INSTR] + (size_t)ks * 2 * 512,
+                     Ws + buf * P_STAGE_HALVES + (wave * W_INSTR + i - A_INSTR) * 512);
+  };
   auto step = [&](int kt, int f) {           // f = kt & 1, passed as a constant by the unrolled caller
     wait_vmcnt<LPS>();                       // this wave's loads of slab kt+1 have landed (kt+2 may be in flight)
     __builtin_amdgcn_s_barrier();            // ... everyone's have; everyone holds slab kt in registers
-    {
+    if constexpr (NW == 8) {
+#if defined(VLA_GEMM_BURST)
+      {
+        const unsigned so = stage_off(kt + 1);
+        read_frags_asm(af[f ^ 1], bfr[f ^ 1], a_k0 + so, a_k1 + so, w_b + so);
+      }
+      mfma_half(f, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      issue(kt + 3);                         // refill the buffer slab kt-1 lived in
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_half(f, 1);
+      __builtin_amdgcn_sched_barrier(0);
+#else
+      // 16 MFMAs, and between them the 12 fragment reads of slab kt+1 and the 4 loads of slab kt+3, one each
       const unsigned so = stage_off(kt + 1);
-      read_frags_asm<MT, NT>(af[f ^ 1], bfr[f ^ 1], a_k0 + so, a_k1 + so, w_b + so);
+      const unsigned ra0 = a_k0 + so, ra1 = a_k1 + so, rw = w_b + so;
+#define VLA_MF(kk, mt, nt) \
+  acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[f][kk][mt], bfr[f][kk][nt], acc[mt][nt], 0, 0, 0)
+#define VLA_SB __builtin_amdgcn_sched_barrier(0)
+      VLA_MF(0, 0, 0); read_frag_asm<0>(af[f ^ 1][0][0], ra0); VLA_SB;
+      VLA_MF(0, 0, 1); read_frag_asm<0>(bfr[f ^ 1][0][0], rw); VLA_SB;
+      VLA_MF(0, 0, 2); read_frag_asm<2048>(af[f ^ 1][0][1], ra0); VLA_SB;
+      VLA_MF(0, 0, 3); read_frag_asm<2048>(bfr[f ^ 1][0][1], rw); VLA_SB;
+      VLA_MF(0, 1, 0); read_frag_asm<4096>(bfr[f ^ 1][0][2], rw); VLA_SB;
+      VLA_MF(0, 1, 1); read_frag_asm<6144>(bfr[f ^ 1][0][3], rw); VLA_SB;
+      VLA_MF(0, 1, 2); read_frag_asm<0>(af[f ^ 1][1][0], ra1); VLA_SB;
+      VLA_MF(0, 1, 3); read_frag_asm<2048>(af[f ^ 1][1][1], ra1); VLA_SB;
+      VLA_MF(1, 0, 0); read_frag_asm<1024>(bfr[f ^ 1][1][0], rw); VLA_SB;
+      VLA_MF(1, 0, 1); issue_one(kt + 3, 0); VLA_SB;
+      VLA_MF(1, 0, 2); read_frag_asm<3072>(bfr[f ^ 1][1][1], rw); VLA_SB;
+      VLA_MF(1, 0, 3); issue_one(kt + 3, 1); VLA_SB;
+      VLA_MF(1, 1, 0); read_frag_asm<5120>(bfr[f ^ 1][1][2], rw); VLA_SB;
+      VLA_MF(1, 1, 1); issue_one(kt + 3, 2); VLA_SB;
+      VLA_MF(1, 1, 2); read_frag_asm<7168>(bfr[f ^ 1][1][3], rw); VLA_SB;
+      VLA_MF(1, 1, 3); issue_one(kt + 3, 3); VLA_SB;
+#undef VLA_MF
+#undef VLA_SB
+#endif
+    } else {
+      static_assert(NW == 8 || (MT == 4 && NT == 4 && LPS == 8), "interleaved schedule is written for 128x128 wave tiles");
+      const unsigned so = stage_off(kt + 1);
+      const unsigned ra0 = a_k0 + so, ra1 = a_k1 + so, rw = w_b + so;
+      // first k-step of slab kt: 16 MFMAs, the 16 fragment reads of slab kt+1 between them
+#define VLA_MF(kk, mt, nt) \
+  acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[f][kk][mt], bfr[f][kk][nt], acc[mt][nt], 0, 0, 0)
+#define VLA_SB __builtin_amdgcn_sched_barrier(0)
+      VLA_MF(0, 0, 0); read_frag_asm<0>(af[f ^ 1][0][0], ra0); VLA_SB;
+      VLA_MF(0, 0, 1); read_frag_asm<0>(bfr[f ^ 1][0][0], rw); VLA_SB;
+      VLA_MF(0, 0, 2); read_frag_asm<2048>(af[f ^ 1][0][1], ra0); VLA_SB;
+      VLA_MF(0, 0, 3); read_frag_asm<2048>(bfr[f ^ 1][0][1], rw); VLA_SB;
+      VLA_MF(0, 1, 0); read_frag_asm<4096>(af[f ^ 1][0][2], ra0); VLA_SB;
+      VLA_MF(0, 1, 1); read_frag_asm<4096>(bfr[f ^ 1][0][2], rw); VLA_SB;
+      VLA_MF(0, 1, 2); read_frag_asm<6144>(af[f ^ 1][0][3], ra0); VLA_SB;
+      VLA_MF(0, 1, 3); read_frag_asm<6144>(bfr[f ^ 1][0][3], rw); VLA_SB;
+      VLA_MF(0, 2, 0); read_frag_asm<0>(af[f ^ 1][1][0], ra1); VLA_SB;
+      VLA_MF(0, 2, 1); read_frag_asm<1024>(bfr[f ^ 1][1][0], rw); VLA_SB;
+      VLA_MF(0, 2, 2); read_frag_asm<2048>(af[f ^ 1][1][1], ra1); VLA_SB;
+      VLA_MF(0, 2, 3); read_frag_asm<3072>(bfr[f ^ 1][1][1], rw); VLA_SB;
+      VLA_MF(0, 3, 0); read_frag_asm<4096>(af[f ^ 1][1][2], ra1); VLA_SB;
+      VLA_MF(0, 3, 1); read_frag_asm<5120>(bfr[f ^ 1][1][2], rw); VLA_SB;
+      VLA_MF(0, 3, 2); read_frag_asm<6144>(af[f ^ 1][1][3], ra1); VLA_SB;
+      VLA_MF(0, 3, 3); read_frag_asm<7168>(bfr[f ^ 1][1][3], rw); VLA_SB;
+      // second k-step: 16 MFMAs, the 8 loads of slab kt+3 between every other pair
+      VLA_MF(1, 0, 0); issue_one(kt + 3, 0); VLA_SB;
+      VLA_MF(1, 0, 1); VLA_SB;
+      VLA_MF(1, 0, 2); issue_one(kt + 3, 1); VLA_SB;
+      VLA_MF(1, 0, 3); VLA_SB;
+      VLA_MF(1, 1, 0); issue_one(kt + 3, 2); VLA_SB;
+      VLA_MF(1, 1, 1); VLA_SB;
+      VLA_MF(1, 1, 2); issue_one(kt + 3, 3); VLA_SB;
+      VLA_MF(1, 1, 3); VLA_SB;
+      VLA_MF(1, 2, 0); issue_one(kt + 3, 4); VLA_SB;
+      VLA_MF(1, 2, 1); VLA_SB;
+      VLA_MF(1, 2, 2); issue_one(kt + 3, 5); VLA_SB;
+      VLA_MF(1, 2, 3); VLA_SB;
+      VLA_MF(1, 3, 0); issue_one(kt + 3, 6); VLA_SB;
+      VLA_MF(1, 3, 1); VLA_SB;
+      VLA_MF(1, 3, 2); issue_one(kt + 3, 7); VLA_SB;
+      VLA_MF(1, 3, 3); VLA_SB;
+#undef VLA_MF
+#undef VLA_SB
     }
-    mfma_half(f, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    issue(kt + 3);                           // refill the buffer slab kt-1 lived in
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half(f, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    frags_arrived<MT, NT>(af[f ^ 1], bfr[f ^ 1]);
+    frags_arrived(af[f ^ 1], bfr[f ^ 1]);
   };
   issue(0);
   issue(1);
   issue(2);
   wait_vmcnt<2 * LPS>();
   __builtin_amdgcn_s_barrier();
-  read_frags_asm<MT, NT>(af[0], bfr[0], a_k0, a_k1, w_b);
-  frags_arrived<MT, NT>(af[0], bfr[0]);
+  read_frags_asm(af[0], bfr[0], a_k0, a_k1, w_b);
+  frags_arrived(af[0], bfr[0]);
   for (int kt = 0; kt < KT; kt += 2) {       // K is a multiple of 64: KT is even
     step(kt, 0);
     step(kt + 1, 1);
@@ -647,21 +773,21 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_pipe_kernel(const f16* __rest
   }
 }
 
-template <class Epi>
+template <int WGM, int WGN, class Epi>
 static void launch_pipe(const GemmF16& g, const Epi& epi, hipStream_t st) {
   const int tiles_m = (g.M + 255) / 256, tiles_n = g.N / 256;
   const int nblk = tiles_m * tiles_n;
   const int grid = (nblk + 7) / 8 * 8;
   constexpr size_t slabs = 2 * (size_t)P_STAGES * P_STAGE_HALVES * sizeof(f16);
-  constexpr size_t stage = 8 * (size_t)kStageFloats * sizeof(float);
+  constexpr size_t stage = (size_t)WGM * WGN * kStageFloats * sizeof(float);
   constexpr size_t smem = slabs > stage ? slabs : stage;
-  auto kern = gemm_f16_pipe_kernel<Epi>;
+  auto kern = gemm_f16_pipe_kernel<WGM, WGN, Epi>;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, tiles_m, tiles_n, epi);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, tiles_m, tiles_n, epi);
 }
 
 template <int WGM, int WGN, class Epi>
@@ -698,31 +824,35 @@ static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
 
 // Tile choice: big square tiles when there are enough rows to fill them, a 64-row tile for the
 // decode-sized problems.  The QKV epilogue needs wave tiles that cover whole heads (128 columns).
-template <class Epi>
+// kWaves4: the 4-wave (128x128 wave tile) schedule reads a third less from LDS per MFMA and is the faster one
+// for the residual and SwiGLU epilogues; the QKV epilogue measures marginally faster with 8 waves.
+template <bool kWaves4, class Epi>
 static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
-  if (g.M > 128 && g.N % 256 == 0)
+  if (g.M > 128 && g.N % 256 == 0) {
 #if defined(VLA_GEMM_NO_DMA)
     launch<256, 256, 4, 2, Epi>(g, epi, st);
 #elif defined(VLA_GEMM_DMA2)
     launch_dma<4, 2, Epi>(g, epi, st);
 #else
-    launch_pipe<Epi>(g, epi, st);
+    if (kWaves4) launch_pipe<2, 2, Epi>(g, epi, st);
+    else launch_pipe<4, 2, Epi>(g, epi, st);
 #endif
-  else if (g.N % 256 == 0)
+  } else if (g.N % 256 == 0) {
     launch<64, 256, 2, 2, Epi>(g, epi, st);
-  else
+  } else {
     launch<64, 128, 2, 1, Epi>(g, epi, st);   // N multiple of 128
+  }
 }
 
 void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st) {
-  dispatch(g, EpiResid{x, ldx}, st);
+  dispatch<true>(g, EpiResid{x, ldx}, st);
 }
 void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, hipStream_t st) {
-  dispatch(g, EpiSwiglu{act, ldact}, st);
+  dispatch<true>(g, EpiSwiglu{act, ldact}, st);
 }
 void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st) {
-  if (o.head_dim == 128) dispatch(g, EpiQkv<128>{o}, st);
-  else dispatch(g, EpiQkv<64>{o}, st);
+  if (o.head_dim == 128) dispatch<false>(g, EpiQkv<128>{o}, st);
+  else dispatch<false>(g, EpiQkv<64>{o}, st);
 }
 
 // ---- weight repacking -------------------------------------------------------------------------------

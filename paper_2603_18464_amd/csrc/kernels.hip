@@ -129,6 +129,37 @@ template void assemble_prefix<float>(const float*, const int32_t*, const float*,
 template void assemble_prefix<bf16>(const bf16*, const int32_t*, const bf16*, const int32_t*, float*, int, int,
                                     int, hipStream_t);
 
+// ---- last-layer tail: only the rows that feed the head go through the last O / feed-forward ------------
+// Row i of the compact set is packed row need[i]: its attention output goes to fragment order
+// [i/32][k/16][lane][8] (what the weight-streaming GEMMs read), its residual row to x_c[i].
+__global__ __launch_bounds__(256) void gather_tail_kernel(const f16* __restrict__ att, const float* __restrict__ x,
+                                                          const int32_t* __restrict__ need, int d,
+                                                          f16* __restrict__ att_frag, float* __restrict__ x_c) {
+  const int i = blockIdx.x, src = need[i];
+  const u32x4* arow = (const u32x4*)(att + (size_t)src * d);
+  u32x4* ablk = (u32x4*)(att_frag + (size_t)(i >> 5) * (d >> 4) * 512);
+  for (int kc = threadIdx.x; kc < (d >> 3); kc += blockDim.x)
+    ablk[(size_t)(kc >> 1) * 64 + (i & 31) + 32 * (kc & 1)] = arow[kc];
+  const f32x4* xr = (const f32x4*)(x + (size_t)src * d);
+  f32x4* xo = (f32x4*)(x_c + (size_t)i * d);
+  for (int j = threadIdx.x; j < (d >> 2); j += blockDim.x) xo[j] = xr[j];
+}
+void gather_tail(const f16* att, const float* x, const int32_t* need, int n, int d, f16* att_frag, float* x_c,
+                 hipStream_t st) {
+  hipLaunchKernelGGL(gather_tail_kernel, dim3(n), dim3(256), 0, st, att, x, need, d, att_frag, x_c);
+}
+__global__ __launch_bounds__(256) void scatter_tail_kernel(const float* __restrict__ x_c,
+                                                           const int32_t* __restrict__ need, int d,
+                                                           float* __restrict__ x) {
+  const int i = blockIdx.x;
+  const f32x4* xr = (const f32x4*)(x_c + (size_t)i * d);
+  f32x4* xo = (f32x4*)(x + (size_t)need[i] * d);
+  for (int j = threadIdx.x; j < (d >> 2); j += blockDim.x) xo[j] = xr[j];
+}
+void scatter_tail(const float* x_c, const int32_t* need, int n, int d, float* x, hipStream_t st) {
+  hipLaunchKernelGGL(scatter_tail_kernel, dim3(n), dim3(256), 0, st, x_c, need, d, x);
+}
+
 // ---- chunk pass: every sequence is [prefix ; n_tail fed tokens], logits wanted at its last n_tail + 1 rows ----
 // cu2[b] = cu_instr[b] + b * n_tail are the offsets of the merged id stream.
 __global__ void merge_tail_kernel(const int32_t* __restrict__ instr_ids, const int32_t* __restrict__ cu2,
