@@ -860,28 +860,34 @@ void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st) {
 // the exponent only, and f16 has more mantissa bits than bf16; values beyond +-255 saturate) and
 // stores them in fragment order starting at packed row `row0`.  interleave_mode 0: packed row =
 // row0 + r.  1 (gate) / 2 (up): rows go to the even / odd 32-row blocks of the fused gate-up matrix.
-__global__ void pack_weight_kernel(const bf16* __restrict__ src, int rows, int K, f16* __restrict__ dst,
-                                   int row0, int mode) {
-  const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // 8 consecutive k of one row
-  const int kchunks = K >> 3;
-  if (chunk >= (size_t)rows * kchunks) return;
-  const int r = (int)(chunk / kchunks), kc = (int)(chunk % kchunks);
-  int pr;
-  if (mode == 0) pr = row0 + r;
-  else pr = (r / 32) * 64 + (mode == 2 ? 32 : 0) + (r & 31);
-  const int nb = pr >> 5, kb = kc >> 1, lane = (pr & 31) + 32 * (kc & 1);
-  const bf16x8 v = *(const bf16x8*)(src + (size_t)r * K + kc * 8);
-  f16x8 o;
+// One workgroup re-encodes 32 source rows x 512 k: 128-byte row segments are read coalesced, transposed through
+// LDS, and each 1 KiB fragment block is written by one wave in one piece.
+__global__ __launch_bounds__(256) void pack_weight_kernel(const bf16* __restrict__ src, int K,
+                                                          f16* __restrict__ dst, int row0, int mode) {
+  __shared__ u32x4 tile[32 * 8];
+  const int r0 = blockIdx.x * 32;                       // first source row of this workgroup
+  const int nb = mode == 0 ? (row0 + r0) >> 5 : (r0 >> 5) * 2 + (mode == 2 ? 1 : 0);
+  const int t = threadIdx.x, rr = t >> 3, cc = t & 7;   // load role: row, 16-byte chunk of a 64-k span
+  const int blk = t >> 6, lane = t & 63;                // store role: fragment block of the span, lane
+  const int k_end = min(K, (int)(blockIdx.y + 1) * 512);
+  for (int k0 = blockIdx.y * 512; k0 < k_end; k0 += 64) {
+    const bf16x8 v = *(const bf16x8*)(src + (size_t)(r0 + rr) * K + k0 + cc * 8);
+    f16x8 o;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) o[j] = from_f32<f16>((float)v[j] * kWeightScale);
-  *(f16x8*)(dst + ((size_t)nb * (K >> 4) + kb) * 512 + lane * 8) = o;
+    for (int j = 0; j < 8; ++j) o[j] = from_f32<f16>((float)v[j] * kWeightScale);
+    __syncthreads();                                    // the previous span has been read out
+    tile[rr * 8 + (cc ^ (rr & 7))] = __builtin_bit_cast(u32x4, o);
+    __syncthreads();
+    const int sr = lane & 31, sc = 2 * blk + (lane >> 5);
+    *(u32x4*)(dst + ((size_t)nb * (K >> 4) + (k0 >> 4) + blk) * 512 + lane * 8) = tile[sr * 8 + (sc ^ (sr & 7))];
+  }
 }
 
 void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode,
                      hipStream_t st) {
-  const size_t chunks = (size_t)rows * (K >> 3);
-  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, src,
-                     rows, K, dst, row0, interleave_mode);
+  // rows, row0 multiples of 32 and K a multiple of 64: guaranteed by the configuration checks
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)(rows / 32), (unsigned)((K + 511) / 512)), dim3(256), 0, st,
+                     src, K, dst, row0, interleave_mode);
 }
 
 }  // namespace vla

@@ -282,25 +282,39 @@ template <class T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                       T* __restrict__ out, int d, float eps,
                                                       const int32_t* __restrict__ row_index) {
+  typedef __attribute__((ext_vector_type(4))) T T4;
   __shared__ float red[4];
   const int r = blockIdx.x;
   const float* row = x + (size_t)(row_index ? row_index[r] : r) * d;
+  constexpr int kHeld = 8;                 // float4 per thread kept in registers: rows up to 8192 wide are read once
+  f32x4 held[kHeld];
   float ss = 0.f;
-  for (int i = threadIdx.x * 4; i < d; i += 1024) {
-    const float4 v = *(const float4*)(row + i);
-    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+  for (int it = 0; it < kHeld; ++it) {
+    const int i = threadIdx.x * 4 + it * 1024;
+    held[it] = i < d ? *(const f32x4*)(row + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+    ss += held[it][0] * held[it][0] + held[it][1] * held[it][1] + held[it][2] * held[it][2] + held[it][3] * held[it][3];
+  }
+  for (int i = threadIdx.x * 4 + kHeld * 1024; i < d; i += 1024) {
+    const f32x4 v = *(const f32x4*)(row + i);
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
   }
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
   T* o = out + (size_t)r * d;
-  for (int i = threadIdx.x * 4; i < d; i += 1024) {
-    const float4 v = *(const float4*)(row + i);
-    const float4 g = *(const float4*)(gain + i);
-    o[i] = from_f32<T>(v.x * inv * g.x);
-    o[i + 1] = from_f32<T>(v.y * inv * g.y);
-    o[i + 2] = from_f32<T>(v.z * inv * g.z);
-    o[i + 3] = from_f32<T>(v.w * inv * g.w);
+  auto emit = [&](int i, const f32x4& v) {
+    const f32x4 g = *(const f32x4*)(gain + i);
+    T4 q;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) q[j] = from_f32<T>(v[j] * inv * g[j]);
+    *(T4*)(o + i) = q;
+  };
+#pragma unroll
+  for (int it = 0; it < kHeld; ++it) {
+    const int i = threadIdx.x * 4 + it * 1024;
+    if (i < d) emit(i, held[it]);
   }
+  for (int i = threadIdx.x * 4 + kHeld * 1024; i < d; i += 1024) emit(i, *(const f32x4*)(row + i));
 }
 template <class T>
 void rmsnorm(const float* x, const T*, const float* gain, T* out, int rows, int d, float eps,
