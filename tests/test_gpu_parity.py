@@ -95,6 +95,18 @@ def test_bf16_small_ragged_spans_tiles(hd, heads):
     run_both(wl, obs=obs, gumbel=gum)
 
 
+def test_bf16_tiny_prefixes_keep_every_row_in_the_last_layer():
+    """Prefixes of 1-3 tokens: more than half of the packed rows feed the head, so the last layer is not
+    restricted to them (the other branch of the prefill), and all GEMMs take the small-tile path."""
+    shape = W.PolicyShape(3, 256, 2, 128, 704, 1024, dtype="bf16")
+    nps, lens = [1, 1, 1, 2, 1, 1], [0, 1, 0, 1, 1, 0]
+    wl = W.Workload("Tt", 19, shape, batch=len(lens), n_patches=2, instr_len=(0, 1), n_tokens=5,
+                    sampling="gumbel", temperature=0.8)
+    obs = ragged_obs(wl, nps, lens, seed=83)
+    assert int(obs["cu_patch"][-1] + obs["cu_instr"][-1]) < 2 * wl.batch
+    run_both(wl, obs=obs, gumbel=W.make_gumbel(wl))
+
+
 @pytest.mark.timeout(600)
 def test_c2_bf16_whole_batch():
     wl = W.get_workload("C2")
