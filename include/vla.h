@@ -87,8 +87,9 @@ int vla_destroy(vla_ctx* ctx);
 const char* vla_last_error(const vla_ctx* ctx);
 
 /* Bytes the caller must provide (each buffer 256-byte aligned): the weight arena (repacked
- * weights, only the action rows of the head), the KV cache [layer][slot][head][position][head_dim]
- * in the storage dtype, and the activation workspace. */
+ * weights, only the action rows of the head), the KV cache [layer][K|V][slot][head][position][head_dim]
+ * in the storage dtype (the position extent is max_seq rounded up to an odd number, which keeps the
+ * blocks of different heads on different memory channels), and the activation workspace. */
 int vla_query_sizes(const vla_config* cfg, size_t* weight_arena_bytes, size_t* kv_bytes,
                     size_t* workspace_bytes);
 int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace);

@@ -63,9 +63,15 @@ ArenaLayout arena_layout(const vla_config& c) {
   a.total = off;
   return a;
 }
+// Positions per (slot, head) block of the KV cache.  Kept odd: the blocks of the (slot, head) pairs that are
+// streamed concurrently then start an odd number of 256-byte rows apart and spread over all memory channels
+// (an even max_seq such as 352 made every workgroup hit the same channels at the same time: 3.1 instead of
+// 5.1 TB/s in decode attention).
+inline int kv_pitch(const vla_config& c) { return c.max_seq | 1; }
+
 
 size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one layer
-  return (size_t)c.max_batch * c.n_heads * c.max_seq * c.head_dim;
+  return (size_t)c.max_batch * c.n_heads * kv_pitch(c) * c.head_dim;
 }
 size_t kv_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
 
@@ -128,7 +134,7 @@ const char* check_config(const vla_config& c) {
     if (c.head_dim != 64 && c.head_dim != 128) return "bf16 path needs head_dim 64 or 128";
     if (c.d_model % 128 || c.d_ffn % 64) return "bf16 path needs d_model % 128 == 0 and d_ffn % 64 == 0";
   }
-  if ((size_t)(c.head_dim + c.max_seq) * 16 > 64 * 1024) return "max_seq too large for the attention kernel's LDS";
+  if ((size_t)(c.head_dim + kv_pitch(c)) * 16 > 64 * 1024) return "max_seq too large for the attention kernel's LDS";
   if ((int64_t)c.d_model * 4 > 64 * 1024) return "d_model too large for the head kernel's LDS";
   return nullptr;
 }
@@ -244,7 +250,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     rk.rope_sin = at<float>(ctx->work, w.rope_sin);
     rk.n_heads = c.n_heads;
     rk.head_dim = c.head_dim;
-    rk.max_seq = c.max_seq;
+    rk.max_seq = kv_pitch(c);
     rk.d_model = d;
     {
       ProfScope ps(ctx, FAM_NORM, st);
@@ -265,13 +271,13 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
         if (!decode)
           flash_prefill((const f16*)q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache,
                         at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), (f16*)att, d,
-                        ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim, c.max_seq, st);
+                        ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim, kv_pitch(c), st);
         else
           attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
-                            c.n_heads, c.head_dim, c.max_seq, false, st);
+                            c.n_heads, c.head_dim, kv_pitch(c), false, st);
       } else {
         attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
-                          c.n_heads, c.head_dim, c.max_seq, false, st);
+                          c.n_heads, c.head_dim, kv_pitch(c), false, st);
       }
     }
     if constexpr (sizeof(T) == 2) {
@@ -351,7 +357,7 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
     rk.rope_sin = at<float>(ctx->work, w.rope_sin);
     rk.n_heads = c.n_heads;
     rk.head_dim = c.head_dim;
-    rk.max_seq = c.max_seq;
+    rk.max_seq = kv_pitch(c);
     rk.d_model = d;
     // GEMMs and their reduce kernels run on chunks of at most kSkinnyMaxRows rows (the weights are streamed
     // once per chunk); attention runs on the whole batch.
@@ -368,10 +374,10 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
       if (c.max_seq <= decode_attention_max_ctx(c.head_dim))
         decode_attention(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_pos, att, B, d, c.n_heads,
-                         c.head_dim, c.max_seq, st);
+                         c.head_dim, kv_pitch(c), st);
       else
         attention_rows<f16>(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, d, B,
-                            c.n_heads, c.head_dim, c.max_seq, true, st);
+                            c.n_heads, c.head_dim, kv_pitch(c), true, st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_O_DECODE, st);

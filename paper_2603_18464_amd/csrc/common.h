@@ -67,7 +67,7 @@ struct RopeKv {
   const int32_t* tok_pos;   // [T] position of each packed token inside its sequence
   const float* rope_cos;    // [max_seq, head_dim/2]
   const float* rope_sin;
-  int n_heads, head_dim, max_seq, d_model;
+  int n_heads, head_dim, max_seq, d_model;   // max_seq: positions per (slot, head) block of the cache (its pitch)
 };
 
 // The 16-bit path keeps weights as bfloat16 at the boundary but feeds the matrix cores in half
