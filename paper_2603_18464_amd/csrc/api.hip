@@ -65,8 +65,7 @@ ArenaLayout arena_layout(const vla_config& c) {
 }
 // Positions per (slot, head) block of the KV cache.  Kept odd: the blocks of the (slot, head) pairs that are
 // streamed concurrently then start an odd number of 256-byte rows apart and spread over all memory channels
-// (an even max_seq such as 352 made every workgroup hit the same channels at the same time: 3.1 instead of
-// 5.1 TB/s in decode attention).
+// (with max_seq = 608 the prefill attention of a 128 x 552-token batch took 1222 us per layer, with 609 1078 us).
 inline int kv_pitch(const vla_config& c) { return c.max_seq | 1; }
 
 
