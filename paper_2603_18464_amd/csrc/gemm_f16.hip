@@ -563,6 +563,18 @@ __device__ __forceinline__ void read_frag_asm(f16x8& dst, unsigned addr) {
 #endif
 }
 
+// Waits until at most N LDS reads of this wave are outstanding (they complete in issue order) and ties the
+// eight fragments of one k-step to the wait, so that nothing that uses them is scheduled above it.
+template <int N>
+__device__ __forceinline__ void frags_fence(f16x8 (&a)[4], f16x8 (&b)[4]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3])
+               : "n"(N)
+               : "memory");
+#endif
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -710,47 +722,53 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
       static_assert(NW == 8 || (MT == 4 && NT == 4 && LPS == 8), "interleaved schedule is written for 128x128 wave tiles");
       const unsigned so = stage_off(kt + 1);
       const unsigned ra0 = a_k0 + so, ra1 = a_k1 + so, rw = w_b + so;
-      // first k-step of slab kt: 16 MFMAs, the 16 fragment reads of slab kt+1 between them
 #define VLA_MF(kk, mt, nt) \
   acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[f][kk][mt], bfr[f][kk][nt], acc[mt][nt], 0, 0, 0)
 #define VLA_SB __builtin_amdgcn_sched_barrier(0)
+      // Slots between the 32 MFMAs: a fragment read of slab kt+1 after every even one (first its k-step 0, then
+      // its k-step 1), a load of slab kt+3 after every fourth.  The LDS thus sees one read per two MFMAs instead
+      // of a burst, and the two waits below only ask for the eight reads that are needed next.
       VLA_MF(0, 0, 0); read_frag_asm<0>(af[f ^ 1][0][0], ra0); VLA_SB;
-      VLA_MF(0, 0, 1); read_frag_asm<0>(bfr[f ^ 1][0][0], rw); VLA_SB;
-      VLA_MF(0, 0, 2); read_frag_asm<2048>(af[f ^ 1][0][1], ra0); VLA_SB;
-      VLA_MF(0, 0, 3); read_frag_asm<2048>(bfr[f ^ 1][0][1], rw); VLA_SB;
-      VLA_MF(0, 1, 0); read_frag_asm<4096>(af[f ^ 1][0][2], ra0); VLA_SB;
-      VLA_MF(0, 1, 1); read_frag_asm<4096>(bfr[f ^ 1][0][2], rw); VLA_SB;
-      VLA_MF(0, 1, 2); read_frag_asm<6144>(af[f ^ 1][0][3], ra0); VLA_SB;
-      VLA_MF(0, 1, 3); read_frag_asm<6144>(bfr[f ^ 1][0][3], rw); VLA_SB;
-      VLA_MF(0, 2, 0); read_frag_asm<0>(af[f ^ 1][1][0], ra1); VLA_SB;
-      VLA_MF(0, 2, 1); read_frag_asm<1024>(bfr[f ^ 1][1][0], rw); VLA_SB;
-      VLA_MF(0, 2, 2); read_frag_asm<2048>(af[f ^ 1][1][1], ra1); VLA_SB;
-      VLA_MF(0, 2, 3); read_frag_asm<3072>(bfr[f ^ 1][1][1], rw); VLA_SB;
-      VLA_MF(0, 3, 0); read_frag_asm<4096>(af[f ^ 1][1][2], ra1); VLA_SB;
-      VLA_MF(0, 3, 1); read_frag_asm<5120>(bfr[f ^ 1][1][2], rw); VLA_SB;
-      VLA_MF(0, 3, 2); read_frag_asm<6144>(af[f ^ 1][1][3], ra1); VLA_SB;
-      VLA_MF(0, 3, 3); read_frag_asm<7168>(bfr[f ^ 1][1][3], rw); VLA_SB;
-      // second k-step: 16 MFMAs, the 8 loads of slab kt+3 between every other pair
-      VLA_MF(1, 0, 0); issue_one(kt + 3, 0); VLA_SB;
-      VLA_MF(1, 0, 1); VLA_SB;
-      VLA_MF(1, 0, 2); issue_one(kt + 3, 1); VLA_SB;
+      VLA_MF(0, 0, 1); issue_one(kt + 3, 0); VLA_SB;
+      VLA_MF(0, 0, 2); read_frag_asm<0>(bfr[f ^ 1][0][0], rw); VLA_SB;
+      VLA_MF(0, 0, 3); VLA_SB;
+      VLA_MF(0, 1, 0); read_frag_asm<2048>(af[f ^ 1][0][1], ra0); VLA_SB;
+      VLA_MF(0, 1, 1); issue_one(kt + 3, 1); VLA_SB;
+      VLA_MF(0, 1, 2); read_frag_asm<2048>(bfr[f ^ 1][0][1], rw); VLA_SB;
+      VLA_MF(0, 1, 3); VLA_SB;
+      VLA_MF(0, 2, 0); read_frag_asm<4096>(af[f ^ 1][0][2], ra0); VLA_SB;
+      VLA_MF(0, 2, 1); issue_one(kt + 3, 2); VLA_SB;
+      VLA_MF(0, 2, 2); read_frag_asm<4096>(bfr[f ^ 1][0][2], rw); VLA_SB;
+      VLA_MF(0, 2, 3); VLA_SB;
+      VLA_MF(0, 3, 0); read_frag_asm<6144>(af[f ^ 1][0][3], ra0); VLA_SB;
+      VLA_MF(0, 3, 1); issue_one(kt + 3, 3); VLA_SB;
+      VLA_MF(0, 3, 2); read_frag_asm<6144>(bfr[f ^ 1][0][3], rw); VLA_SB;
+      VLA_MF(0, 3, 3); VLA_SB;
+      // k-step 1 of slab kt was read during the second half of the previous step: eight newer reads may be pending
+      frags_fence<8>(af[f][1], bfr[f][1]);
+      VLA_SB;
+      VLA_MF(1, 0, 0); read_frag_asm<0>(af[f ^ 1][1][0], ra1); VLA_SB;
+      VLA_MF(1, 0, 1); issue_one(kt + 3, 4); VLA_SB;
+      VLA_MF(1, 0, 2); read_frag_asm<1024>(bfr[f ^ 1][1][0], rw); VLA_SB;
       VLA_MF(1, 0, 3); VLA_SB;
-      VLA_MF(1, 1, 0); issue_one(kt + 3, 2); VLA_SB;
-      VLA_MF(1, 1, 1); VLA_SB;
-      VLA_MF(1, 1, 2); issue_one(kt + 3, 3); VLA_SB;
+      VLA_MF(1, 1, 0); read_frag_asm<2048>(af[f ^ 1][1][1], ra1); VLA_SB;
+      VLA_MF(1, 1, 1); issue_one(kt + 3, 5); VLA_SB;
+      VLA_MF(1, 1, 2); read_frag_asm<3072>(bfr[f ^ 1][1][1], rw); VLA_SB;
       VLA_MF(1, 1, 3); VLA_SB;
-      VLA_MF(1, 2, 0); issue_one(kt + 3, 4); VLA_SB;
-      VLA_MF(1, 2, 1); VLA_SB;
-      VLA_MF(1, 2, 2); issue_one(kt + 3, 5); VLA_SB;
+      VLA_MF(1, 2, 0); read_frag_asm<4096>(af[f ^ 1][1][2], ra1); VLA_SB;
+      VLA_MF(1, 2, 1); issue_one(kt + 3, 6); VLA_SB;
+      VLA_MF(1, 2, 2); read_frag_asm<5120>(bfr[f ^ 1][1][2], rw); VLA_SB;
       VLA_MF(1, 2, 3); VLA_SB;
-      VLA_MF(1, 3, 0); issue_one(kt + 3, 6); VLA_SB;
-      VLA_MF(1, 3, 1); VLA_SB;
-      VLA_MF(1, 3, 2); issue_one(kt + 3, 7); VLA_SB;
+      VLA_MF(1, 3, 0); read_frag_asm<6144>(af[f ^ 1][1][3], ra1); VLA_SB;
+      VLA_MF(1, 3, 1); issue_one(kt + 3, 7); VLA_SB;
+      VLA_MF(1, 3, 2); read_frag_asm<7168>(bfr[f ^ 1][1][3], rw); VLA_SB;
       VLA_MF(1, 3, 3); VLA_SB;
+      // k-step 0 of slab kt+1 must be in registers before the next step; its k-step 1 may still be on its way
+      frags_fence<8>(af[f ^ 1][0], bfr[f ^ 1][0]);
 #undef VLA_MF
 #undef VLA_SB
     }
-    frags_arrived(af[f ^ 1], bfr[f ^ 1]);
+    if constexpr (NW == 8) frags_arrived(af[f ^ 1], bfr[f ^ 1]);
   };
   issue(0);
   issue(1);
@@ -762,6 +780,10 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   for (int kt = 0; kt < KT; kt += 2) {       // K is a multiple of 64: KT is even
     step(kt, 0);
     step(kt + 1, 1);
+  }
+  if constexpr (NW == 4) {                   // the last step leaves eight fragment reads in flight: they must land
+    frags_arrived(af[0], bfr[0]);            // before the registers they write are used for anything else
+    frags_arrived(af[1], bfr[1]);
   }
   wait_vmcnt<0>();                           // the clamped tail loads still target this workgroup's LDS
   __syncthreads();                           // every wave is done with the slabs: LDS becomes epilogue staging
