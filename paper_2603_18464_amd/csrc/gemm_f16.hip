@@ -370,105 +370,6 @@ __device__ __forceinline__ void load_to_lds_16(const f16* src, f16* lds_wave_bas
 #endif
 }
 
-template <int WGM, int WGN, class Epi>
-__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_dma_kernel(
-    const f16* __restrict__ A, int lda, const f16* __restrict__ Wp, int M, int N, int K,
-    int tiles_m, int tiles_n, Epi epi) {
-  constexpr int BM = 256, BN = 256;
-  constexpr int NW = WGM * WGN;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
-  constexpr int A_INSTR = (BM / 8) / NW;       // wave instructions (8 rows each) per wave for the A slab
-  constexpr int W_INSTR = (BN * BK * 2 / 1024) / NW;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  f16* As = (f16*)smem;                       // [2][BM*64]
-  f16* Ws = As + 2 * BM * BK;                  // [2][BN*64]
-
-  const int nblk = tiles_m * tiles_n;
-  const int per_xcd = gridDim.x >> 3;
-  const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (pid >= nblk) return;
-  constexpr int GM = 4;
-  const int per_group = GM * tiles_n;
-  const int grp = pid / per_group;
-  const int first_m = grp * GM;
-  const int gm = min(tiles_m - first_m, GM);
-  const int in_grp = pid - grp * per_group;
-  const int tm = first_m + in_grp % gm;
-  const int tn = in_grp / gm;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  const int t = threadIdx.x, lane = t & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wave / WGN, wn = wave % WGN;
-  const int KB16 = K >> 4, KT = K / BK;
-
-  // source pointers of this lane for its wave's load instructions (advance by one k-tile per iteration)
-  const f16* a_src[A_INSTR];
-#pragma unroll
-  for (int i = 0; i < A_INSTR; ++i) {
-    const int g = wave * A_INSTR + i;                    // group of 8 rows
-    const int r = g * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    a_src[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
-  }
-  const f16* w_src[W_INSTR];
-#pragma unroll
-  for (int i = 0; i < W_INSTR; ++i) {
-    const int j = wave * W_INSTR + i;                    // KiB of the slab: block row j/4, k-step j%4
-    w_src[i] = Wp + ((size_t)(n0 / 32 + (j >> 2)) * KB16 + (j & 3)) * 512 + lane * 8;
-  }
-  auto issue = [&](int kt, int buf) {
-    f16* as = As + buf * BM * BK + wave * A_INSTR * 512;
-    f16* ws = Ws + buf * BN * BK + wave * W_INSTR * 512;
-#pragma unroll
-    for (int i = 0; i < A_INSTR; ++i)
-      load_to_lds_16(a_src[i] + (size_t)kt * BK, as + i * 512);
-#pragma unroll
-    for (int i = 0; i < W_INSTR; ++i)
-      load_to_lds_16(w_src[i] + (size_t)kt * 4 * 512, ws + i * 512);
-  };
-
-  f32x16 acc[MT][NT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-  const int frow = wm * WTM + (lane & 31);
-  const int fhalf = lane >> 5;
-  int a_off[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) a_off[kk] = frow * BK + (((kk * 2 + fhalf) ^ ((frow >> 1) & 7)) << 3);
-  const int w_off = wn * NT * 4 * 512 + lane * 8;
-
-  issue(0, 0);
-  for (int kt = 0; kt < KT; ++kt) {
-    __syncthreads();            // own loads of slab kt have landed (the compiler waits vmcnt before it), and
-                                // every wave has finished reading the other buffer
-    const f16* as = As + (kt & 1) * BM * BK;
-    const f16* ws = Ws + (kt & 1) * BN * BK + w_off;
-    f16x8 af[4][MT], bfr[4][NT];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) af[kk][mt] = *(const f16x8*)(as + a_off[kk] + mt * 32 * BK);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) bfr[kk][nt] = *(const f16x8*)(ws + (nt * 4 + kk) * 512);
-    }
-    if (kt + 1 < KT) issue(kt + 1, (kt + 1) & 1);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[kk][mt], bfr[kk][nt], acc[mt][nt], 0, 0, 0);
-  }
-  epi.template apply<MT, NT>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, M);
-}
-
 // ---- 4-stage pipelined variant ------------------------------------------------------------------------
 // 256x256 tiles, k-slabs of 32 (16 KiB of A + 16 KiB of W per stage, four stages = 128 KiB of LDS), loaded
 // straight into LDS three slabs ahead of the MFMAs.  The compiler cannot tell the stages apart and would
@@ -658,13 +559,6 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   // are already in flight, so the LDS latency and the read burst after each barrier hide under MFMA work.
   f16x8 af[2][2][MT], bfr[2][2][NT];
   auto stage_off = [&](int kt) { return (unsigned)(kt & (P_STAGES - 1)) * (2u * P_STAGE_HALVES); };
-  auto mfma_half = [&](int f, int kk) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[f][kk][mt], bfr[f][kk][nt], acc[mt][nt], 0, 0, 0);
-  };
   // One workgroup-wide slab step.  With two waves per SIMD (8 waves) the other wave's MFMAs cover this wave's
   // bursts of fragment reads and load issues; with one wave per SIMD (4 waves, 128x128 wave tile) every read and
   // every load is slotted between two MFMAs instead, so the matrix pipe never waits for the issue of a burst.
@@ -681,18 +575,6 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
     wait_vmcnt<LPS>();                       // this wave's loads of slab kt+1 have landed (kt+2 may be in flight)
     __builtin_amdgcn_s_barrier();            // ... everyone's have; everyone holds slab kt in registers
     if constexpr (NW == 8) {
-#if defined(VLA_GEMM_BURST)
-      {
-        const unsigned so = stage_off(kt + 1);
-        read_frags_asm(af[f ^ 1], bfr[f ^ 1], a_k0 + so, a_k1 + so, w_b + so);
-      }
-      mfma_half(f, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      issue(kt + 3);                         // refill the buffer slab kt-1 lived in
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_half(f, 1);
-      __builtin_amdgcn_sched_barrier(0);
-#else
       // 16 MFMAs, and between them the 12 fragment reads of slab kt+1 and the 4 loads of slab kt+3, one each
       const unsigned so = stage_off(kt + 1);
       const unsigned ra0 = a_k0 + so, ra1 = a_k1 + so, rw = w_b + so;
@@ -717,7 +599,6 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
       VLA_MF(1, 1, 3); issue_one(kt + 3, 3); VLA_SB;
 #undef VLA_MF
 #undef VLA_SB
-#endif
     } else {
       static_assert(NW == 8 || (MT == 4 && NT == 4 && LPS == 8), "interleaved schedule is written for 128x128 wave tiles");
       const unsigned so = stage_off(kt + 1);
@@ -812,22 +693,6 @@ static void launch_pipe(const GemmF16& g, const Epi& epi, hipStream_t st) {
   hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, tiles_m, tiles_n, epi);
 }
 
-template <int WGM, int WGN, class Epi>
-static void launch_dma(const GemmF16& g, const Epi& epi, hipStream_t st) {
-  const int tiles_m = (g.M + 255) / 256, tiles_n = g.N / 256;
-  const int nblk = tiles_m * tiles_n;
-  const int grid = (nblk + 7) / 8 * 8;
-  constexpr size_t smem = 2 * (size_t)(256 + 256) * BK * sizeof(f16);
-  auto kern = gemm_f16_dma_kernel<WGM, WGN, Epi>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K,
-                     tiles_m, tiles_n, epi);
-}
-
 template <int BM, int BN, int WGM, int WGN, class Epi>
 static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
@@ -851,14 +716,8 @@ static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
 template <bool kWaves4, class Epi>
 static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
   if (g.M > 128 && g.N % 256 == 0) {
-#if defined(VLA_GEMM_NO_DMA)
-    launch<256, 256, 4, 2, Epi>(g, epi, st);
-#elif defined(VLA_GEMM_DMA2)
-    launch_dma<4, 2, Epi>(g, epi, st);
-#else
     if (kWaves4) launch_pipe<2, 2, Epi>(g, epi, st);
     else launch_pipe<4, 2, Epi>(g, epi, st);
-#endif
   } else if (g.N % 256 == 0) {
     launch<64, 256, 2, 2, Epi>(g, epi, st);
   } else {
