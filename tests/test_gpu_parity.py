@@ -107,6 +107,19 @@ def test_bf16_tiny_prefixes_keep_every_row_in_the_last_layer():
     run_both(wl, obs=obs, gumbel=W.make_gumbel(wl))
 
 
+@pytest.mark.parametrize("hd,heads", [(128, 2), (64, 4)])
+def test_bf16_long_context_uses_the_general_decode_attention(hd, heads):
+    """Contexts beyond what the streaming decode-attention kernel holds in registers (640 positions at head
+    size 128, 320 at 64): decode falls back to the row-wise attention kernel, prefill walks 11 key tiles."""
+    shape = W.PolicyShape(2, 256, heads, hd, 704, 1024, dtype="bf16")
+    nps, lens = [640, 600, 333], [41, 0, 17]
+    wl = W.Workload("Tl", 23, shape, batch=3, n_patches=640, instr_len=(0, 41), n_tokens=4,
+                    sampling="gumbel", temperature=0.9)
+    assert wl.max_seq > 640
+    obs = ragged_obs(wl, nps, lens, seed=85)
+    run_both(wl, obs=obs, gumbel=W.make_gumbel(wl))
+
+
 @pytest.mark.timeout(600)
 def test_c2_bf16_whole_batch():
     wl = W.get_workload("C2")
