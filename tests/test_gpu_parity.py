@@ -558,6 +558,28 @@ def test_parallel_decoding_and_token_scoring(case):
     pol.close()
 
 
+@pytest.mark.parametrize("name", ["C1", "bf16"])
+def test_head_already_cut_to_the_action_rows(name):
+    """Appendix "Vocabulary Slimming": a head that arrives as its last A rows gives bit-identical outputs to the
+    full head (the library keeps only those rows either way)."""
+    if name == "C1":
+        wl = W.get_workload("C1")
+    else:
+        wl = W.Workload("Ts", 29, W.PolicyShape(2, 256, 2, 128, 704, 1024, dtype="bf16"), batch=5, n_patches=40,
+                        instr_len=(3, 20), n_tokens=4)
+    obs = W.make_observations(wl)
+    full = W.make_weights(wl.shape, wl.seed)
+    A = wl.shape.n_action_bins
+    slim = dict(full, lm_head=np.ascontiguousarray(full["lm_head"][wl.shape.vocab - A:]))
+    outs = []
+    for weights in (full, slim):
+        pol = make_policy(wl, weights)
+        outs.append(P.to_numpy(_step(pol, wl, obs, P.device_inputs(pol, obs))))
+        pol.close()
+    for k in ("tokens", "logp", "actions", "logits"):
+        assert np.array_equal(outs[0][k], outs[1][k]), k
+
+
 def test_policy_step_is_deterministic_and_matches_stepwise_calls():
     """Two identical policy steps give bit-identical outputs; prefill + select + decode_step called
     one by one reproduce vla_policy_step."""
