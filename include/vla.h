@@ -226,6 +226,25 @@ int vla_score_tokens(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32
                      int32_t placeholder_id, float temperature, const float* mu_logp, float sigma,
                      float* logp_out, float* ratio_out, float* weight_out, float* logits_out, void* hip_stream);
 
+/* Continuous batching: the same two steps on an arbitrary set of cache slots, so that newly admitted requests are
+ * prefilled while the sequences already running keep decoding in shared steps.  Sequence i of a call lives in
+ * cache slot slot_ids[i] (host array, n distinct values in [0, max_batch)); rows of patch_emb / offsets /
+ * token_ids / logits_out are in call order, not slot order.  Sequences are independent, so a sequence's
+ * results do not depend on which slot it occupies or on what runs beside it.
+ *   vla_prefill_slots  arguments as vla_prefill; overwrites the given slots only (an occupied slot restarts).
+ *   vla_decode_slots   arguments as vla_decode_step; VLA_E_STATE if a slot holds no sequence,
+ *                      VLA_E_CAPACITY if one is full.
+ *   vla_release_slots  marks slots free (host state only).
+ * Mixing with the whole-batch calls: vla_prefill and the policy-step calls reset every slot and use slots
+ * 0..B-1; after vla_prefill_slots / vla_release_slots, vla_decode_step is refused until the next whole-batch
+ * prefill.  A weight update (vla_update_begin, vla_load_weights) frees every slot. */
+int vla_prefill_slots(vla_ctx* ctx, int32_t n, const int32_t* slot_ids, const void* patch_emb,
+                      const int32_t* cu_patch, const int32_t* instr_ids, const int32_t* cu_instr,
+                      float* logits_out, void* hip_stream);
+int vla_decode_slots(vla_ctx* ctx, int32_t n, const int32_t* slot_ids, const int32_t* token_ids,
+                     float* logits_out, void* hip_stream);
+int vla_release_slots(vla_ctx* ctx, int32_t n, const int32_t* slot_ids);
+
 /* Request queue with the dynamic-window trigger of Section 3.2, Eq. 1 (host code; no GPU work):
  *     Trigger = (|Q| >= target_batch) or (t_now - t_first >= t_max),   t_first = arrival of the oldest request.
  * Times are seconds on any monotonic clock of the caller's choice, passed in explicitly.  A poll that
@@ -237,8 +256,9 @@ int vla_score_tokens(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32
  *   vla_batcher_create   VLA_E_CONFIG unless target_batch > 0, t_max >= 0 and finite, max_tokens >= 0.
  *   vla_batcher_push     VLA_E_SHAPE for an empty or negative prefix or a NaN stamp, VLA_E_CAPACITY if the
  *                        request alone exceeds max_tokens.  The struct is copied; `id` is opaque.
- *   vla_batcher_poll     out: host array of cap >= target_batch entries (else VLA_E_CAPACITY);
- *                        *n_out = number handed out (0: not triggered).
+ *   vla_batcher_poll     out: host array of cap >= 1 entries (else VLA_E_CAPACITY); a triggered poll hands out at
+ *                        most min(target_batch, cap) requests (cap = what the caller can take now, e.g. its
+ *                        free cache slots); *n_out = number handed out (0: not triggered).
  *   vla_batcher_deadline *t = t_first + t_max, the time at which waiting alone will trigger (+inf if empty). */
 typedef struct vla_batcher vla_batcher;
 typedef struct {

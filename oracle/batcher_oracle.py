@@ -24,7 +24,8 @@ def trigger(q_len: int, B: int, t_now: float, t_first: float, T_max: float) -> b
 def simulate(events: Sequence[Tuple], B: int, T_max: float, max_tokens: int = 0) -> List[Tuple[float, List[int]]]:
     """events, in the order the worker sees them:
          ("push", t_arrival, request_id, n_tokens)   a request joins the back of Q
-         ("poll", t_now)                             the worker evaluates Eq. 1 once
+         ("poll", t_now[, cap])                      the worker evaluates Eq. 1 once; cap (default B) is the most
+                                                     requests it can take at this moment
     Returns one (t_now, [request ids]) per poll that triggered."""
     Q: List[Tuple[float, int, int]] = []
     out = []
@@ -37,7 +38,8 @@ def simulate(events: Sequence[Tuple], B: int, T_max: float, max_tokens: int = 0)
             if not trigger(len(Q), B, t_now, Q[0][0] if Q else 0.0, T_max):
                 continue
             batch, tokens = [], 0
-            while Q and len(batch) < B:
+            most = min(B, ev[2]) if len(ev) > 2 else B
+            while Q and len(batch) < most:
                 if max_tokens and batch and tokens + Q[0][2] > max_tokens:
                     break
                 t, rid, n_tok = Q.pop(0)

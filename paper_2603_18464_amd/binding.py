@@ -17,6 +17,7 @@ EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vl
            "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_policy_step", "vla_select",
            "vla_load_value_head", "vla_policy_step_value",
            "vla_policy_step_parallel", "vla_score_tokens",
+           "vla_prefill_slots", "vla_decode_slots", "vla_release_slots",
            "vla_batcher_create", "vla_batcher_destroy", "vla_batcher_push", "vla_batcher_size",
            "vla_batcher_deadline", "vla_batcher_poll",
            "vla_get_state", "vla_drain_begin", "vla_update_begin", "vla_update_tensors", "vla_update_commit",
@@ -82,6 +83,9 @@ def lib() -> C.CDLL:
         L.vla_update_commit.argtypes = [vp, vp, C.POINTER(C.c_int64)]
         L.vla_policy_step_parallel.argtypes = [vp, i32, vp, vp, vp, vp, i32, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         L.vla_score_tokens.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, f32, vp, f32, vp, vp, vp, vp, vp]
+        L.vla_prefill_slots.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.vla_decode_slots.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.vla_release_slots.argtypes = [vp, i32, vp]
         L.vla_batcher_create.argtypes = [i32, C.c_double, C.c_int64, C.POINTER(vp)]
         L.vla_batcher_destroy.argtypes = [vp]
         L.vla_batcher_push.argtypes = [vp, C.POINTER(vla_request)]
@@ -215,6 +219,22 @@ def vla_score_tokens(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens,
                                        _ptr(logp_out), _ptr(ratio_out), _ptr(weight_out), _ptr(logits_out), stream))
 
 
+def vla_prefill_slots(ctx, slot_ids, patch_emb, cu_patch, instr_ids, cu_instr, logits_out, stream: int = 0) -> None:
+    slot_ids = np.ascontiguousarray(slot_ids, dtype=np.int32)
+    _check(ctx, lib().vla_prefill_slots(ctx, len(slot_ids), _ptr(slot_ids), _ptr(patch_emb), _ptr(cu_patch),
+                                        _ptr(instr_ids), _ptr(cu_instr), _ptr(logits_out), stream))
+
+
+def vla_decode_slots(ctx, slot_ids, token_ids, logits_out, stream: int = 0) -> None:
+    slot_ids = np.ascontiguousarray(slot_ids, dtype=np.int32)
+    _check(ctx, lib().vla_decode_slots(ctx, len(slot_ids), _ptr(slot_ids), _ptr(token_ids), _ptr(logits_out), stream))
+
+
+def vla_release_slots(ctx, slot_ids) -> None:
+    slot_ids = np.ascontiguousarray(slot_ids, dtype=np.int32)
+    _check(ctx, lib().vla_release_slots(ctx, len(slot_ids), _ptr(slot_ids)))
+
+
 def vla_prefill(ctx, B, patch_emb, cu_patch: np.ndarray, instr_ids, cu_instr: np.ndarray, logits_out,
                 stream: int = 0) -> None:
     _check(ctx, lib().vla_prefill(ctx, B, _ptr(patch_emb), _ptr(cu_patch), _ptr(instr_ids), _ptr(cu_instr),
@@ -291,10 +311,12 @@ class Batcher:
         lib().vla_batcher_deadline(self.h, C.byref(t))
         return t.value
 
-    def poll(self, t_now: float):
-        """[(id, n_patches, n_instr, t_arrival)] of the released batch, [] if the rule did not fire."""
+    def poll(self, t_now: float, cap: Optional[int] = None):
+        """[(id, n_patches, n_instr, t_arrival)] of the released batch (at most min(target, cap) requests), [] if
+        the rule did not fire."""
         n = C.c_int32()
-        rc = lib().vla_batcher_poll(self.h, t_now, self._buf, self.target, C.byref(n))
+        rc = lib().vla_batcher_poll(self.h, t_now, self._buf, self.target if cap is None else min(cap, self.target),
+                                    C.byref(n))
         if rc:
             raise VlaError(rc, "vla_batcher_poll")
         return [(r.id, r.n_patches, r.n_instr, r.t_arrival) for r in self._buf[:n.value]]
@@ -385,6 +407,22 @@ class VlaPolicy:
         vla_prefill(self.ctx, B, patch_emb, np.ascontiguousarray(cu_patch, dtype=np.int32), instr_ids,
                     np.ascontiguousarray(cu_instr, dtype=np.int32), out, self._stream())
         return out
+
+    def prefill_slots(self, slot_ids, patch_emb, cu_patch, instr_ids, cu_instr):
+        torch = self.torch
+        out = torch.empty((len(slot_ids), self.shape.n_action_bins), dtype=torch.float32, device=self.device)
+        vla_prefill_slots(self.ctx, slot_ids, patch_emb, np.ascontiguousarray(cu_patch, dtype=np.int32), instr_ids,
+                          np.ascontiguousarray(cu_instr, dtype=np.int32), out, self._stream())
+        return out
+
+    def decode_slots(self, slot_ids, token_ids):
+        torch = self.torch
+        out = torch.empty((len(slot_ids), self.shape.n_action_bins), dtype=torch.float32, device=self.device)
+        vla_decode_slots(self.ctx, slot_ids, token_ids, out, self._stream())
+        return out
+
+    def release_slots(self, slot_ids):
+        vla_release_slots(self.ctx, slot_ids)
 
     def decode_step(self, token_ids, want_logits=True):
         torch = self.torch

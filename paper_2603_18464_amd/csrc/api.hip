@@ -29,7 +29,7 @@ struct ArenaLayout {
 };
 struct WorkLayout {
   size_t x, hn, q, att, act, scratch, part, rope_cos, rope_sin, tok_seq, tok_pos, tok_src, last_row, seq_len,
-      cu_patch, cu_instr, cur_ids, logits, vz, vml, vu, vh, ids2, tail, chunk_rows, chunk_logits, total;
+      cu_patch, cu_instr, cur_ids, logits, vz, vml, vu, vh, ids2, tail, chunk_rows, chunk_logits, slot_map, total;
 };
 
 size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
@@ -114,6 +114,7 @@ WorkLayout work_layout(const vla_config& c) {
   w.tail = take(B * (size_t)kMaxChunk * 4);
   w.chunk_rows = take(B * (size_t)kMaxChunk * 4);
   w.chunk_logits = take(B * (size_t)kMaxChunk * c.n_action_bins * 4);
+  w.slot_map = take(B * 4);
   w.total = off;
   return w;
 }
@@ -158,6 +159,7 @@ struct vla_ctx {
   bool have_work = false, have_update = false;
   int active_B = 0;                  // batch of the last prefill (0: none)
   int run_B = 0, run_max_len = 0;    // batch and longest prefix of the prefill being enqueued
+  const int32_t* run_slots = nullptr; // device slot map of the call being enqueued (nullptr: sequence b is slot b)
   std::vector<int32_t> len;          // host copy of the sequence lengths
   std::string err;
   // pinned staging ring for the host offset arrays
@@ -269,7 +271,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       if constexpr (sizeof(T) == 2) {
         if (!decode)
           flash_prefill((const f16*)q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache,
-                        at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), (f16*)att, d,
+                        at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), ctx->run_slots, (f16*)att, d,
                         ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim, kv_pitch(c), st);
         else
           attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
@@ -372,7 +374,7 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
     {
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
       if (c.max_seq <= decode_attention_max_ctx(c.head_dim))
-        decode_attention(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_pos, att, B, d, c.n_heads,
+        decode_attention(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, B, d, c.n_heads,
                          c.head_dim, kv_pitch(c), st);
       else
         attention_rows<f16>(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, d, B,
@@ -522,8 +524,9 @@ template <> struct ActOf<bf16> { typedef f16 type; };
 template <class T>
 int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu_patch, const int32_t* instr_ids,
                const int32_t* cu_instr, int64_t T_tokens, float* logits, int ld_logits, hipStream_t st,
-               const int32_t* tail = nullptr, int n_tail = 0) {
+               const int32_t* tail = nullptr, int n_tail = 0, const int32_t* slots = nullptr) {
   const int n_last = n_tail + 1;   // rows per sequence whose final hidden state is read: the last n_tail + 1
+  // slots (host, [B], or nullptr): cache slot of each sequence; nullptr means sequence b goes to slot b.
   // With a tail, cu_instr already counts n_tail extra ids per sequence (device array tail[B, n_tail]) and the
   // id stream the layers see is the merge of instr_ids and tail.
   const vla_config& c = ctx->cfg;
@@ -532,17 +535,23 @@ int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu
   const int slot = ctx->stage_next;
   ctx->stage_next = (slot + 1) % vla_ctx::kRing;
   if (ctx->stage_used[slot]) HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev[slot]));
-  int32_t* host = ctx->stage + (size_t)slot * 2 * (c.max_batch + 1);
+  int32_t* host = ctx->stage + (size_t)slot * 3 * (c.max_batch + 1);
   memcpy(host, cu_patch, (B + 1) * sizeof(int32_t));
   memcpy(host + c.max_batch + 1, cu_instr, (B + 1) * sizeof(int32_t));
   HIP_TRY(ctx, hipMemcpyAsync(at<int32_t>(ctx->work, w.cu_patch), host, (B + 1) * 4, hipMemcpyHostToDevice, st));
   HIP_TRY(ctx, hipMemcpyAsync(at<int32_t>(ctx->work, w.cu_instr), host + c.max_batch + 1, (B + 1) * 4, hipMemcpyHostToDevice, st));
+  ctx->run_slots = nullptr;
+  if (slots) {
+    memcpy(host + 2 * (c.max_batch + 1), slots, B * sizeof(int32_t));
+    HIP_TRY(ctx, hipMemcpyAsync(at<int32_t>(ctx->work, w.slot_map), host + 2 * (c.max_batch + 1), B * 4, hipMemcpyHostToDevice, st));
+    ctx->run_slots = at<int32_t>(ctx->work, w.slot_map);
+  }
   HIP_TRY(ctx, hipEventRecord(ctx->stage_ev[slot], st));
   ctx->stage_used[slot] = true;
   ensure_tables(ctx, st);
   {
     ProfScope ps(ctx, FAM_MISC, st);
-    build_token_maps(at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), B, (int)T_tokens,
+    build_token_maps(at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), ctx->run_slots, B, (int)T_tokens,
                      at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos),
                      at<int32_t>(ctx->work, w.tok_src), at<int32_t>(ctx->work, w.last_row),
                      at<int32_t>(ctx->work, w.seq_len), st);
@@ -570,30 +579,50 @@ int do_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* cu
   run_layers<typename ActOf<T>::type>(ctx, (int)T_tokens, false, st, need, B * n_last);
   if (logits) run_head<T>(ctx, B, at<int32_t>(ctx->work, w.last_row), logits, ld_logits, st);
   HIP_TRY(ctx, hipGetLastError());
-  ctx->active_B = B;
-  ctx->len.assign(B, 0);
-  for (int b = 0; b < B; ++b) ctx->len[b] = (cu_patch[b + 1] - cu_patch[b]) + (cu_instr[b + 1] - cu_instr[b]);
+  // host mirror of the sequence lengths, by slot (0: free)
+  if (!slots) {
+    ctx->active_B = B;
+    ctx->len.assign(c.max_batch, 0);
+  } else {
+    ctx->active_B = 0;             // slots are now managed one by one: vla_decode_slots, not vla_decode_step
+    ctx->len.resize(c.max_batch, 0);
+  }
+  for (int b = 0; b < B; ++b)
+    ctx->len[slots ? slots[b] : b] = (cu_patch[b + 1] - cu_patch[b]) + (cu_instr[b + 1] - cu_instr[b]);
   return VLA_OK;
 }
 
 template <class T>
-int do_decode(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits, int ld_logits, hipStream_t st) {
+int do_decode(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits, int ld_logits, hipStream_t st,
+              const int32_t* slots = nullptr) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
+  const int32_t* slot_map = nullptr;
+  if (slots) {      // host list of cache slots, one per row of this step
+    const int slot = ctx->stage_next;
+    ctx->stage_next = (slot + 1) % vla_ctx::kRing;
+    if (ctx->stage_used[slot]) HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev[slot]));
+    int32_t* host = ctx->stage + (size_t)slot * 3 * (c.max_batch + 1);
+    memcpy(host, slots, B * sizeof(int32_t));
+    HIP_TRY(ctx, hipMemcpyAsync(at<int32_t>(ctx->work, w.slot_map), host, B * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipEventRecord(ctx->stage_ev[slot], st));
+    ctx->stage_used[slot] = true;
+    slot_map = at<int32_t>(ctx->work, w.slot_map);
+  }
   {
     ProfScope ps(ctx, FAM_MISC, st);
     embed_tokens<T>(token_ids, at<T>(ctx->arena, ctx->al.embed), at<float>(ctx->work, w.x), B, c.d_model, c.vocab, st);
-    decode_maps(at<int32_t>(ctx->work, w.seq_len), B, at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos), st);
+    decode_maps(at<int32_t>(ctx->work, w.seq_len), slot_map, B, at<int32_t>(ctx->work, w.tok_seq), at<int32_t>(ctx->work, w.tok_pos), st);
   }
   if (sizeof(T) == 2) run_layers_decode_f16(ctx, B, st);
   else run_layers<typename ActOf<T>::type>(ctx, B, true, st);
   if (logits) run_head<T>(ctx, B, nullptr, logits, ld_logits, st);
   {
     ProfScope ps(ctx, FAM_MISC, st);
-    advance_lengths(at<int32_t>(ctx->work, w.seq_len), B, st);
+    advance_lengths(at<int32_t>(ctx->work, w.seq_len), slot_map, B, st);
   }
   HIP_TRY(ctx, hipGetLastError());
-  for (int b = 0; b < B; ++b) ctx->len[b] += 1;
+  for (int b = 0; b < B; ++b) ctx->len[slots ? slots[b] : b] += 1;
   return VLA_OK;
 }
 
@@ -632,6 +661,20 @@ int check_chunk(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* c
   if (*T_out + (int64_t)B * (K - 1) > ctx->cfg.max_prefill_tokens)
     return fail(ctx, VLA_E_CAPACITY, "%lld prefix + %lld fed tokens exceed max_prefill_tokens %lld", (long long)*T_out,
                 (long long)B * (K - 1), (long long)ctx->cfg.max_prefill_tokens);
+  return VLA_OK;
+}
+
+// Validates a host slot list: n entries, each in [0, max_batch), no duplicates.
+int check_slots(vla_ctx* ctx, int32_t n, const int32_t* slots) {
+  if (!slots) return fail(ctx, VLA_E_NULL, "slot_ids is NULL");
+  if (n <= 0) return fail(ctx, VLA_E_SHAPE, "the number of slots must be positive");
+  if (n > ctx->cfg.max_batch) return fail(ctx, VLA_E_CAPACITY, "%d slots exceed max_batch %d", n, ctx->cfg.max_batch);
+  std::vector<char> seen(ctx->cfg.max_batch, 0);
+  for (int i = 0; i < n; ++i) {
+    if (slots[i] < 0 || slots[i] >= ctx->cfg.max_batch) return fail(ctx, VLA_E_SHAPE, "slot id %d outside [0, max_batch)", slots[i]);
+    if (seen[slots[i]]) return fail(ctx, VLA_E_SHAPE, "slot id %d given twice", slots[i]);
+    seen[slots[i]] = 1;
+  }
   return VLA_OK;
 }
 
@@ -692,7 +735,7 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
   if (((uintptr_t)weight_arena | (uintptr_t)kv | (uintptr_t)workspace) % kAlign)
     return fail(ctx, VLA_E_SHAPE, "buffers must be %zu-byte aligned", kAlign);
   if (!ctx->stage) {
-    HIP_TRY(ctx, hipHostMalloc((void**)&ctx->stage, (size_t)vla_ctx::kRing * 2 * (ctx->cfg.max_batch + 1) * sizeof(int32_t), hipHostMallocDefault));
+    HIP_TRY(ctx, hipHostMalloc((void**)&ctx->stage, (size_t)vla_ctx::kRing * 3 * (ctx->cfg.max_batch + 1) * sizeof(int32_t), hipHostMallocDefault));
     for (int i = 0; i < vla_ctx::kRing; ++i) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming));
     HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_work, hipEventDisableTiming));
     HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_update, hipEventDisableTiming));
@@ -705,6 +748,7 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
   ctx->value_weights = false;
   ctx->tables = false;
   ctx->active_B = 0;
+  ctx->len.assign(ctx->cfg.max_batch, 0);
   ctx->serving = VLA_ACCEPTING;
   ctx->have_work = ctx->have_update = false;
   return VLA_OK;
@@ -853,6 +897,7 @@ int load_slots(vla_ctx* ctx, const std::vector<const vla_tensor*>& slot, hipStre
   ctx->have_update = true;
   ctx->version += 1;
   ctx->active_B = 0;     // cached keys / values belong to the old weights
+  ctx->len.assign(ctx->cfg.max_batch, 0);
   return VLA_OK;
 }
 
@@ -916,6 +961,7 @@ int vla_update_begin(vla_ctx* ctx, void* hip_stream) {
   if (ctx->have_work) HIP_TRY(ctx, hipStreamWaitEvent((hipStream_t)hip_stream, ctx->ev_work, 0));
   ctx->serving = VLA_UPDATING;
   ctx->active_B = 0;     // the batch in flight has been enqueued to its end; its cache dies with the old weights
+  ctx->len.assign(ctx->cfg.max_batch, 0);
   return VLA_OK;
 }
 
@@ -979,6 +1025,59 @@ int vla_decode_step(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* lo
                                   : do_decode<float>(ctx, B, token_ids, logits_out, A, st);
   if (rc) return rc;
   return leave_compute(ctx, st);
+}
+
+int vla_prefill_slots(vla_ctx* ctx, int32_t n, const int32_t* slot_ids, const void* patch_emb, const int32_t* cu_patch,
+                      const int32_t* instr_ids, const int32_t* cu_instr, float* logits_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if ((rc = check_serving(ctx, true))) return rc;
+  if ((rc = check_slots(ctx, n, slot_ids))) return rc;
+  int64_t T = 0;
+  if ((rc = check_prefill(ctx, n, patch_emb, cu_patch, instr_ids, cu_instr, 0, &T))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
+  const int A = ctx->cfg.n_action_bins;
+  rc = ctx->cfg.dtype == VLA_BF16
+           ? do_prefill<bf16>(ctx, n, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st, nullptr, 0, slot_ids)
+           : do_prefill<float>(ctx, n, patch_emb, cu_patch, instr_ids, cu_instr, T, logits_out, A, st, nullptr, 0, slot_ids);
+  if (rc) return rc;
+  return leave_compute(ctx, st);
+}
+
+int vla_decode_slots(vla_ctx* ctx, int32_t n, const int32_t* slot_ids, const int32_t* token_ids, float* logits_out,
+                     void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if ((rc = check_serving(ctx, false))) return rc;
+  if (!token_ids) return fail(ctx, VLA_E_NULL, "token_ids is NULL");
+  if ((rc = check_slots(ctx, n, slot_ids))) return rc;
+  if ((int)ctx->len.size() < ctx->cfg.max_batch) ctx->len.resize(ctx->cfg.max_batch, 0);
+  for (int i = 0; i < n; ++i) {
+    const int len = ctx->len[slot_ids[i]];
+    if (len == 0) return fail(ctx, VLA_E_STATE, "slot %d holds no sequence (prefill it first)", slot_ids[i]);
+    if (len + 1 > ctx->cfg.max_seq)
+      return fail(ctx, VLA_E_CAPACITY, "slot %d is full (%d of %d positions)", slot_ids[i], len, ctx->cfg.max_seq);
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
+  const int A = ctx->cfg.n_action_bins;
+  rc = ctx->cfg.dtype == VLA_BF16 ? do_decode<bf16>(ctx, n, token_ids, logits_out, A, st, slot_ids)
+                                  : do_decode<float>(ctx, n, token_ids, logits_out, A, st, slot_ids);
+  if (rc) return rc;
+  return leave_compute(ctx, st);
+}
+
+int vla_release_slots(vla_ctx* ctx, int32_t n, const int32_t* slot_ids) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_slots(ctx, n, slot_ids);
+  if (rc) return rc;
+  if ((int)ctx->len.size() < ctx->cfg.max_batch) ctx->len.resize(ctx->cfg.max_batch, 0);
+  for (int i = 0; i < n; ++i) ctx->len[slot_ids[i]] = 0;
+  ctx->active_B = 0;
+  return VLA_OK;
 }
 
 int vla_select(vla_ctx* ctx, int32_t B, const float* logits, float temperature, const float* gumbel, int32_t k,

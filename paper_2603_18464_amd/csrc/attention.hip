@@ -77,8 +77,8 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
 template <int HD>
 __global__ __launch_bounds__(256) void flash_prefill_kernel(
     const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
-    const int32_t* __restrict__ cu_patch, const int32_t* __restrict__ cu_instr, f16* __restrict__ out, int ldo,
-    int n_heads, int max_seq) {
+    const int32_t* __restrict__ cu_patch, const int32_t* __restrict__ cu_instr,
+    const int32_t* __restrict__ slot_map, f16* __restrict__ out, int ldo, int n_heads, int max_seq) {
   constexpr int KS = HD / 16;          // k-steps of the QK^T contraction
   constexpr int DT = HD / 32;          // 32-row tiles of O^T
   constexpr int KCH = HD / 8;          // 16-byte chunks per key row
@@ -95,8 +95,9 @@ __global__ __launch_bounds__(256) void flash_prefill_kernel(
   const int half = lane >> 5, col = lane & 31;
   const int qpos = q0 + wave * 32 + col;                 // this lane's query position
   const int qrow = row0 + min(qpos, S - 1);               // clamped: rows past the end are never stored
-  const f16* kbase = k_cache + ((size_t)b * n_heads + head) * max_seq * HD;
-  const f16* vbase = v_cache + ((size_t)b * n_heads + head) * max_seq * HD;
+  const int slot = slot_map ? slot_map[b] : b;
+  const f16* kbase = k_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
+  const f16* vbase = v_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
 
   f16x8 qf[KS];
 #pragma unroll
@@ -222,15 +223,15 @@ __global__ __launch_bounds__(256) void flash_prefill_kernel(
 }
 
 void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* cu_patch,
-                   const int32_t* cu_instr, f16* out, int ldo, int B, int max_len, int n_heads, int head_dim,
-                   int max_seq, hipStream_t st) {
+                   const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B, int max_len,
+                   int n_heads, int head_dim, int max_seq, hipStream_t st) {
   const dim3 grid((max_len + 127) / 128, B, n_heads);
   if (head_dim == 128)
     hipLaunchKernelGGL(flash_prefill_kernel<128>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, cu_patch,
-                       cu_instr, out, ldo, n_heads, max_seq);
+                       cu_instr, slot_map, out, ldo, n_heads, max_seq);
   else
     hipLaunchKernelGGL(flash_prefill_kernel<64>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, cu_patch,
-                       cu_instr, out, ldo, n_heads, max_seq);
+                       cu_instr, slot_map, out, ldo, n_heads, max_seq);
 }
 
 // ---- decode: one new query per (sequence, head) against the whole cache -------------------------------
@@ -243,7 +244,8 @@ void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache
 template <int HD>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
     const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
-    const int32_t* __restrict__ tok_pos, f16* __restrict__ out_frag, int d_model, int n_heads, int max_seq) {
+    const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos, f16* __restrict__ out_frag,
+    int d_model, int n_heads, int max_seq) {
   constexpr int LPR = HD / 8;            // lanes per row
   constexpr int RPI = 64 / LPR;          // rows per wave instruction
   constexpr int MAXR = 40;               // score slots per lane: covers (ctx / (4*RPI)) rows per wave
@@ -253,8 +255,9 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPR, c = lane % LPR;          // row inside the instruction, 8-dim chunk
   const int ctx = tok_pos[b] + 1;
-  const f16* kb = k_cache + ((size_t)b * n_heads + head) * max_seq * HD;
-  const f16* vb = v_cache + ((size_t)b * n_heads + head) * max_seq * HD;
+  const int slot = tok_seq[b];
+  const f16* kb = k_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
+  const f16* vb = v_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
   const f16x8 qv = *(const f16x8*)(q + (size_t)b * ldq + head * HD + c * 8);
   float qf[8];
 #pragma unroll
@@ -327,15 +330,16 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
 }
 
 // Rows are the slots 0..B-1 themselves (decode keeps token b in slot b).  ctx <= 4 * RPI * 40 rows.
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_pos,
-                      f16* out_frag, int B, int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
+void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
+                      const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
+                      int max_seq, hipStream_t st) {
   const dim3 grid(B, n_heads);
   if (head_dim == 128)
-    hipLaunchKernelGGL(decode_attention_kernel<128>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_pos,
-                       out_frag, d_model, n_heads, max_seq);
+    hipLaunchKernelGGL(decode_attention_kernel<128>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_seq,
+                       tok_pos, out_frag, d_model, n_heads, max_seq);
   else
-    hipLaunchKernelGGL(decode_attention_kernel<64>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_pos,
-                       out_frag, d_model, n_heads, max_seq);
+    hipLaunchKernelGGL(decode_attention_kernel<64>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_seq,
+                       tok_pos, out_frag, d_model, n_heads, max_seq);
 }
 int decode_attention_max_ctx(int head_dim) { return 4 * (64 / (head_dim / 8)) * 40; }
 

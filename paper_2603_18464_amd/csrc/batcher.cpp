@@ -71,7 +71,7 @@ int vla_batcher_deadline(vla_batcher* b, double* t) {
 int vla_batcher_poll(vla_batcher* b, double t_now, vla_request* out, int32_t cap, int32_t* n_out) {
   if (!b || !out || !n_out) return VLA_E_NULL;
   *n_out = 0;
-  if (cap < b->target) return VLA_E_CAPACITY;
+  if (cap < 1) return VLA_E_CAPACITY;
   std::lock_guard<std::mutex> lock(b->mu);
   if (b->q.empty()) return VLA_OK;
   const bool full = (int64_t)b->q.size() >= b->target;
@@ -79,7 +79,8 @@ int vla_batcher_poll(vla_batcher* b, double t_now, vla_request* out, int32_t cap
   if (!full && !waited) return VLA_OK;
   int64_t tokens = 0;
   int32_t n = 0;
-  while (!b->q.empty() && n < b->target) {
+  const int32_t most = cap < b->target ? cap : b->target;   // e.g. the free cache slots of a continuous batcher
+  while (!b->q.empty() && n < most) {
     const vla_request& r = b->q.front();
     const int64_t need = r.n_patches + (int64_t)r.n_instr;
     if (b->max_tokens && n > 0 && tokens + need > b->max_tokens) break;

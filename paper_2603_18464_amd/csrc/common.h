@@ -114,10 +114,11 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
                     int max_seq, bool out_frag, hipStream_t st);
 
 // Prefill attention for the 16-bit path: causal flash attention over whole prefixes (MFMA).
-// cu_patch / cu_instr are the device copies of the cumulative offsets; max_len = longest prefix.
+// cu_patch / cu_instr are the device copies of the cumulative offsets; max_len = longest prefix; slot_map
+// (device, [B], or nullptr for the identity) gives the cache slot of each sequence of the call.
 void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* cu_patch,
-                   const int32_t* cu_instr, f16* out, int ldo, int B, int max_len, int n_heads, int head_dim,
-                   int max_seq, hipStream_t st);
+                   const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B, int max_len,
+                   int n_heads, int head_dim, int max_seq, hipStream_t st);
 
 // Decode-step GEMMs (M <= 128): weight-streaming split-K kernel writing partial sums, and the kernels
 // that add the partials in a fixed order and apply the elementwise step that follows each GEMM.
@@ -133,8 +134,9 @@ void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, int 
 
 // Decode attention of the 16-bit path (one query per slot); output in fragment order.  Handles contexts
 // up to decode_attention_max_ctx(head_dim) positions.
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_pos,
-                      f16* out_frag, int B, int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
+void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
+                      const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
+                      int max_seq, hipStream_t st);
 int decode_attention_max_ctx(int head_dim);
 
 // Action head: final RMSNorm + action rows of the LM head -> logits [B, A] float32.
@@ -169,11 +171,12 @@ void score_rows(const float* logits, int rows, int A, float temperature, const i
 
 // Small utilities.
 void rope_table(float* cos_t, float* sin_t, int max_seq, int head_dim, float theta, hipStream_t st);
-void build_token_maps(const int32_t* cu_patch_dev, const int32_t* cu_instr_dev, int B, int T_tokens,
-                      int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src, int32_t* last_row,
+// slot_map: device [B] cache slot of each sequence of the call, nullptr = identity; seq_len is indexed by slot.
+void build_token_maps(const int32_t* cu_patch_dev, const int32_t* cu_instr_dev, const int32_t* slot_map, int B,
+                      int T_tokens, int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src, int32_t* last_row,
                       int32_t* seq_len, hipStream_t st);
-void decode_maps(int32_t* seq_len, int B, int32_t* tok_seq, int32_t* tok_pos, hipStream_t st);
-void advance_lengths(int32_t* seq_len, int B, hipStream_t st);
+void decode_maps(int32_t* seq_len, const int32_t* slot_map, int B, int32_t* tok_seq, int32_t* tok_pos, hipStream_t st);
+void advance_lengths(int32_t* seq_len, const int32_t* slot_map, int B, hipStream_t st);
 template <class T>
 void convert_copy(const T* src, float* dst, size_t n, hipStream_t st);   // gains -> float32
 template <class T>

@@ -6,17 +6,17 @@
 namespace vla {
 
 // ---- token maps ---------------------------------------------------------------------------------
-// Packed prefix token t belongs to sequence slot b with cu_seq[b] <= t < cu_seq[b+1], where
-// cu_seq[b] = cu_patch[b] + cu_instr[b].  tok_src >= 0 is a row of patch_emb, tok_src < 0 is
-// instruction id number -1 - tok_src.
+// Packed prefix token t belongs to sequence b of the call with cu_seq[b] <= t < cu_seq[b+1], where
+// cu_seq[b] = cu_patch[b] + cu_instr[b]; sequence b lives in cache slot slot_map[b] (b itself without a map).
+// tok_src >= 0 is a row of patch_emb, tok_src < 0 is instruction id number -1 - tok_src.
 __global__ void token_maps_kernel(const int32_t* __restrict__ cu_patch, const int32_t* __restrict__ cu_instr,
-                                  int B, int T, int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src,
-                                  int32_t* last_row, int32_t* seq_len) {
+                                  const int32_t* __restrict__ slot_map, int B, int T, int32_t* tok_seq,
+                                  int32_t* tok_pos, int32_t* tok_src, int32_t* last_row, int32_t* seq_len) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t < B) {
     const int end = cu_patch[t + 1] + cu_instr[t + 1];
     last_row[t] = end - 1;
-    seq_len[t] = end - (cu_patch[t] + cu_instr[t]);
+    seq_len[slot_map ? slot_map[t] : t] = end - (cu_patch[t] + cu_instr[t]);
   }
   if (t >= T) return;
   int lo = 0, hi = B;                       // find b with cu_seq[b] <= t < cu_seq[b+1]
@@ -27,36 +27,39 @@ __global__ void token_maps_kernel(const int32_t* __restrict__ cu_patch, const in
   const int b = lo;
   const int pos = t - (cu_patch[b] + cu_instr[b]);
   const int np = cu_patch[b + 1] - cu_patch[b];
-  tok_seq[t] = b;
+  tok_seq[t] = slot_map ? slot_map[b] : b;
   tok_pos[t] = pos;
   tok_src[t] = pos < np ? cu_patch[b] + pos : -1 - (cu_instr[b] + pos - np);
 }
 
-void build_token_maps(const int32_t* cu_patch_dev, const int32_t* cu_instr_dev, int B, int T_tokens,
-                      int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src, int32_t* last_row,
+void build_token_maps(const int32_t* cu_patch_dev, const int32_t* cu_instr_dev, const int32_t* slot_map, int B,
+                      int T_tokens, int32_t* tok_seq, int32_t* tok_pos, int32_t* tok_src, int32_t* last_row,
                       int32_t* seq_len, hipStream_t st) {
   const int n = T_tokens > B ? T_tokens : B;
   hipLaunchKernelGGL(token_maps_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cu_patch_dev, cu_instr_dev,
-                     B, T_tokens, tok_seq, tok_pos, tok_src, last_row, seq_len);
+                     slot_map, B, T_tokens, tok_seq, tok_pos, tok_src, last_row, seq_len);
 }
 
-__global__ void decode_maps_kernel(const int32_t* seq_len, int B, int32_t* tok_seq, int32_t* tok_pos) {
+__global__ void decode_maps_kernel(const int32_t* seq_len, const int32_t* __restrict__ slot_map, int B,
+                                   int32_t* tok_seq, int32_t* tok_pos) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b < B) {
-    tok_seq[b] = b;
-    tok_pos[b] = seq_len[b];
+    const int slot = slot_map ? slot_map[b] : b;
+    tok_seq[b] = slot;
+    tok_pos[b] = seq_len[slot];
   }
 }
-void decode_maps(int32_t* seq_len, int B, int32_t* tok_seq, int32_t* tok_pos, hipStream_t st) {
-  hipLaunchKernelGGL(decode_maps_kernel, dim3((B + 255) / 256), dim3(256), 0, st, seq_len, B, tok_seq, tok_pos);
+void decode_maps(int32_t* seq_len, const int32_t* slot_map, int B, int32_t* tok_seq, int32_t* tok_pos, hipStream_t st) {
+  hipLaunchKernelGGL(decode_maps_kernel, dim3((B + 255) / 256), dim3(256), 0, st, seq_len, slot_map, B, tok_seq,
+                     tok_pos);
 }
 
-__global__ void advance_kernel(int32_t* seq_len, int B) {
+__global__ void advance_kernel(int32_t* seq_len, const int32_t* __restrict__ slot_map, int B) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B) seq_len[b] += 1;
+  if (b < B) seq_len[slot_map ? slot_map[b] : b] += 1;
 }
-void advance_lengths(int32_t* seq_len, int B, hipStream_t st) {
-  hipLaunchKernelGGL(advance_kernel, dim3((B + 255) / 256), dim3(256), 0, st, seq_len, B);
+void advance_lengths(int32_t* seq_len, const int32_t* slot_map, int B, hipStream_t st) {
+  hipLaunchKernelGGL(advance_kernel, dim3((B + 255) / 256), dim3(256), 0, st, seq_len, slot_map, B);
 }
 
 // ---- rotary table ---------------------------------------------------------------------------------

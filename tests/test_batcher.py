@@ -87,7 +87,7 @@ def run_native(ev, Bt, T_max, max_tokens):
             n_patch = e[3] // 2
             q.push(e[2], n_patch, e[3] - n_patch, e[1])
         else:
-            got = q.poll(e[1])
+            got = q.poll(e[1], e[2] if len(e) > 2 else None)
             if got:
                 out.append((e[1], [r[0] for r in got]))
     left = len(q)
@@ -106,6 +106,23 @@ def test_native_queue_equals_oracle_on_random_traces(seed, Bt, T_max, max_tokens
     assert max(len(b) for _, b in got) <= Bt
 
 
+def test_poll_capacity_limits_the_batch_not_the_trigger():
+    """A caller with fewer free places than the target batch (continuous batching): the rule fires as before,
+    the batch is cut to what can be taken, the rest waits with its own arrival times."""
+    ev = [("push", 0.0, i, 10) for i in range(6)] + [("poll", 0.0, 2), ("poll", 0.0, 1), ("poll", 0.0, 8),
+                                                      ("poll", 0.5, 8), ("poll", 1.0, 1), ("poll", 1.0, 8)]
+    # B = 4: |Q| = 6 >= 4 fires, take 2; |Q| = 4 fires, take 1; |Q| = 3: wait; at t = 1.0 the oldest has waited T_max
+    want = [(0.0, [0, 1]), (0.0, [2]), (1.0, [3]), (1.0, [4, 5])]
+    assert BO.simulate(ev, 4, 1.0) == want
+    got, left = run_native(ev, 4, 1.0, 0)
+    assert got == want and left == 0
+    g = np.random.default_rng(11)
+    ev = []
+    for e in random_trace(7, 300, rate=400.0, poll_dt=0.004, burstiness=[0.5, 0.4, 0.1]):
+        ev.append(e if e[0] == "push" else ("poll", e[1], int(g.integers(1, 12))))
+    assert run_native(ev, 8, 0.03, 0)[0] == BO.simulate(ev, 8, 0.03, 0)
+
+
 def test_native_queue_deadline_errors_and_threads():
     L = B.lib()
     q = B.Batcher(4, 0.25)
@@ -121,7 +138,7 @@ def test_native_queue_deadline_errors_and_threads():
     small = (B.vla_request * 2)()
     import ctypes as C
     n = C.c_int32()
-    assert L.vla_batcher_poll(q.h, 0.0, small, 2, C.byref(n)) == -4           # cap < target
+    assert L.vla_batcher_poll(q.h, 0.0, small, 0, C.byref(n)) == -4           # nothing can be taken
     h = C.c_void_p()
     assert L.vla_batcher_create(0, 1.0, 0, C.byref(h)) == -2
     assert L.vla_batcher_create(4, -1.0, 0, C.byref(h)) == -2

@@ -580,6 +580,162 @@ def test_head_already_cut_to_the_action_rows(name):
         assert np.array_equal(outs[0][k], outs[1][k]), k
 
 
+@pytest.mark.parametrize("name", ["fp32", "bf16"])
+def test_slot_calls_do_not_depend_on_placement_or_neighbours(name):
+    """vla_prefill_slots / vla_decode_slots: sequences prefilled at different times into scattered slots and decoded
+    together in another order give, row for row, the bits of the whole-batch calls on slots 0..B-1; freed slots
+    are reused; misuse is refused."""
+    import torch
+    from paper_2603_18464_amd import VlaError, VlaPolicy
+    if name == "fp32":
+        shape = W.get_workload("C1").shape
+    else:
+        shape = W.PolicyShape(2, 256, 2, 128, 704, 1024, dtype="bf16")
+    nps, lens = [40, 64, 17, 64, 1, 50], [9, 0, 30, 12, 0, 21]
+    wl = W.Workload("Tq", 31, shape, batch=6, n_patches=64, instr_len=(0, 30), n_tokens=4)
+    obs = ragged_obs(wl, nps, lens, seed=87)
+    weights = W.make_weights(shape, wl.seed)
+    pol = VlaPolicy(shape, 8, wl.max_seq, 6 * 94)
+    pol.load_weights(weights)
+    dev = P.device_inputs(pol, obs)
+    id0 = shape.action_id0
+    # reference: the whole-batch calls, greedy tokens fed back
+    lg = [pol.prefill(dev["patch_emb"], obs["cu_patch"], dev["instr_ids"], obs["cu_instr"])]
+    for _ in range(2):
+        lg.append(pol.decode_step((lg[-1].argmax(-1) + id0).to(torch.int32)))
+    ref = torch.stack(lg, 1).cpu().numpy()                       # [6, 3, A]
+
+    def sub(rows):
+        pe = torch.cat([dev["patch_emb"][obs["cu_patch"][r]:obs["cu_patch"][r + 1]] for r in rows])
+        ii = torch.cat([dev["instr_ids"][obs["cu_instr"][r]:obs["cu_instr"][r + 1]] for r in rows])
+        cu_p = np.concatenate([[0], np.cumsum([nps[r] for r in rows])]).astype(np.int32)
+        cu_i = np.concatenate([[0], np.cumsum([lens[r] for r in rows])]).astype(np.int32)
+        return pe, cu_p, ii, cu_i
+    got = np.zeros_like(ref)
+    nxt = {}
+
+    def record(rows, k, logits):
+        lgc = logits.cpu().numpy()
+        for i, r in enumerate(rows):
+            got[r, k] = lgc[i]
+            nxt[r] = int(lgc[i].argmax()) + id0
+    slot_of = {0: 5, 1: 2, 2: 7, 3: 0, 4: 3, 5: 5}                # request 5 reuses the slot of request 0
+    record([0, 1, 2], 0, pol.prefill_slots([5, 2, 7], *sub([0, 1, 2])))
+    # second wave arrives while the first decodes
+    record([3, 4], 0, pol.prefill_slots([0, 3], *sub([3, 4])))
+    order = [2, 0, 1]
+    record(order, 1, pol.decode_slots([slot_of[r] for r in order],
+                                      torch.tensor([nxt[r] for r in order], dtype=torch.int32, device=pol.device)))
+    order = [4, 1, 3, 0, 2]                                        # both waves in one step, mixed order
+    ks = {4: 1, 3: 1, 1: 2, 0: 2, 2: 2}
+    lgs = pol.decode_slots([slot_of[r] for r in order],
+                           torch.tensor([nxt[r] for r in order], dtype=torch.int32, device=pol.device)).cpu().numpy()
+    for i, r in enumerate(order):
+        got[r, ks[r]] = lgs[i]
+        nxt[r] = int(lgs[i].argmax()) + id0
+    pol.release_slots([5])                                         # request 0 is finished: its slot goes to request 5
+    record([5], 0, pol.prefill_slots([5], *sub([5])))
+    order = [5, 3, 4]
+    ks = {5: 1, 3: 2, 4: 2}
+    lgs = pol.decode_slots([slot_of[r] for r in order],
+                           torch.tensor([nxt[r] for r in order], dtype=torch.int32, device=pol.device)).cpu().numpy()
+    for i, r in enumerate(order):
+        got[r, ks[r]] = lgs[i]
+        nxt[r] = int(lgs[i].argmax()) + id0
+    record([5], 2, pol.decode_slots([5], torch.tensor([nxt[5]], dtype=torch.int32, device=pol.device)))
+    assert np.array_equal(got, ref)
+    # and the reference itself is the oracle's (teacher-forced on the GPU's greedy tokens)
+    from oracle import vla_oracle as O
+    pes, ids = P.split_obs(obs, list(range(6)))
+    forced = ref.argmax(-1)
+    ora = O.OraclePolicy(shape, weights).policy_step(pes, ids, 3, mode="cached", forced_tokens=forced)
+    assert np.abs(ref - ora["logits"]).max() <= P.tolerances(wl)["logit"]
+    # misuse
+    with pytest.raises(VlaError):
+        pol.decode_slots([6], torch.tensor([id0], dtype=torch.int32, device=pol.device))      # never filled
+    with pytest.raises(VlaError):
+        pol.prefill_slots([2, 2], *sub([0, 1]))                                                # duplicate
+    with pytest.raises(VlaError):
+        pol.prefill_slots([8], *sub([0]))                                                      # beyond max_batch
+    with pytest.raises(VlaError):
+        pol.decode_step(torch.tensor([id0] * 6, dtype=torch.int32, device=pol.device))        # whole-batch decode is off
+    pol.close()
+
+
+def test_continuous_worker_matches_batch_at_a_time_serving():
+    """More requests than cache slots, arriving over simulated time: every request is answered once, admissions
+    follow Eq. 1 cut to the free slots (oracle), and every admitted batch gets the bits that vla_policy_step gives
+    for the same batch alone; sampled answers meet the policy oracle."""
+    import torch
+    from oracle import batcher_oracle as BO
+    from oracle import vla_oracle as O
+    from paper_2603_18464_amd import ContinuousWorker, VlaPolicy
+    shape = W.PolicyShape(2, 256, 2, 128, 704, 1024, dtype="bf16")
+    K, Bt, T_max, n_req, n_slots = 5, 6, 0.010, 40, 10
+    wl = W.Workload("Sc", 37, shape, batch=n_slots, n_patches=48, instr_len=(0, 20), n_tokens=K, sampling="gumbel",
+                    temperature=0.8)
+    weights = W.make_weights(shape, wl.seed)
+    g = W.tensor_rng(wl.seed, "stream")
+    t_arr = np.cumsum(g.exponential(0.0015, n_req))
+    n_patch = g.choice([16, 48], n_req)
+    n_instr = g.integers(0, 21, n_req)
+    gum_all = W.make_gumbel(replace(wl, batch=n_req))
+    reqs = []
+    for r in range(n_req):
+        pe = W.bf16_bits_from_f32(g.standard_normal((int(n_patch[r]), shape.d_model), dtype=np.float32))
+        reqs.append((pe, g.integers(0, shape.action_id0, size=int(n_instr[r])).astype(np.int32)))
+    pol = VlaPolicy(shape, n_slots, 48 + 20 + K, n_slots * 68)
+    pol.load_weights(weights)
+    worker = ContinuousWorker(pol, Bt, T_max, n_tokens=K, temperature=wl.temperature)
+    dev = [(pol.to_device(pe), torch.from_numpy(ii).to(pol.device), torch.from_numpy(gum_all[r]).to(pol.device))
+           for r, (pe, ii) in enumerate(reqs)]
+    events, cohorts, a, t = [], [], 0, 0.0
+    while a < n_req or len(worker.queue) or worker.running:
+        while a < n_req and t_arr[a] <= t:
+            worker.submit(a, dev[a][0], dev[a][1], float(t_arr[a]), gumbel=dev[a][2])
+            events.append(("push", float(t_arr[a]), a, int(n_patch[a] + n_instr[a])))
+            a += 1
+        cap = len(worker.free)                # slots of batches that finish in this very step are freed after the admission
+        if cap:
+            events.append(("poll", t, cap))
+        for res in worker.step(t):
+            cohorts.append((res["ids"], res["tokens"].cpu().numpy(), res["logp"].cpu().numpy()))
+        assert len(worker.free) + sum(len(c["ids"]) for c in worker.running) == n_slots
+        t += 0.002
+    answered = [r for ids, _, _ in cohorts for r in ids]
+    assert sorted(answered) == list(range(n_req))
+    want = BO.simulate(events, Bt, T_max, n_slots * 68)
+    assert sorted(sorted(b) for _, b in want) == sorted(sorted(ids) for ids, _, _ in cohorts)
+    assert max(len(ids) for ids, _, _ in cohorts) <= Bt
+    # every admitted batch: same bits as the one-call policy step on that batch
+    for ids, tok, lp in cohorts[::3]:
+        pe = torch.cat([dev[r][0] for r in ids])
+        ii = torch.cat([dev[r][1] for r in ids])
+        cu_p = np.concatenate([[0], np.cumsum([n_patch[r] for r in ids])]).astype(np.int32)
+        cu_i = np.concatenate([[0], np.cumsum([n_instr[r] for r in ids])]).astype(np.int32)
+        gm = torch.stack([dev[r][2] for r in ids])
+        one = pol.policy_step(pe, cu_p, ii, cu_i, K, temperature=wl.temperature, gumbel=gm, action_dim=wl.action_dim)
+        assert np.array_equal(one["tokens"].cpu().numpy(), tok) and np.array_equal(one["logp"].cpu().numpy(), lp)
+    tol = P.tolerances(wl)
+    opol = O.OraclePolicy(shape, weights)
+    checked = 0
+    for ids, tok, lp in cohorts:
+        i = len(ids) - 1                      # the last request of every admitted batch
+        r = ids[i]
+        ora = opol.policy_step([reqs[r][0]], [reqs[r][1]], K, temperature=wl.temperature, gumbel=gum_all[r:r + 1],
+                               mode="cached")
+        gaps = P.top2_gap(ora["scores"])[0]
+        for k in range(K):
+            if tok[i, k] != ora["tokens"][0, k]:
+                assert gaps[k] < tol["tie"]
+                break
+            assert abs(lp[i, k] - ora["logp"][0, k]) <= tol["logp"]
+            checked += 1
+    assert checked >= 20 and len(cohorts) >= 6
+    worker.close()
+    pol.close()
+
+
 def test_policy_step_is_deterministic_and_matches_stepwise_calls():
     """Two identical policy steps give bit-identical outputs; prefill + select + decode_step called
     one by one reproduce vla_policy_step."""
