@@ -124,7 +124,6 @@ void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache
 // that add the partials in a fixed order and apply the elementwise step that follows each GEMM.
 // Activations named *_frag are [M, K] in MFMA fragment order: [m/32][k/16][lane][8].
 int skinny_ksplit(int N, int K);
-int skinny_effective_ksplit(int K, int ksplit);
 void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int K, int ksplit, hipStream_t st);
 void reduce_resid_norm(const float* part, int ksplit, int M, int d, float* x, const float* gain, float eps,
                        f16* hn_frag, int row0, hipStream_t st);

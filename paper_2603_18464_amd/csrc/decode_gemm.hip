@@ -175,11 +175,6 @@ void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int
 #undef VLA_SKINNY_CASE
 }
 
-int skinny_effective_ksplit(int K, int ksplit) {
-  (void)K;
-  return ksplit;
-}
-
 // ---- reduce + elementwise kernels ---------------------------------------------------------------------
 __device__ __forceinline__ size_t frag_index(int m, int k, int K) {
   return ((size_t)(m >> 5) * (K >> 4) + (k >> 4)) * 512 + ((m & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7);
