@@ -87,3 +87,32 @@ def test_serving_state_transitions_on_the_host():
     assert L.vla_get_state(None, None, None) == -1
     assert L.vla_drain_begin(None) == -1
     B.vla_destroy(ctx)
+
+
+def test_later_entry_points_refuse_null_and_unbound_contexts():
+    """Every compute entry point added after the first path checks the context before anything else."""
+    L = B.lib()
+    wl = W.get_workload("C1")
+    ctx = B.vla_create(B.make_config(wl.shape, 4, 64, 256, value_max_steps=2))
+    cu = (C.c_int32 * 2)(0, 1)
+    one = (C.c_int32 * 1)(0)
+    assert L.vla_policy_step_parallel(None, 1, None, cu, None, cu, 1, 0, 0.0, None, None, None, 7, None, None, None, None, None) == -1
+    assert L.vla_score_tokens(None, 1, None, cu, None, cu, 1, None, -1, 0.0, None, 1.0, None, None, None, None, None) == -1
+    assert L.vla_prefill_slots(None, 1, one, None, cu, None, cu, None, None) == -1
+    assert L.vla_decode_slots(None, 1, one, None, None, None) == -1
+    assert L.vla_release_slots(None, 1, one) == -1
+    assert L.vla_load_value_head(None, None, 0, None) == -1
+    assert L.vla_policy_step_value(None, 1, None, cu, None, cu, 1, 0.0, None, None, None, 7, None, None, None, None, None, None, None) == -1
+    # unbound context: state error, nothing touched
+    assert L.vla_policy_step_parallel(ctx, 1, None, cu, None, cu, 1, 0, 0.0, None, None, None, 7, None, None, None, None, None) == -5
+    assert L.vla_score_tokens(ctx, 1, None, cu, None, cu, 1, None, -1, 0.0, None, 1.0, None, None, None, None, None) == -5
+    assert L.vla_prefill_slots(ctx, 1, one, None, cu, None, cu, None, None) == -5
+    assert L.vla_decode_slots(ctx, 1, one, None, None, None) == -5
+    assert L.vla_policy_step_value(ctx, 1, None, cu, None, cu, 1, 0.0, None, None, None, 7, None, None, None, None, None, None, None) == -5
+    # slot lists are validated on the host
+    bad = (C.c_int32 * 2)(1, 1)
+    assert L.vla_release_slots(ctx, 2, bad) == -3
+    assert L.vla_release_slots(ctx, 1, (C.c_int32 * 1)(4)) == -3
+    assert L.vla_release_slots(ctx, 0, one) == -3
+    assert L.vla_release_slots(ctx, 1, one) == 0
+    B.vla_destroy(ctx)
