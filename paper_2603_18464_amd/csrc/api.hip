@@ -363,17 +363,24 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
     // GEMMs and their reduce kernels run on chunks of at most kSkinnyMaxRows rows (the weights are streamed
     // once per chunk); attention runs on the whole batch.
     auto frag_rows = [&](f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; };
+    // One chunk and a context the streaming attention kernel can hold: the attention kernel itself sums the QKV
+    // partials of its (sequence, head), applies RoPE and appends the new cache row, so the reduce pass is skipped.
+    const bool stream_attn = c.max_seq <= decode_attention_max_ctx(c.head_dim);
+    const bool fused_qkv = stream_attn && B <= kSkinnyMaxRows;
     {
       ProfScope ps(ctx, FAM_GEMM_QKV_DECODE, st);
       for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
         const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
         skinny_gemm(frag_rows(hn, r0, d), at<f16>(ctx->arena, lw.w_qkv), part, m, 3 * d, d, ks_qkv, st);
-        reduce_qkv_rope(part, ks_qkv, m, rk, r0, st);
+        if (!fused_qkv) reduce_qkv_rope(part, ks_qkv, m, rk, r0, st);
       }
     }
     {
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
-      if (c.max_seq <= decode_attention_max_ctx(c.head_dim))
+      if (fused_qkv)
+        decode_attention_fused(part, ks_qkv, rk.rope_cos, rk.rope_sin, (f16*)rk.k_cache, (f16*)rk.v_cache, tok_seq,
+                               tok_pos, att, B, d, c.n_heads, c.head_dim, kv_pitch(c), st);
+      else if (stream_attn)
         decode_attention(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, B, d, c.n_heads,
                          c.head_dim, kv_pitch(c), st);
       else

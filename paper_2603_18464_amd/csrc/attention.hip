@@ -241,24 +241,59 @@ void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache
 // owns 8 head dimensions of one row at a time: scores are reduced across the HD/8 lanes of a row with
 // shuffles, the probability-weighted values stay in 8 per-lane accumulators, and the partial softmax
 // statistics and outputs of the waves are merged through LDS at the end.
-template <int HD>
+//
+// FUSED: the query and the new key / value row of this (sequence, head) are not read from memory but formed
+// here from the split-K partial sums of the QKV GEMM (summed in plane order, RoPE applied, rounded to half
+// precision exactly as the stand-alone reduce kernel does); the new row is appended to the cache for the
+// following steps and used from LDS in this one.
+struct QkvPartials {
+  const float* part;       // [ksplit][rows][3 * d_model]
+  int ksplit, rows;
+  const float* rope_cos;   // [max_seq, HD/2]
+  const float* rope_sin;
+};
+
+template <int HD, bool FUSED>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
-    const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
+    const f16* __restrict__ q, int ldq, f16* __restrict__ k_cache, f16* __restrict__ v_cache,
     const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos, f16* __restrict__ out_frag,
-    int d_model, int n_heads, int max_seq) {
+    int d_model, int n_heads, int max_seq, QkvPartials qp) {
   constexpr int LPR = HD / 8;            // lanes per row
   constexpr int RPI = 64 / LPR;          // rows per wave instruction
   constexpr int MAXR = 40;               // score slots per lane: covers (ctx / (4*RPI)) rows per wave
   __shared__ float s_m[4], s_l[4];
   __shared__ float s_o[4][HD];
+  __shared__ __attribute__((aligned(16))) f16 s_q[HD], s_k[HD], s_v[HD];
   const int b = blockIdx.x, head = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPR, c = lane % LPR;          // row inside the instruction, 8-dim chunk
-  const int ctx = tok_pos[b] + 1;
+  const int ctx = tok_pos[b] + 1;                      // >= 2 in a decode step: the prefix holds a position
   const int slot = tok_seq[b];
-  const f16* kb = k_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
-  const f16* vb = v_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
-  const f16x8 qv = *(const f16x8*)(q + (size_t)b * ldq + head * HD + c * 8);
+  f16* kb = k_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
+  f16* vb = v_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
+  const int last_global = FUSED ? ctx - 2 : ctx - 1;   // last row that is read from the cache
+  if constexpr (FUSED) {
+    constexpr int HALF = HD / 2;
+    if (threadIdx.x < HALF) {
+      const int i = threadIdx.x, c0 = head * HD + i, c1 = c0 + HALF, d = d_model, pos = ctx - 1;
+      const size_t N = 3 * (size_t)d;
+      float v[6] = {};
+      for (int ks = 0; ks < qp.ksplit; ++ks) {
+        const float* p = qp.part + ((size_t)ks * qp.rows + b) * N;
+        v[0] += p[c0]; v[1] += p[c1]; v[2] += p[d + c0]; v[3] += p[d + c1]; v[4] += p[2 * d + c0]; v[5] += p[2 * d + c1];
+      }
+      const float cs = qp.rope_cos[pos * HALF + i], sn = qp.rope_sin[pos * HALF + i];
+      s_q[i] = from_f32<f16>(v[0] * cs - v[1] * sn);
+      s_q[i + HALF] = from_f32<f16>(v[1] * cs + v[0] * sn);
+      const f16 k0 = from_f32<f16>(v[2] * cs - v[3] * sn), k1 = from_f32<f16>(v[3] * cs + v[2] * sn);
+      const f16 v0 = from_f32<f16>(v[4]), v1 = from_f32<f16>(v[5]);
+      s_k[i] = k0; s_k[i + HALF] = k1; s_v[i] = v0; s_v[i + HALF] = v1;
+      kb[(size_t)pos * HD + i] = k0; kb[(size_t)pos * HD + i + HALF] = k1;
+      vb[(size_t)pos * HD + i] = v0; vb[(size_t)pos * HD + i + HALF] = v1;
+    }
+    __syncthreads();
+  }
+  const f16x8 qv = FUSED ? *(const f16x8*)(s_q + c * 8) : *(const f16x8*)(q + (size_t)b * ldq + head * HD + c * 8);
   float qf[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) qf[j] = (float)qv[j];
@@ -273,7 +308,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     sc[it] = -INFINITY;
     if (it < n_it) {
       const int row = (it * 4 + wave) * RPI + sub;
-      const f16x8 kv = *(const f16x8*)(kb + (size_t)min(row, ctx - 1) * HD + c * 8);
+      f16x8 kv = *(const f16x8*)(kb + (size_t)min(row, last_global) * HD + c * 8);
+      if (FUSED && row > last_global) kv = *(const f16x8*)(s_k + c * 8);
       float s = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) s = fmaf(qf[j], (float)kv[j], s);
@@ -295,7 +331,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     if (it < n_it) {
       const int row = (it * 4 + wave) * RPI + sub;
       const float p = __expf(sc[it] - m_use);              // exp(-inf) = 0 for rows past the end
-      const f16x8 vv = *(const f16x8*)(vb + (size_t)min(row, ctx - 1) * HD + c * 8);
+      f16x8 vv = *(const f16x8*)(vb + (size_t)min(row, last_global) * HD + c * 8);
+      if (FUSED && row > last_global) vv = *(const f16x8*)(s_v + c * 8);
       lsum += p;
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[j] = fmaf(p, (float)vv[j], acc[j]);
@@ -329,17 +366,31 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   }
 }
 
-// Rows are the slots 0..B-1 themselves (decode keeps token b in slot b).  ctx <= 4 * RPI * 40 rows.
+// Row b of the step lives in cache slot tok_seq[b].  ctx <= 4 * RPI * 40 rows.
 void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
                       const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
                       int max_seq, hipStream_t st) {
   const dim3 grid(B, n_heads);
+  const QkvPartials none{nullptr, 0, 0, nullptr, nullptr};
   if (head_dim == 128)
-    hipLaunchKernelGGL(decode_attention_kernel<128>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_seq,
-                       tok_pos, out_frag, d_model, n_heads, max_seq);
+    hipLaunchKernelGGL((decode_attention_kernel<128, false>), grid, dim3(256), 0, st, q, ldq, (f16*)k_cache,
+                       (f16*)v_cache, tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, none);
   else
-    hipLaunchKernelGGL(decode_attention_kernel<64>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, tok_seq,
-                       tok_pos, out_frag, d_model, n_heads, max_seq);
+    hipLaunchKernelGGL((decode_attention_kernel<64, false>), grid, dim3(256), 0, st, q, ldq, (f16*)k_cache,
+                       (f16*)v_cache, tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, none);
+}
+// Same, with the query and the new cache row taken from the QKV GEMM's partial sums part[ksplit][B][3 * d_model].
+void decode_attention_fused(const float* part, int ksplit, const float* rope_cos, const float* rope_sin, f16* k_cache,
+                            f16* v_cache, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, int B,
+                            int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
+  const dim3 grid(B, n_heads);
+  const QkvPartials qp{part, ksplit, B, rope_cos, rope_sin};
+  if (head_dim == 128)
+    hipLaunchKernelGGL((decode_attention_kernel<128, true>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache,
+                       tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, qp);
+  else
+    hipLaunchKernelGGL((decode_attention_kernel<64, true>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache,
+                       tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, qp);
 }
 int decode_attention_max_ctx(int head_dim) { return 4 * (64 / (head_dim / 8)) * 40; }
 

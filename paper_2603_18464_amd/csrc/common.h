@@ -136,6 +136,9 @@ void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, int 
 void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
                       const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
                       int max_seq, hipStream_t st);
+void decode_attention_fused(const float* part, int ksplit, const float* rope_cos, const float* rope_sin, f16* k_cache,
+                            f16* v_cache, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, int B,
+                            int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
 int decode_attention_max_ctx(int head_dim);
 
 // Action head: final RMSNorm + action rows of the LM head -> logits [B, A] float32.
