@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
 //                  LDS tile that was transposed while staging, with the key order inside each group of
 //                  16 arranged so that a lane's 8 keys are contiguous.
 template <int HD>
-__global__ __launch_bounds__(256) void flash_prefill_kernel(
+__global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
     const int32_t* __restrict__ cu_patch, const int32_t* __restrict__ cu_instr,
     const int32_t* __restrict__ slot_map, f16* __restrict__ out, int ldo, int n_heads, int max_seq) {
@@ -99,10 +99,16 @@ __global__ __launch_bounds__(256) void flash_prefill_kernel(
   const f16* kbase = k_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
   const f16* vbase = v_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
 
-  f16x8 qf[KS];
+  // The wave's query fragments live in LDS (chunk c of query column `col` in slot c ^ (col & 7): conflict-free
+  // 16-byte accesses); the registers they would occupy hold the prefetched next key / value tile instead.
+  __shared__ __attribute__((aligned(16))) f16 Qs[4][32 * HD];
+  f16* qs = Qs[wave];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-    qf[ks] = *(const f16x8*)(q + (size_t)qrow * ldq + head * HD + ks * 16 + half * 8);
+  for (int ks = 0; ks < KS; ++ks) {
+    const int ch = ks * 2 + half;
+    *(f16x8*)(qs + col * HD + ((ch ^ (col & 7)) << 3)) =
+        *(const f16x8*)(q + (size_t)qrow * ldq + head * HD + ch * 8);
+  }
 
   f32x16 o[DT];
 #pragma unroll
@@ -114,37 +120,56 @@ __global__ __launch_bounds__(256) void flash_prefill_kernel(
 
   const int kend = min(S, q0 + 128);                      // keys needed by this workgroup
   const int wave_last = q0 + wave * 32 + 31;              // last query position of this wave
+  // The next tile's keys and values are fetched into registers while the current tile is being consumed, so
+  // the global-memory latency of a tile hides under the MFMAs and the softmax of the one before.
+  constexpr int KI = 64 * KCH / 256, VI = 32 * KCH / 256;
+  u32x4 kreg[KI];
+  f16x8 vreg[VI][2];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < KI; ++i) {
+      const int item = t + 256 * i;
+      const int c = item % KCH, kk = item / KCH;
+      const int kp = min(k0 + kk, S - 1);
+      kreg[i] = *(const u32x4*)(kbase + (size_t)kp * HD + c * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < VI; ++i) {
+      const int item = t + 256 * i;
+      const int u = item & 31, c = item >> 5;
+      const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
+      vreg[i][0] = *(const f16x8*)(vbase + (size_t)ka * HD + c * 8);
+      vreg[i][1] = *(const f16x8*)(vbase + (size_t)kb * HD + c * 8);
+    }
+  };
+  fetch(0);
   for (int k0 = 0; k0 < kend; k0 += 64) {
     __syncthreads();                                      // previous tile fully consumed
     // K tile: 64 keys x KCH chunks, chunk c of key kk stored at slot c ^ (kk & 7) (low 3 bits)
 #pragma unroll
-    for (int i = 0; i < 64 * KCH / 256; ++i) {
+    for (int i = 0; i < KI; ++i) {
       const int item = t + 256 * i;
       const int c = item % KCH, kk = item / KCH;
-      const int kp = min(k0 + kk, S - 1);
-      const u32x4 v = *(const u32x4*)(kbase + (size_t)kp * HD + c * 8);
-      *(u32x4*)(Ks + kk * HD + ((c ^ (kk & 7)) << 3)) = v;
+      *(u32x4*)(Ks + kk * HD + ((c ^ (kk & 7)) << 3)) = kreg[i];
     }
     // V tile, transposed: Vt[dim][pos(key)], two keys per 32-bit store
 #pragma unroll
-    for (int i = 0; i < 32 * KCH / 256; ++i) {
+    for (int i = 0; i < VI; ++i) {
       const int item = t + 256 * i;
       const int u = item & 31, c = item >> 5;
-      const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
-      const f16x8 va = *(const f16x8*)(vbase + (size_t)ka * HD + c * 8);
-      const f16x8 vb = *(const f16x8*)(vbase + (size_t)kb * HD + c * 8);
       const int g = (2 * u) & 15;                         // position of the key inside its group of 16
       const int pos = ((2 * u) & ~15) + ((g >> 2) & 1) * 8 + (g >> 3) * 4 + (g & 3);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
         f16x2 pr;
-        pr[0] = va[j];
-        pr[1] = vb[j];
+        pr[0] = vreg[i][0][j];
+        pr[1] = vreg[i][1][j];
         *(f16x2*)(Vt + (c * 8 + j) * VPITCH + pos) = pr;
       }
     }
     __syncthreads();
+    if (k0 + 64 < kend) fetch(k0 + 64);                   // uniform across the workgroup
     if (k0 > wave_last) continue;                         // tile entirely above this wave's diagonal
 
     // S^T for the two 32-key sub-tiles
@@ -157,7 +182,8 @@ __global__ __launch_bounds__(256) void flash_prefill_kernel(
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const f16x8 kf = *(const f16x8*)(Ks + kk * HD + (((ks * 2 + half) ^ (kk & 7)) << 3));
-        sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ks], sacc[st], 0, 0, 0);
+        const f16x8 qfr = *(const f16x8*)(qs + col * HD + (((ks * 2 + half) ^ (col & 7)) << 3));
+        sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qfr, sacc[st], 0, 0, 0);
       }
     }
     // mask, running max
