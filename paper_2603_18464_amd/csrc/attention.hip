@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     }
     __syncthreads();
     if (k0 + 64 < kend) fetch(k0 + 64);                   // uniform across the workgroup
-    if (k0 > wave_last) continue;                         // tile entirely above this wave's diagonal
+    if (k0 > wave_last || q0 + wave * 32 >= S) continue;  // tile above this wave's diagonal, or no live query in the wave
 
     // S^T for the two 32-key sub-tiles
     f32x16 sacc[2];
