@@ -143,24 +143,37 @@ struct EpiQkv {
     const int d = o.d_model;
     const int sect = nb / d;
     const int head = (nb - sect * d) / HD + hh;
+    // Positions, slots and rotary factors of all eight row groups are fetched up front (rows past M clamped), so
+    // the two dependent global loads per row overlap instead of forming eight serial chains.
+    int pos[8], slot[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int m = min(m_base + it * 4 + rs, M - 1);
+      pos[it] = o.tok_pos[m];
+      slot[it] = o.tok_seq[m];
+    }
+    f32x4 cs[8], sn[8];
+    if (sect < 2) {
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        cs[it] = *(const f32x4*)(o.rope_cos + (size_t)pos[it] * HALF + c4);
+        sn[it] = *(const f32x4*)(o.rope_sin + (size_t)pos[it] * HALF + c4);
+      }
+    }
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int r = it * 4 + rs, m = m_base + r;
-      if (m >= M) continue;
       f32x4 lo = *(const f32x4*)(tile + r * kStagePitch + hh * HD + c4) * (1.0f / kWeightScale);
       f32x4 hi = *(const f32x4*)(tile + r * kStagePitch + hh * HD + HALF + c4) * (1.0f / kWeightScale);
-      const int pos = o.tok_pos[m];
       f16* dst;
       if (sect == 0) {
-        dst = (f16*)o.q + (size_t)m * d + (size_t)head * HD;
+        dst = (f16*)o.q + (size_t)min(m, M - 1) * d + (size_t)head * HD;
       } else {
-        const int slot = o.tok_seq[m];
-        dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) + (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * HD;
+        dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) +
+              (((size_t)slot[it] * o.n_heads + head) * o.max_seq + pos[it]) * HD;
       }
       if (sect < 2) {
-        const f32x4 cs = *(const f32x4*)(o.rope_cos + (size_t)pos * HALF + c4);
-        const f32x4 sn = *(const f32x4*)(o.rope_sin + (size_t)pos * HALF + c4);
-        const f32x4 a = lo * cs - hi * sn, b = hi * cs + lo * sn;
+        const f32x4 a = lo * cs[it] - hi * sn[it], b = hi * cs[it] + lo * sn[it];
         lo = a;
         hi = b;
       }
@@ -170,8 +183,10 @@ struct EpiQkv {
         l4[j] = from_f32<f16>(lo[j]);
         h4[j] = from_f32<f16>(hi[j]);
       }
-      *(f16x4*)(dst + c4) = l4;
-      *(f16x4*)(dst + HALF + c4) = h4;
+      if (m < M) {
+        *(f16x4*)(dst + c4) = l4;
+        *(f16x4*)(dst + HALF + c4) = h4;
+      }
     }
   }
   template <int MT, int NT>
