@@ -175,14 +175,17 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     // S^T for the two 32-key sub-tiles
     f32x16 sacc[2];
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
+    for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int e = 0; e < 16; ++e) sacc[st][e] = 0.f;
-      const int kk = st * 32 + col;
+    // k-step outermost: one query fragment serves both key sub-tiles, and the two accumulator chains alternate
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
+      const f16x8 qfr = *(const f16x8*)(qs + col * HD + (((ks * 2 + half) ^ (col & 7)) << 3));
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        const int kk = st * 32 + col;
         const f16x8 kf = *(const f16x8*)(Ks + kk * HD + (((ks * 2 + half) ^ (kk & 7)) << 3));
-        const f16x8 qfr = *(const f16x8*)(qs + col * HD + (((ks * 2 + half) ^ (col & 7)) << 3));
         sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qfr, sacc[st], 0, 0, 0);
       }
     }
