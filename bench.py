@@ -206,6 +206,14 @@ def main():
         extra["decode_gbs"] = gbs
         extra["decode_frac_of_hbm_peak"] = gbs / PEAK_HBM_GBS
         extra["decode_ms_per_token_step"] = dec_ms / max(1, wl.n_tokens - 1)
+    if wl.shape.dtype == "bf16":
+        # what this device sustains with nothing in the way, next to the vendor peaks the fractions are quoted on
+        mf, sr = P.vla_probe(pol.ctx, 0, pol._stream()), P.vla_probe(pol.ctx, 1, pol._stream())
+        extra["ceilings"] = {"mfma_only_tflops": mf, "stream_read_gbs": sr}
+        if roofline:
+            roofline["frac_of_measured_mfma_loop"] = roofline["achieved"] / mf
+        if "decode_gbs" in extra:
+            extra["decode_frac_of_measured_stream_read"] = extra["decode_gbs"] / sr
     extra["prefill_kernels_ms"] = pre_ms
     extra["families"] = fam
     # the one-pass (placeholder-fed) variant of the step on the same batch: reported, not the headline value

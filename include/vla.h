@@ -273,6 +273,15 @@ int vla_batcher_size(vla_batcher* b, int32_t* n);
 int vla_batcher_deadline(vla_batcher* b, double* t);
 int vla_batcher_poll(vla_batcher* b, double t_now, vla_request* out, int32_t cap, int32_t* n_out);
 
+/* Practical ceilings of the device the context runs on, for reporting next to the vendor peaks (benchmark
+ * support, not part of the policy path; unlike every other call it waits for its own kernels).  Needs loaded
+ * weights on the 16-bit path.
+ *   kind 0: an MFMA-only loop (8 independent 32x32x16 half-precision MFMAs per iteration and wave, two waves
+ *           per SIMD, operands = real weight fragments held in registers) -> *value_out in TFLOP/s
+ *   kind 1: a plain 16-byte-per-lane streaming read of all layer weights                -> *value_out in GB/s
+ * Best of three timed runs after a warm-up. */
+int vla_probe(vla_ctx* ctx, int32_t kind, double* value_out, void* hip_stream);
+
 /* Selection alone, for callers that drive vla_prefill / vla_decode_step themselves:
  * logits [B, n_action_bins] (device) -> bin index, log-prob, action, for token index k of the
  * chunk (k selects the action dimension k mod action_dim and the row [b, k] of gumbel [B, K, A]).

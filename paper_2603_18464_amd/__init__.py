@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     vla_policy_step_parallel, vla_score_tokens, vla_prefill_slots, vla_decode_slots, vla_release_slots,
     vla_get_state, vla_drain_begin, vla_update_begin, vla_update_tensors, vla_update_commit,
     VLA_ACCEPTING, VLA_DRAINING, VLA_UPDATING, VLA_E_STATE, VLA_E_DRAINING,
-    vla_prof_enable, vla_prof_count, vla_prof_read,
+    vla_prof_enable, vla_prof_count, vla_prof_read, vla_probe,
 )
 from .serving import ContinuousWorker, InferenceWorker  # noqa: F401,E402

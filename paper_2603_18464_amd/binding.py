@@ -18,6 +18,7 @@ EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vl
            "vla_load_value_head", "vla_policy_step_value",
            "vla_policy_step_parallel", "vla_score_tokens",
            "vla_prefill_slots", "vla_decode_slots", "vla_release_slots",
+           "vla_probe",
            "vla_batcher_create", "vla_batcher_destroy", "vla_batcher_push", "vla_batcher_size",
            "vla_batcher_deadline", "vla_batcher_poll",
            "vla_get_state", "vla_drain_begin", "vla_update_begin", "vla_update_tensors", "vla_update_commit",
@@ -86,6 +87,7 @@ def lib() -> C.CDLL:
         L.vla_prefill_slots.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.vla_decode_slots.argtypes = [vp, i32, vp, vp, vp, vp]
         L.vla_release_slots.argtypes = [vp, i32, vp]
+        L.vla_probe.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
         L.vla_batcher_create.argtypes = [i32, C.c_double, C.c_int64, C.POINTER(vp)]
         L.vla_batcher_destroy.argtypes = [vp]
         L.vla_batcher_push.argtypes = [vp, C.POINTER(vla_request)]
@@ -259,6 +261,12 @@ def vla_select(ctx, B, logits, temperature, gumbel, k, n_tokens, act_scale, act_
     _check(ctx, lib().vla_select(ctx, B, _ptr(logits), temperature, _ptr(gumbel), k, n_tokens, _ptr(act_scale),
                                  _ptr(act_offset), action_dim, _ptr(tokens_out), _ptr(logp_out),
                                  _ptr(actions_out), out_stride, _ptr(next_ids_out), stream))
+
+
+def vla_probe(ctx, kind: int, stream: int = 0) -> float:
+    v = C.c_double()
+    _check(ctx, lib().vla_probe(ctx, kind, C.byref(v), stream))
+    return v.value
 
 
 def vla_prof_enable(ctx, mask: int) -> None:

@@ -1251,6 +1251,42 @@ int vla_score_tokens(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32
   return leave_compute(ctx, st);
 }
 
+int vla_probe(vla_ctx* ctx, int32_t kind, double* value_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  if (!value_out) return fail(ctx, VLA_E_NULL, "value_out is NULL");
+  if (!ctx->bound || !ctx->weights) return fail(ctx, VLA_E_STATE, "the probes read the loaded weight arena");
+  if (ctx->cfg.dtype != VLA_BF16) return fail(ctx, VLA_E_CONFIG, "the probes are for the 16-bit path");
+  if (kind != 0 && kind != 1) return fail(ctx, VLA_E_SHAPE, "kind must be 0 (MFMA loop) or 1 (streaming read)");
+  hipStream_t st = (hipStream_t)hip_stream;
+  // layer 0's fused gate/up matrix: fragment-ordered half-precision weights
+  const vla_config& c = ctx->cfg;
+  const f16* w = at<f16>(ctx->arena, ctx->al.layers[0].w_gu);
+  const size_t w_bytes = (size_t)2 * c.d_ffn * c.d_model * sizeof(f16);
+  const size_t bytes = kind == 1 ? ctx->al.total - ctx->al.layers[0].w_qkv : 0;   // all layer matrices and gains
+  float* sink = at<float>(ctx->work, ctx->wl.logits);
+  hipEvent_t e0, e1;
+  HIP_TRY(ctx, hipEventCreate(&e0));
+  HIP_TRY(ctx, hipEventCreate(&e1));
+  const int n_wg = 512, iters = 8192, reps = 3;
+  float best = 1e30f;
+  for (int r = 0; r < reps + 1; ++r) {     // first run warms up
+    HIP_TRY(ctx, hipEventRecord(e0, st));
+    if (kind == 0) probe_mfma(w, w_bytes / 1024, n_wg, iters, sink, st);
+    else probe_stream(at<char>(ctx->arena, ctx->al.layers[0].w_qkv), bytes, 4096, (unsigned*)sink, st);
+    HIP_TRY(ctx, hipEventRecord(e1, st));
+    HIP_TRY(ctx, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, e0, e1));
+    if (r > 0 && ms < best) best = ms;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  HIP_TRY(ctx, hipGetLastError());
+  if (kind == 0) *value_out = (double)n_wg * 4 * iters * 8 * 32768.0 / (best * 1e-3) / 1e12;   // TFLOP/s
+  else *value_out = (double)bytes / (best * 1e-3) / 1e9;                                        // GB/s
+  return VLA_OK;
+}
+
 int vla_prof_enable(vla_ctx* ctx, int32_t mask) {
   if (!ctx) return VLA_E_NULL;
   for (auto& v : ctx->prof) {

@@ -171,6 +171,10 @@ void chunk_rows(const int32_t* last_row, int B, int K, int32_t* rows, hipStream_
 void score_rows(const float* logits, int rows, int A, float temperature, const int32_t* tokens, const float* mu,
                 float sigma, float* logp_out, float* ratio_out, float* weight_out, hipStream_t st);
 
+// Ceiling probes (see vla_probe): an MFMA-only loop on weight bits and a plain streaming read.
+void probe_mfma(const f16* w, size_t n_frag, int n_wg, int iters, float* sink, hipStream_t st);
+void probe_stream(const void* src, size_t bytes, int n_wg, unsigned* sink, hipStream_t st);
+
 // Small utilities.
 void rope_table(float* cos_t, float* sin_t, int max_seq, int head_dim, float theta, hipStream_t st);
 // slot_map: device [B] cache slot of each sequence of the call, nullptr = identity; seq_len is indexed by slot.

@@ -479,6 +479,57 @@ template void value_finish<bf16>(const float*, const float*, const bf16*, int, c
                                  const float*, const float*, const float*, int, int, float*, float*, float*,
                                  hipStream_t);
 
+// ---- practical ceilings, measured on request ------------------------------------------------------------
+// MFMA-only loop: every wave loads two A and four B fragments once (real weight bits, so the operands toggle
+// like real data) and issues 8 independent 32x32x16 MFMAs per iteration on them; nothing else runs.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(const f16* __restrict__ w, size_t n_frag, int iters,
+                                                         float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  f16x8 a[2], b[4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) a[i] = *(const f16x8*)(w + ((wave * 6 + i) % n_frag) * 512 + lane * 8);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = *(const f16x8*)(w + ((wave * 6 + 2 + i) % n_frag) * 512 + lane * 8);
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  for (int it = 0; it < iters; ++it)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) t += acc[i][j][0];
+  if (t == 123.456f) sink[0] = t;      // keeps the loop alive; never true in practice
+}
+void probe_mfma(const f16* w, size_t n_frag, int n_wg, int iters, float* sink, hipStream_t st) {
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(n_wg), dim3(256), 0, st, w, n_frag, iters, sink);
+}
+// Streaming read: 16 bytes per lane, grid-stride, four loads in flight per lane.
+__global__ __launch_bounds__(256) void probe_stream_kernel(const u32x4* __restrict__ src, size_t n16,
+                                                           unsigned* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  unsigned x = 0;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    x ^= a[0] ^ b[1] ^ c[2] ^ d[3];
+  }
+  for (; i < n16; i += stride) x ^= src[i][0];
+  if (x == 0x9e3779b9u) sink[0] = x;   // practically never
+}
+void probe_stream(const void* src, size_t bytes, int n_wg, unsigned* sink, hipStream_t st) {
+  hipLaunchKernelGGL(probe_stream_kernel, dim3(n_wg), dim3(256), 0, st, (const u32x4*)src, bytes / 16, sink);
+}
+
 // ---- selection ----------------------------------------------------------------------------------------
 // One wave per sequence: scores = logits / tau (+ Gumbel noise); token = lowest index among the
 // maxima; log-prob = log_softmax(logits / tau)[token]; action = bin centre (optionally affine).

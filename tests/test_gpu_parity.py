@@ -736,6 +736,26 @@ def test_continuous_worker_matches_batch_at_a_time_serving():
     pol.close()
 
 
+def test_ceiling_probes_report_plausible_rates():
+    """vla_probe: both probes run on the loaded arena of a 16-bit context, give finite positive rates below the
+    vendor peaks, and refuse contexts they cannot use."""
+    from paper_2603_18464_amd import VlaError, vla_probe
+    wl = W.get_workload("C2")
+    pol = make_policy(wl, W.make_weights(wl.shape, wl.seed))
+    mf = vla_probe(pol.ctx, 0, pol._stream())
+    sr = vla_probe(pol.ctx, 1, pol._stream())
+    print(f"\nMFMA-only loop {mf:.0f} TFLOP/s, streaming read {sr:.0f} GB/s (C2 arena)")
+    assert 100 < mf < 2600 and 100 < sr < 20000          # the small arena may be served by the caches
+    with pytest.raises(VlaError):
+        vla_probe(pol.ctx, 2, pol._stream())
+    pol.close()
+    c1 = W.get_workload("C1")
+    pol = make_policy(c1, W.make_weights(c1.shape, c1.seed))
+    with pytest.raises(VlaError):
+        vla_probe(pol.ctx, 0, pol._stream())                # float32 context
+    pol.close()
+
+
 def test_policy_step_is_deterministic_and_matches_stepwise_calls():
     """Two identical policy steps give bit-identical outputs; prefill + select + decode_step called
     one by one reproduce vla_policy_step."""
