@@ -214,6 +214,7 @@ def main():
             roofline["frac_of_measured_mfma_loop"] = roofline["achieved"] / mf
         if "decode_gbs" in extra:
             extra["decode_frac_of_measured_stream_read"] = extra["decode_gbs"] / sr
+    extra["action_tokens_per_s"] = wl.batch * wl.n_tokens / (dt / args.steps)
     extra["prefill_kernels_ms"] = pre_ms
     extra["families"] = fam
     # the one-pass (placeholder-fed) variant of the step on the same batch: reported, not the headline value
