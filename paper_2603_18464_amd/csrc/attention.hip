@@ -289,7 +289,6 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     int d_model, int n_heads, int max_seq, QkvPartials qp) {
   constexpr int LPR = HD / 8;            // lanes per row
   constexpr int RPI = 64 / LPR;          // rows per wave instruction
-  constexpr int MAXR = 40;               // score slots per lane: covers (ctx / (4*RPI)) rows per wave
   __shared__ float s_m[4], s_l[4];
   __shared__ float s_o[4][HD];
   __shared__ __attribute__((aligned(16))) f16 s_q[HD], s_k[HD], s_v[HD];
@@ -328,44 +327,54 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   for (int j = 0; j < 8; ++j) qf[j] = (float)qv[j];
   const float scale = rsqrtf((float)HD);
 
-  // pass 1: scores of this wave's rows (row = (it*4 + wave)*RPI + sub), kept in registers
-  float sc[MAXR];
-  float mx = -INFINITY;
+  // One pass with a running maximum per lane (row = (it*4 + wave)*RPI + sub): the key row and the value row of
+  // an iteration are requested together, so twice as many bytes are in flight as with a score pass followed by
+  // a value pass, and no scores have to be kept.
+  float m_run = -INFINITY, lsum = 0.f;
+  float acc[8] = {};
   const int n_it = (ctx + 4 * RPI - 1) / (4 * RPI);
+  constexpr int U = 8;                     // iterations whose loads are issued together (16 rows of 16 bytes per lane)
+  for (int it0 = 0; it0 < n_it; it0 += U) {
+    f16x8 kv[U], vv[U];
 #pragma unroll
-  for (int it = 0; it < MAXR; ++it) {
-    sc[it] = -INFINITY;
-    if (it < n_it) {
-      const int row = (it * 4 + wave) * RPI + sub;
-      f16x8 kv = *(const f16x8*)(kb + (size_t)min(row, last_global) * HD + c * 8);
-      if (FUSED && row > last_global) kv = *(const f16x8*)(s_k + c * 8);
+    for (int u = 0; u < U; ++u) {
+      const int row = ((it0 + u) * 4 + wave) * RPI + sub;
+      kv[u] = *(const f16x8*)(kb + (size_t)min(row, last_global) * HD + c * 8);
+      vv[u] = *(const f16x8*)(vb + (size_t)min(row, last_global) * HD + c * 8);
+      if (FUSED && row > last_global) {
+        kv[u] = *(const f16x8*)(s_k + c * 8);
+        vv[u] = *(const f16x8*)(s_v + c * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = ((it0 + u) * 4 + wave) * RPI + sub;
       float s = 0.f;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) s = fmaf(qf[j], (float)kv[j], s);
+      for (int j = 0; j < 8; ++j) s = fmaf(qf[j], (float)kv[u][j], s);
 #pragma unroll
       for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-      s = row < ctx ? s * scale : -INFINITY;
-      sc[it] = s;
-      mx = fmaxf(mx, s);
+      if (row < ctx) {                                      // uniform over the LPR lanes of a row
+        s *= scale;
+        const float m_new = fmaxf(m_run, s);
+        const float alpha = __expf(m_run - m_new);          // exp(-inf) = 0 on the lane's first row
+        const float p = __expf(s - m_new);
+        lsum = lsum * alpha + p;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = fmaf(p, (float)vv[u][j], acc[j] * alpha);
+        m_run = m_new;
+      }
     }
   }
+  // bring the lanes of the wave to a common maximum, then add the row groups
+  float mx = m_run;
 #pragma unroll
-  for (int o = 32; o >= LPR; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));   // over the rows of the wave
-  const float m_use = mx == -INFINITY ? 0.f : mx;
-  // pass 2: probabilities and weighted values
-  float acc[8] = {};
-  float lsum = 0.f;
+  for (int o = 32; o >= LPR; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  {
+    const float f = m_run == -INFINITY ? 0.f : __expf(m_run - mx);
+    lsum *= f;
 #pragma unroll
-  for (int it = 0; it < MAXR; ++it) {
-    if (it < n_it) {
-      const int row = (it * 4 + wave) * RPI + sub;
-      const float p = __expf(sc[it] - m_use);              // exp(-inf) = 0 for rows past the end
-      f16x8 vv = *(const f16x8*)(vb + (size_t)min(row, last_global) * HD + c * 8);
-      if (FUSED && row > last_global) vv = *(const f16x8*)(s_v + c * 8);
-      lsum += p;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[j] = fmaf(p, (float)vv[j], acc[j]);
-    }
+    for (int j = 0; j < 8; ++j) acc[j] *= f;
   }
 #pragma unroll
   for (int o = 32; o >= LPR; o >>= 1) {
@@ -421,6 +430,8 @@ void decode_attention_fused(const float* part, int ksplit, const float* rope_cos
     hipLaunchKernelGGL((decode_attention_kernel<64, true>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache,
                        tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, qp);
 }
+// The streaming kernel has no context limit of its own any more; the bound keeps the row-wise kernel in use for
+// very long contexts, where its one-workgroup-per-row layout spreads the work better.
 int decode_attention_max_ctx(int head_dim) { return 4 * (64 / (head_dim / 8)) * 40; }
 
 template <class T>
