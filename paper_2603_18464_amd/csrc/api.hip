@@ -363,10 +363,9 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
     // GEMMs and their reduce kernels run on chunks of at most kSkinnyMaxRows rows (the weights are streamed
     // once per chunk); attention runs on the whole batch.
     auto frag_rows = [&](f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; };
-    // One chunk and a context the streaming attention kernel can hold: the attention kernel itself sums the QKV
-    // partials of its (sequence, head), applies RoPE and appends the new cache row, so the reduce pass is skipped.
-    const bool stream_attn = c.max_seq <= decode_attention_max_ctx(c.head_dim);
-    const bool fused_qkv = stream_attn && B <= kSkinnyMaxRows;
+    // One chunk: the attention kernel itself sums the QKV partials of its (sequence, head), applies RoPE and
+    // appends the new cache row, so the reduce pass is skipped.
+    const bool fused_qkv = B <= kSkinnyMaxRows;
     {
       ProfScope ps(ctx, FAM_GEMM_QKV_DECODE, st);
       for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
@@ -380,12 +379,9 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
       if (fused_qkv)
         decode_attention_fused(part, ks_qkv, rk.rope_cos, rk.rope_sin, (f16*)rk.k_cache, (f16*)rk.v_cache, tok_seq,
                                tok_pos, att, B, d, c.n_heads, c.head_dim, kv_pitch(c), st);
-      else if (stream_attn)
+      else
         decode_attention(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, B, d, c.n_heads,
                          c.head_dim, kv_pitch(c), st);
-      else
-        attention_rows<f16>(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, d, B,
-                            c.n_heads, c.head_dim, kv_pitch(c), true, st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_O_DECODE, st);

@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   }
 }
 
-// Row b of the step lives in cache slot tok_seq[b].  ctx <= 4 * RPI * 40 rows.
+// Row b of the step lives in cache slot tok_seq[b].
 void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
                       const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
                       int max_seq, hipStream_t st) {
@@ -430,9 +430,6 @@ void decode_attention_fused(const float* part, int ksplit, const float* rope_cos
     hipLaunchKernelGGL((decode_attention_kernel<64, true>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache,
                        tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, qp);
 }
-// The streaming kernel has no context limit of its own any more; the bound keeps the row-wise kernel in use for
-// very long contexts, where its one-workgroup-per-row layout spreads the work better.
-int decode_attention_max_ctx(int head_dim) { return 4 * (64 / (head_dim / 8)) * 40; }
 
 template <class T>
 void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, const int32_t* tok_seq,

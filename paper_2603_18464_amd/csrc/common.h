@@ -131,15 +131,13 @@ void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f1
 void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, int row0, hipStream_t st);
 void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, int row0, hipStream_t st);
 
-// Decode attention of the 16-bit path (one query per slot); output in fragment order.  Handles contexts
-// up to decode_attention_max_ctx(head_dim) positions.
+// Decode attention of the 16-bit path (one query per row of the step); output in fragment order.
 void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
                       const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
                       int max_seq, hipStream_t st);
 void decode_attention_fused(const float* part, int ksplit, const float* rope_cos, const float* rope_sin, f16* k_cache,
                             f16* v_cache, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, int B,
                             int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
-int decode_attention_max_ctx(int head_dim);
 
 // Action head: final RMSNorm + action rows of the LM head -> logits [B, A] float32.
 template <class T>

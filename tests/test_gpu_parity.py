@@ -108,9 +108,8 @@ def test_bf16_tiny_prefixes_keep_every_row_in_the_last_layer():
 
 
 @pytest.mark.parametrize("hd,heads", [(128, 2), (64, 4)])
-def test_bf16_long_context_uses_the_general_decode_attention(hd, heads):
-    """Contexts beyond what the streaming decode-attention kernel holds in registers (640 positions at head
-    size 128, 320 at 64): decode falls back to the row-wise attention kernel, prefill walks 11 key tiles."""
+def test_bf16_long_context(hd, heads):
+    """Contexts of 600+ positions: decode attention streams 40+ row groups per wave, prefill walks 11 key tiles."""
     shape = W.PolicyShape(2, 256, heads, hd, 704, 1024, dtype="bf16")
     nps, lens = [640, 600, 333], [41, 0, 17]
     wl = W.Workload("Tl", 23, shape, batch=3, n_patches=640, instr_len=(0, 41), n_tokens=4,
