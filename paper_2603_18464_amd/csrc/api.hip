@@ -134,7 +134,8 @@ const char* check_config(const vla_config& c) {
     if (c.head_dim != 64 && c.head_dim != 128) return "bf16 path needs head_dim 64 or 128";
     if (c.d_model % 128 || c.d_ffn % 64) return "bf16 path needs d_model % 128 == 0 and d_ffn % 64 == 0";
   }
-  if ((size_t)(c.head_dim + kv_pitch(c)) * 16 > 64 * 1024) return "max_seq too large for the attention kernel's LDS";
+  if (c.dtype == VLA_F32 && (size_t)(c.head_dim + kv_pitch(c)) * 16 > 64 * 1024)
+    return "max_seq too large for the float32 attention kernel's LDS";
   if ((int64_t)c.d_model * 4 > 64 * 1024) return "d_model too large for the head kernel's LDS";
   return nullptr;
 }
