@@ -41,12 +41,19 @@ def model_numbers(wl, cu_seq):
 
 
 def measured_traffic(kernel: str, workload: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary (profiles/traffic.json), or None."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    """HBM-side bytes per launch (fetch + write) from the committed rocprofv3 --pmc summary
+    profiles/pmc_traffic_<workload>.md, or None if the summary or the kernel's row is missing."""
+    path = os.path.join(ROOT, "profiles", f"pmc_traffic_{workload}.md")
     if not os.path.exists(path):
         return None
-    entry = json.load(open(path)).get(f"{kernel}:{workload}")
-    return None if entry is None else entry.get("hbm_bytes_per_launch")
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and cells[0] == kernel:
+            try:
+                return (float(cells[2]) + float(cells[3])) * 1e6
+            except ValueError:
+                return None
+    return None
 
 
 def cpu_baseline(wl, weights_fn, obs, sample_layers):
