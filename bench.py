@@ -149,8 +149,9 @@ def main():
     gum = W.make_gumbel(wl) if wl.sampling == "gumbel" else None
     cu_seq = obs["cu_patch"] + obs["cu_instr"]
     nums = model_numbers(wl, cu_seq)
-    pol = VlaPolicy(wl.shape, wl.batch, wl.max_seq, nums["T"] + wl.batch * (wl.n_tokens - 1))
+    pol = VlaPolicy(wl.shape, wl.batch, wl.max_seq, nums["T"] + wl.batch * (wl.n_tokens - 1), value_max_steps=64)
     pol.load_weights(weights)
+    pol.load_value_head(W.make_value_weights(wl.shape, wl.seed, 64))
     if args.no_weight_update:
         del weights
     pe = pol.to_device(obs["patch_emb"])
@@ -241,6 +242,21 @@ def main():
     pdt = (time.perf_counter() - t0) / args.steps
     extra["parallel_decoding"] = {"ms_per_step": pdt * 1e3,
                                   "actions_per_s": wl.batch * (wl.n_tokens / wl.action_dim) / pdt}
+    # the same step with the value head on the rollout path (v_t of the trajectory), reported only
+    vout = None
+    step_t = torch.arange(wl.batch, dtype=torch.int32, device=pol.device) % 64
+
+    def vstep():
+        nonlocal vout
+        vout = pol.policy_step(pe, obs["cu_patch"], ids, obs["cu_instr"], wl.n_tokens, temperature=temp, gumbel=gdev,
+                               action_dim=wl.action_dim, out=vout, step_t=step_t)
+    vstep()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        vstep()
+    torch.cuda.synchronize()
+    extra["with_value_head_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
     if not args.no_weight_update:
         extra["weight_update"] = weight_update_leg(pol, weights, step, torch)
         del weights
