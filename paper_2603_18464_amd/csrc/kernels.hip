@@ -434,24 +434,65 @@ __global__ __launch_bounds__(256) void value_pool_kernel(const float* __restrict
     vu[(size_t)b * d + i] = vz[(size_t)b * d + i] * inv_l + to_f32(step_emb[(size_t)t * d + i]);
 }
 
-// vh[b][j] = w2[j] * gelu(W1[j,:] . u[b] + b1[j]); one wave per output row j, the row kept in registers.
-template <class T>
+// vh[b][j] = w2[j] * gelu(W1[j,:] . u[b] + b1[j]).  A workgroup keeps RB rows of u in LDS; each wave then walks
+// 16 rows of W1, reading every weight once from memory for all RB rows.
+__device__ __forceinline__ f32x4 load4_f32(const float* p) { return *(const f32x4*)p; }
+__device__ __forceinline__ f32x4 load4_f32(const bf16* p) {
+  const bf16x4 v = *(const bf16x4*)p;
+  return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+}
+template <class T, int RB>
 __global__ __launch_bounds__(256) void value_mlp_kernel(const T* __restrict__ w1, const float* __restrict__ b1,
                                                         const float* __restrict__ w2, const float* __restrict__ vu,
                                                         int B, int d, float* __restrict__ vh) {
-  const int lane = threadIdx.x & 63, j = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (j >= d) return;
-  const T* wr = w1 + (size_t)j * d;
-  for (int b = 0; b < B; ++b) {
-    const float* u = vu + (size_t)b * d;
-    float acc = 0.f;
-    for (int i = lane; i < d; i += 64) acc = fmaf(to_f32(wr[i]), u[i], acc);
-    acc = wave_sum(acc);
+  extern __shared__ float us[];                             // [RB][d]
+  constexpr int JPW = 16;                                   // rows of W1 per wave
+  const int b0 = blockIdx.x * RB, nb = min(RB, B - b0);
+  for (int i = threadIdx.x * 4; i < RB * d; i += 1024) {
+    const int r = i / d, c = i - r * d;                     // d is a multiple of 4: a float4 stays inside a row
+    *(f32x4*)(us + i) = r < nb ? *(const f32x4*)(vu + (size_t)(b0 + r) * d + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int jj = 0; jj < JPW; ++jj) {
+    const int j = (blockIdx.y * 4 + wave) * JPW + jj;
+    if (j >= d) break;                                      // uniform per wave
+    const T* wr = w1 + (size_t)j * d;
+    float acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+    for (int c = lane * 4; c < d; c += 256) {
+      const f32x4 w = load4_f32(wr + c);
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+        const f32x4 u = *(const f32x4*)(us + r * d + c);
+        acc[r] += w[0] * u[0] + w[1] * u[1] + w[2] * u[2] + w[3] * u[3];
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = wave_sum(acc[r]);
     if (lane == 0) {
-      const float t = acc + b1[j];
-      vh[(size_t)b * d + j] = w2[j] * 0.5f * t * (1.0f + erff(t * 0.70710678118654752f));
+      const float bj = b1[j], wj = w2[j];
+#pragma unroll
+      for (int r = 0; r < RB; ++r)
+        if (r < nb) {
+          const float t = acc[r] + bj;
+          vh[(size_t)(b0 + r) * d + j] = wj * 0.5f * t * (1.0f + erff(t * 0.70710678118654752f));
+        }
     }
   }
+}
+template <class T, int RB>
+static void launch_value_mlp(const T* w1, const float* b1, const float* w2, const float* vu, int B, int d, float* vh,
+                             hipStream_t st) {
+  const size_t smem = (size_t)RB * d * sizeof(float);
+  auto kern = value_mlp_kernel<T, RB>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((B + RB - 1) / RB, (d + 63) / 64), dim3(256), smem, st, w1, b1, w2, vu, B, d, vh);
 }
 
 __global__ __launch_bounds__(256) void value_sum_kernel(const float* __restrict__ vh, const float* __restrict__ b2,
@@ -469,7 +510,9 @@ void value_finish(const float* vz, const float* vml, const T* step_emb, int n_st
                   const T* w1, const float* b1, const float* w2, const float* b2, int B, int d, float* vu, float* vh,
                   float* values, hipStream_t st) {
   hipLaunchKernelGGL(value_pool_kernel<T>, dim3(B), dim3(256), 0, st, vz, vml, step_emb, n_steps, step_t, d, vu);
-  hipLaunchKernelGGL(value_mlp_kernel<T>, dim3((d + 3) / 4), dim3(256), 0, st, w1, b1, w2, vu, B, d, vh);
+  if (d <= 5120) launch_value_mlp<T, 8>(w1, b1, w2, vu, B, d, vh, st);            // RB * d floats of LDS <= 160 KiB
+  else if (d <= 10240) launch_value_mlp<T, 4>(w1, b1, w2, vu, B, d, vh, st);
+  else launch_value_mlp<T, 2>(w1, b1, w2, vu, B, d, vh, st);
   hipLaunchKernelGGL(value_sum_kernel, dim3(B), dim3(256), 0, st, vh, b2, d, values);
 }
 template void value_finish<float>(const float*, const float*, const float*, int, const int32_t*, const float*,
