@@ -1,6 +1,6 @@
 // C ABI of the VLA policy library: context, validation, weight repacking and the host-side
 // orchestration of prefill, decode step and policy step.  All device work is enqueued on the
-// caller's stream; nothing here synchronises the device except the profiling read-out.
+// caller's stream; nothing here synchronises the device except the profiling read-out and vla_probe.
 #include <hip/hip_runtime.h>
 
 #include <cstdarg>
