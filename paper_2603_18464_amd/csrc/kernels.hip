@@ -576,6 +576,8 @@ void probe_stream(const void* src, size_t bytes, int n_wg, unsigned* sink, hipSt
 // ---- selection ----------------------------------------------------------------------------------------
 // One wave per sequence: scores = logits / tau (+ Gumbel noise); token = lowest index among the
 // maxima; log-prob = log_softmax(logits / tau)[token]; action = bin centre (optionally affine).
+// Non-finite input: NaN scores never win the comparison, so the token is the best of the others; a row
+// with no score above -inf (all NaN or all -inf) selects bin 0.  The log-prob of such rows is NaN.
 __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ logits, int ld_logits, int A, float temperature,
                                                     const float* __restrict__ gumbel, int k, int n_tokens,
                                                     const float* __restrict__ act_scale,
@@ -600,6 +602,7 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ lo
     const int oj = __shfl_xor(best_j, o, 64);
     if (ob > best || (ob == best && oj < best_j)) { best = ob; best_j = oj; }
   }
+  if (best_j >= A) best_j = 0;                     // no lane saw a score above -inf
   zmax = wave_max(zmax);
   float se = 0.f;
   for (int j = lane; j < A; j += 64) se += expf(z[j] * inv_tau - zmax);
