@@ -125,6 +125,18 @@ int vla_prefill(vla_ctx* ctx, int32_t B, const void* patch_emb, const int32_t* c
 int vla_decode_step(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits_out,
                     void* hip_stream);
 
+/* vla_decode_step for callers that cannot provide or allocate staging memory at call time (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation): same arguments, same results bit for
+ * bit, but the step's GEMM staging (the split-K partial sums of the 16-bit path, the GEMM output of the float32
+ * path) lives in a 32 MiB array that is part of the library's device code instead of the bound workspace, and
+ * the call allocates nothing.  The step needs 4 * min(B, 128) * max(3 d_model, 2 d_ffn) * 4 bytes (VLA_BF16) or
+ * B * max(3 d_model, 2 d_ffn) * 4 bytes (VLA_F32); VLA_E_CAPACITY if that exceeds the array (e.g. the 7B shape
+ * fits up to B = 95).  Every context on a GPU shares that GPU's one array: calls that overlap in time on one GPU
+ * (two streams, two contexts, two threads) race; calls ordered on one stream do not.  Nothing in the array has
+ * to survive between calls and nothing in it is read before this call has written it. */
+int vla_decode_step_static(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits_out,
+                           void* hip_stream);
+
 /* Whole policy step, all on the device: prefill, then K = n_tokens action tokens chosen one by one
  * (K-1 decode steps), each with its log-probability under the distribution it was chosen from.
  *   temperature  0 => greedy (argmax of the logits, log-prob at temperature 1);

@@ -14,7 +14,7 @@ STATUS = {0: "VLA_OK", -1: "VLA_E_NULL", -2: "VLA_E_CONFIG", -3: "VLA_E_SHAPE", 
 VLA_E_STATE, VLA_E_DRAINING = -5, -8
 VLA_ACCEPTING, VLA_DRAINING, VLA_UPDATING = 0, 1, 2
 EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vla_bind_buffers",
-           "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_policy_step", "vla_select",
+           "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_decode_step_static", "vla_policy_step", "vla_select",
            "vla_load_value_head", "vla_policy_step_value",
            "vla_policy_step_parallel", "vla_score_tokens",
            "vla_prefill_slots", "vla_decode_slots", "vla_release_slots",
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
         L.vla_load_weights.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
         L.vla_prefill.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
         L.vla_decode_step.argtypes = [vp, i32, vp, vp, vp]
+        L.vla_decode_step_static.argtypes = [vp, i32, vp, vp, vp]
         L.vla_policy_step.argtypes = [vp, i32, vp, vp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         L.vla_load_value_head.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
         L.vla_policy_step_value.argtypes = [vp, i32, vp, vp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -245,6 +246,10 @@ def vla_prefill(ctx, B, patch_emb, cu_patch: np.ndarray, instr_ids, cu_instr: np
 
 def vla_decode_step(ctx, B, token_ids, logits_out, stream: int = 0) -> None:
     _check(ctx, lib().vla_decode_step(ctx, B, _ptr(token_ids), _ptr(logits_out), stream))
+
+
+def vla_decode_step_static(ctx, B, token_ids, logits_out, stream: int = 0) -> None:
+    _check(ctx, lib().vla_decode_step_static(ctx, B, _ptr(token_ids), _ptr(logits_out), stream))
 
 
 def vla_policy_step(ctx, B, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, temperature, gumbel,
@@ -432,11 +437,13 @@ class VlaPolicy:
     def release_slots(self, slot_ids):
         vla_release_slots(self.ctx, slot_ids)
 
-    def decode_step(self, token_ids, want_logits=True):
+    def decode_step(self, token_ids, want_logits=True, static=False, out=None):
+        """static=True: vla_decode_step_static (staging in the library's own device array, nothing allocated)."""
         torch = self.torch
         B = token_ids.shape[0]
-        out = torch.empty((B, self.shape.n_action_bins), dtype=torch.float32, device=self.device) if want_logits else None
-        vla_decode_step(self.ctx, B, token_ids, out, self._stream())
+        if out is None and want_logits:
+            out = torch.empty((B, self.shape.n_action_bins), dtype=torch.float32, device=self.device)
+        (vla_decode_step_static if static else vla_decode_step)(self.ctx, B, token_ids, out, self._stream())
         return out
 
     def policy_step_parallel(self, patch_emb, cu_patch, instr_ids, cu_instr, n_tokens, placeholder_id,

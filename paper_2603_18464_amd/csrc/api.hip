@@ -19,6 +19,12 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
+// Staging memory of vla_decode_step_static: one array per GPU, part of the loaded code object, so that entry
+// point needs no caller-provided or allocated staging.  Host code never uses the array's name as an address:
+// static_scratch() asks the runtime once per device for the device address and keeps it.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+
 struct LayerW {
   size_t g_attn, w_qkv, w_o, g_ffn, w_gu, w_down;   // byte offsets into the weight arena
 };
@@ -144,6 +150,28 @@ struct EventPair { hipEvent_t a, b; };
 
 }  // namespace
 
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of `scratch` (looked up on the first call per device, with that device current).
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
 struct vla_ctx {
   vla_config cfg;
   ArenaLayout al;
@@ -161,6 +189,7 @@ struct vla_ctx {
   int active_B = 0;                  // batch of the last prefill (0: none)
   int run_B = 0, run_max_len = 0;    // batch and longest prefix of the prefill being enqueued
   const int32_t* run_slots = nullptr; // device slot map of the call being enqueued (nullptr: sequence b is slot b)
+  float* part_override = nullptr;    // set for the duration of vla_decode_step_static: GEMM staging outside the workspace
   std::vector<int32_t> len;          // host copy of the sequence lengths
   std::string err;
   // pinned staging ring for the host offset arrays
@@ -234,7 +263,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
   T* q = at<T>(ctx->work, w.q);
   T* att = at<T>(ctx->work, w.att);
   T* act = at<T>(ctx->work, w.act);
-  float* scratch = at<float>(ctx->work, w.scratch);
+  float* gemm_out = ctx->part_override ? ctx->part_override : at<float>(ctx->work, w.scratch);
   const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
   const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
   const size_t kvl = kv_layer_stride(c);
@@ -263,8 +292,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       if constexpr (sizeof(T) == 2) {
         gemm_f16_qkv(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_qkv), rows, 3 * d, d}, rk, st);
       } else {
-        gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_qkv), scratch, rows, 3 * d, d, st);
-        rope_kv_f32(scratch, rows, rk, st);
+        gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_qkv), gemm_out, rows, 3 * d, d, st);
+        rope_kv_f32(gemm_out, rows, rk, st);
       }
     }
     {
@@ -296,8 +325,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       if constexpr (sizeof(T) == 2) {
         gemm_f16_resid(GemmF16{(const f16*)att, d, at<f16>(ctx->arena, lw.w_o), rows, d, d}, x, d, st);
       } else {
-        gemm_f32((const float*)att, d, at<float>(ctx->arena, lw.w_o), scratch, rows, d, d, st);
-        resid_add_f32(x, scratch, (size_t)rows * d, st);
+        gemm_f32((const float*)att, d, at<float>(ctx->arena, lw.w_o), gemm_out, rows, d, d, st);
+        resid_add_f32(x, gemm_out, (size_t)rows * d, st);
       }
     }
     {
@@ -309,8 +338,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       if constexpr (sizeof(T) == 2) {
         gemm_f16_swiglu(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, d}, (f16*)act, f, st);
       } else {
-        gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_gu), scratch, rows, 2 * f, d, st);
-        swiglu_f32(scratch, (float*)act, rows, f, st);
+        gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_gu), gemm_out, rows, 2 * f, d, st);
+        swiglu_f32(gemm_out, (float*)act, rows, f, st);
       }
     }
     {
@@ -318,8 +347,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       if constexpr (sizeof(T) == 2) {
         gemm_f16_resid(GemmF16{(const f16*)act, f, at<f16>(ctx->arena, lw.w_down), rows, d, f}, x, d, st);
       } else {
-        gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), scratch, rows, d, f, st);
-        resid_add_f32(x, scratch, (size_t)rows * d, st);
+        gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), gemm_out, rows, d, f, st);
+        resid_add_f32(x, gemm_out, (size_t)rows * d, st);
       }
     }
   }
@@ -337,7 +366,7 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
   f16* q = at<f16>(ctx->work, w.q);
   f16* att = at<f16>(ctx->work, w.att);
   f16* act = at<f16>(ctx->work, w.act);
-  float* part = at<float>(ctx->work, w.part);
+  float* part = ctx->part_override ? ctx->part_override : at<float>(ctx->work, w.part);
   const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
   const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
   const size_t kvl = kv_layer_stride(c);
@@ -1027,6 +1056,35 @@ int vla_decode_step(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* lo
   const int A = ctx->cfg.n_action_bins;
   rc = ctx->cfg.dtype == VLA_BF16 ? do_decode<bf16>(ctx, B, token_ids, logits_out, A, st)
                                   : do_decode<float>(ctx, B, token_ids, logits_out, A, st);
+  if (rc) return rc;
+  return leave_compute(ctx, st);
+}
+
+int vla_decode_step_static(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* logits_out, void* hip_stream) {
+  if (!ctx) return VLA_E_NULL;
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if ((rc = check_serving(ctx, false))) return rc;
+  if (!token_ids) return fail(ctx, VLA_E_NULL, "token_ids is NULL");
+  if ((rc = check_decode(ctx, B, 1))) return rc;
+  const vla_config& c = ctx->cfg;
+  // staging the step's GEMMs need: the split-K partial planes of the 16-bit path (rows of one chunk), or the
+  // plain GEMM output of the float32 path
+  const size_t widest = 3 * (size_t)c.d_model > 2 * (size_t)c.d_ffn ? 3 * (size_t)c.d_model : 2 * (size_t)c.d_ffn;
+  const size_t rows = c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * (B < kSkinnyMaxRows ? B : kSkinnyMaxRows) : (size_t)B;
+  const size_t need = rows * widest * sizeof(float);
+  if (need > kStaticScratchBytes)
+    return fail(ctx, VLA_E_CAPACITY, "vla_decode_step_static: batch %d of this model needs %zu bytes of staging, the static "
+                "array holds %zu (use vla_decode_step)", B, need, kStaticScratchBytes);
+  void* sp = nullptr;
+  HIP_TRY(ctx, static_scratch(&sp));
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = enter_compute(ctx, st))) return rc;
+  const int A = c.n_action_bins;
+  ctx->part_override = (float*)sp;       // every element read from it in this step is written earlier in this step
+  rc = c.dtype == VLA_BF16 ? do_decode<bf16>(ctx, B, token_ids, logits_out, A, st)
+                           : do_decode<float>(ctx, B, token_ids, logits_out, A, st);
+  ctx->part_override = nullptr;
   if (rc) return rc;
   return leave_compute(ctx, st);
 }
