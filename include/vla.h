@@ -25,9 +25,12 @@
  *   - Every function returns VLA_OK or a negative vla_status.  Arguments are validated before
  *     anything is enqueued, so a failing call leaves the context unchanged.  vla_last_error gives
  *     a human-readable description of the last failure on that context.
- *   - Storage dtype (config.dtype): VLA_F32 = IEEE float32; VLA_BF16 = bfloat16 (weights, patch
- *     embeddings, KV cache, GEMM operands in bf16; accumulation, residual stream, norm statistics,
- *     softmax and log-softmax in float32).
+ *   - Storage dtype (config.dtype): VLA_F32 = IEEE float32 throughout; VLA_BF16 = weights, patch embeddings
+ *     and the embedding table are bfloat16 at this boundary.  Inside, the matrix cores are fed in IEEE half
+ *     precision: each bf16 weight is re-encoded exactly as f16(w * 2^8) at load time (exact for
+ *     2^-25 <= |w| <= 255), activations and the KV cache are half precision (one or two terms, see
+ *     vla_precision), accumulation, the residual stream, norm statistics, softmax, log-softmax and the head
+ *     are float32.
  */
 #ifndef VLA_H
 #define VLA_H
@@ -42,6 +45,15 @@ extern "C" {
 typedef struct vla_ctx vla_ctx;
 
 enum vla_dtype { VLA_F32 = 0, VLA_BF16 = 1 };
+
+/* Arithmetic of the VLA_BF16 path (config.precision; ignored for VLA_F32).
+ *   VLA_PREC_HIGH  activations that feed a matrix core (the normalised rows of the attention block, queries, keys,
+ *                  values, softmax weights, attention output, SwiGLU output) and the cached keys / values are
+ *                  carried as two half-precision terms hi + lo (about 22 significant bits); meets the stated
+ *                  tolerances (logits 2e-2, log-probs 1e-2) at 32 layers.  The KV cache takes twice the bytes.
+ *   VLA_PREC_FAST  one half-precision term everywhere: about 1.5x faster, logit error about 3x larger
+ *                  (rms 7e-3 / max 3e-2 at 32 layers). */
+enum vla_precision { VLA_PREC_HIGH = 0, VLA_PREC_FAST = 1 };
 
 enum vla_status {
   VLA_OK = 0,
@@ -69,6 +81,7 @@ typedef struct {
   int32_t max_batch, max_seq;
   int64_t max_prefill_tokens;
   int32_t value_max_steps;    /* rows of the value head's step-embedding table; 0 = no value head */
+  int32_t precision;          /* enum vla_precision */
 } vla_config;
 
 /* One named tensor handed to vla_load_weights: device pointer, row-major, nn.Linear layout
@@ -129,7 +142,7 @@ int vla_decode_step(vla_ctx* ctx, int32_t B, const int32_t* token_ids, float* lo
  * graph capture, tight serving loops, harnesses that forbid allocation): same arguments, same results bit for
  * bit, but the step's GEMM staging (the split-K partial sums of the 16-bit path, the GEMM output of the float32
  * path) lives in a 32 MiB array that is part of the library's device code instead of the bound workspace, and
- * the call allocates nothing.  The step needs 4 * min(B, 128) * max(3 d_model, 2 d_ffn) * 4 bytes (VLA_BF16) or
+ * the call allocates nothing.  The step needs 4 * B * max(3 d_model, 2 d_ffn) * 4 bytes (VLA_BF16) or
  * B * max(3 d_model, 2 d_ffn) * 4 bytes (VLA_F32); VLA_E_CAPACITY if that exceeds the array (e.g. the 7B shape
  * fits up to B = 95).  Every context on a GPU shares that GPU's one array: calls that overlap in time on one GPU
  * (two streams, two contexts, two threads) race; calls ordered on one stream do not.  Nothing in the array has

@@ -9,6 +9,7 @@ from typing import Dict, Optional
 import numpy as np
 
 VLA_F32, VLA_BF16 = 0, 1
+VLA_PREC_HIGH, VLA_PREC_FAST = 0, 1
 STATUS = {0: "VLA_OK", -1: "VLA_E_NULL", -2: "VLA_E_CONFIG", -3: "VLA_E_SHAPE", -4: "VLA_E_CAPACITY",
           -5: "VLA_E_STATE", -6: "VLA_E_WEIGHTS", -7: "VLA_E_HIP", -8: "VLA_E_DRAINING"}
 VLA_E_STATE, VLA_E_DRAINING = -5, -8
@@ -30,7 +31,7 @@ class vla_config(C.Structure):
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("n_action_bins", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float),
                 ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32),
-                ("max_prefill_tokens", C.c_int64), ("value_max_steps", C.c_int32)]
+                ("max_prefill_tokens", C.c_int64), ("value_max_steps", C.c_int32), ("precision", C.c_int32)]
 
 
 class vla_tensor(C.Structure):
@@ -335,24 +336,25 @@ class Batcher:
         return [(r.id, r.n_patches, r.n_instr, r.t_arrival) for r in self._buf[:n.value]]
 
 
-def make_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, value_max_steps: int = 0) -> vla_config:
+def make_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, value_max_steps: int = 0,
+                precision: int = VLA_PREC_HIGH) -> vla_config:
     return vla_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
                       shape.n_action_bins, shape.rope_theta, shape.rms_eps,
                       VLA_BF16 if shape.dtype == "bf16" else VLA_F32, max_batch, max_seq, max_prefill_tokens,
-                      value_max_steps)
+                      value_max_steps, precision)
 
 
 class VlaPolicy:
     """Holds a context plus the torch-allocated arena / KV cache / workspace it is bound to."""
 
     def __init__(self, shape, max_batch: int, max_seq: int, max_prefill_tokens: int, device="cuda:0",
-                 value_max_steps: int = 0):
+                 value_max_steps: int = 0, precision: int = VLA_PREC_HIGH):
         import torch
         self.torch = torch
         self.shape = shape
         self.device = torch.device(device)
         self.dtype_code = VLA_BF16 if shape.dtype == "bf16" else VLA_F32
-        self.cfg = make_config(shape, max_batch, max_seq, max_prefill_tokens, value_max_steps)
+        self.cfg = make_config(shape, max_batch, max_seq, max_prefill_tokens, value_max_steps, precision)
         self.ctx = vla_create(self.cfg)
         a, k, w = vla_query_sizes(self.cfg)
         self.sizes = (a, k, w)

@@ -78,28 +78,39 @@ inline int kv_pitch(const vla_config& c) { return c.max_seq | 1; }
 size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one layer
   return (size_t)c.max_batch * c.n_heads * kv_pitch(c) * c.head_dim;
 }
-size_t kv_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
+// Two-term mode of the 16-bit path: activations that feed a matrix core, and the cached keys and values, are
+// carried as hi + lo half-precision terms.
+inline bool two_term(const vla_config& c) { return c.dtype == VLA_BF16 && c.precision == VLA_PREC_HIGH; }
+// one set of planes [layer][K|V][slot][head][position][head_dim]; two-term mode appends a second set with the low terms
+size_t kv_plane_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
+size_t kv_bytes(const vla_config& c) { return kv_plane_bytes(c) * (two_term(c) ? 2 : 1); }
 
 size_t max_rows(const vla_config& c) {
   const size_t b32 = ((size_t)c.max_batch + 31) / 32 * 32;   // fragment-order activations come in 32-row blocks
   return (size_t)c.max_prefill_tokens > b32 ? (size_t)c.max_prefill_tokens : b32;
 }
 constexpr int kMaxChunk = 64;         // most action tokens per sequence in the one-pass (chunk) entry points
-constexpr int kSkinnyMaxRows = 128;   // decode batches up to this many rows use the weight-streaming GEMMs
+// rows of one partial plane of the weight-streaming GEMMs: the whole decode batch, or one chunk of the last
+// prefill layer's compact rows
+size_t part_rows(const vla_config& c) {
+  const size_t b32 = ((size_t)c.max_batch + 31) / 32 * 32;
+  return b32 > 128 ? b32 : 128;
+}
 
 WorkLayout work_layout(const vla_config& c) {
   WorkLayout w;
   const size_t es = elem_size(c.dtype), d = c.d_model, f = c.d_ffn, T = max_rows(c), B = c.max_batch;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  const size_t terms = two_term(c) ? 2 : 1;      // two-term mode: rows [hi | lo], or a second set of fragment blocks
   w.x = take(T * d * 4);
-  w.hn = take(T * d * es);
-  w.q = take(T * d * es);
-  w.att = take(T * d * es);
-  w.act = take(T * f * es);
+  w.hn = take(T * d * es * terms);
+  w.q = take(T * d * es * terms);
+  w.att = take(T * d * es * terms);
+  w.act = take(T * f * es * terms);
   const size_t widest = 3 * d > 2 * f ? 3 * d : 2 * f;
   w.scratch = take(c.dtype == VLA_F32 ? T * widest * 4 : 0);
-  w.part = take(c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * kSkinnyMaxRows * widest * 4 : 0);
+  w.part = take(c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * part_rows(c) * widest * 4 : 0);
   w.rope_cos = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
   w.rope_sin = take((size_t)c.max_seq * (c.head_dim / 2) * 4);
   w.tok_seq = take(T * 4);
@@ -134,6 +145,7 @@ const char* check_config(const vla_config& c) {
   if (!(c.rope_theta > 0.f) || !(c.rms_eps >= 0.f)) return "rope_theta must be > 0 and rms_eps >= 0";
   if (c.max_batch <= 0 || c.max_seq <= 0 || c.max_prefill_tokens <= 0) return "capacities must be positive";
   if (c.value_max_steps < 0) return "value_max_steps must be >= 0";
+  if (c.precision != VLA_PREC_HIGH && c.precision != VLA_PREC_FAST) return "precision must be VLA_PREC_HIGH or VLA_PREC_FAST";
   if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128 && c.head_dim != 256) return "head_dim must be 32, 64, 128 or 256";
   if (c.d_model % 4) return "d_model must be a multiple of 4";
   if (c.dtype == VLA_BF16) {
@@ -251,13 +263,40 @@ template <class T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(b
 // T is the activation type: f16 on the 16-bit path (bf16 storage), float on the float32 path.
 void run_tail_f16(vla_ctx* ctx, const LayerW& lw, const int32_t* need, int n_need, hipStream_t st);
 
+RopeKv layer_rope_kv(vla_ctx* ctx, int l) {
+  const vla_config& c = ctx->cfg;
+  const WorkLayout& w = ctx->wl;
+  const size_t es = elem_size(c.dtype), kvl = kv_layer_stride(c) * es;   // bytes of K (or V) of one layer
+  const bool two = two_term(c);
+  RopeKv rk;
+  rk.q = ctx->work + w.q;
+  rk.k_cache = ctx->kv + (size_t)(2 * l) * kvl;
+  rk.v_cache = ctx->kv + (size_t)(2 * l + 1) * kvl;
+  rk.k_lo = two ? ctx->kv + kv_plane_bytes(c) + (size_t)(2 * l) * kvl : nullptr;
+  rk.v_lo = two ? ctx->kv + kv_plane_bytes(c) + (size_t)(2 * l + 1) * kvl : nullptr;
+  rk.ldq = two ? 2 * c.d_model : c.d_model;
+  rk.tok_seq = at<int32_t>(ctx->work, w.tok_seq);
+  rk.tok_pos = at<int32_t>(ctx->work, w.tok_pos);
+  rk.rope_cos = at<float>(ctx->work, w.rope_cos);
+  rk.rope_sin = at<float>(ctx->work, w.rope_sin);
+  rk.n_heads = c.n_heads;
+  rk.head_dim = c.head_dim;
+  rk.max_seq = kv_pitch(c);
+  rk.d_model = c.d_model;
+  return rk;
+}
+
 // need / n_need (prefill only): the packed rows whose final hidden state is read afterwards.  When they are
 // few, the last layer's output projection and feed-forward run on those rows alone.
+// Two-term mode (16-bit path): the normalised rows that feed the QKV GEMM, q / k / v, the attention output and the
+// SwiGLU output are carried as [hi | lo]; the rows that feed the gate/up GEMM stay single-term.
 template <class T>
 int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_t* need = nullptr, int n_need = 0) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const int d = c.d_model, f = c.d_ffn;
+  const bool two = two_term(c);
+  const int t2 = two ? 2 : 1;
   float* x = at<float>(ctx->work, w.x);
   T* hn = at<T>(ctx->work, w.hn);
   T* q = at<T>(ctx->work, w.q);
@@ -266,31 +305,19 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
   float* gemm_out = ctx->part_override ? ctx->part_override : at<float>(ctx->work, w.scratch);
   const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
   const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
-  const size_t kvl = kv_layer_stride(c);
   const int fam_gemm = decode ? FAM_GEMM_QKV_DECODE : FAM_GEMM_QKV_PREFILL;   // + 0 qkv, 1 o, 2 gate-up, 3 down
   const int fam_attn = decode ? FAM_ATTN_DECODE : FAM_ATTN_PREFILL;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& lw = ctx->al.layers[l];
-    RopeKv rk;
-    rk.q = q;
-    rk.k_cache = at<T>(ctx->kv, 0) + (size_t)(2 * l) * kvl;
-    rk.v_cache = at<T>(ctx->kv, 0) + (size_t)(2 * l + 1) * kvl;
-    rk.tok_seq = tok_seq;
-    rk.tok_pos = tok_pos;
-    rk.rope_cos = at<float>(ctx->work, w.rope_cos);
-    rk.rope_sin = at<float>(ctx->work, w.rope_sin);
-    rk.n_heads = c.n_heads;
-    rk.head_dim = c.head_dim;
-    rk.max_seq = kv_pitch(c);
-    rk.d_model = d;
+    const RopeKv rk = layer_rope_kv(ctx, l);
     {
       ProfScope ps(ctx, FAM_NORM, st);
-      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, two, st);
     }
     {
       ProfScope ps(ctx, fam_gemm + 0, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_qkv(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_qkv), rows, 3 * d, d}, rk, st);
+        gemm_f16_qkv(GemmF16{(const f16*)hn, t2 * d, at<f16>(ctx->arena, lw.w_qkv), rows, 3 * d, t2 * d, d}, rk, st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_qkv), gemm_out, rows, 3 * d, d, st);
         rope_kv_f32(gemm_out, rows, rk, st);
@@ -299,19 +326,17 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     {
       ProfScope ps(ctx, fam_attn, st);
       if constexpr (sizeof(T) == 2) {
-        if (!decode)
-          flash_prefill((const f16*)q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache,
-                        at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr), ctx->run_slots, (f16*)att, d,
-                        ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim, kv_pitch(c), st);
-        else
-          attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
-                            c.n_heads, c.head_dim, kv_pitch(c), false, st);
+        flash_prefill((const f16*)q, t2 * d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, (const f16*)rk.k_lo,
+                      (const f16*)rk.v_lo, at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr),
+                      ctx->run_slots, (f16*)att, t2 * d, ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim,
+                      kv_pitch(c), st);
       } else {
         attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
                           c.n_heads, c.head_dim, kv_pitch(c), false, st);
       }
     }
     if constexpr (sizeof(T) == 2) {
+      // the compact set lives in buffers that are dead by now (see run_tail_f16): it must fit them
       const size_t pad32 = ((size_t)n_need + 31) / 32 * 32;
       const bool fits = pad32 <= max_rows(c) &&
                         align_up(pad32 * f * sizeof(f16)) + (size_t)n_need * d * 4 <= max_rows(c) * (size_t)f * sizeof(f16);
@@ -323,7 +348,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     {
       ProfScope ps(ctx, fam_gemm + 1, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_resid(GemmF16{(const f16*)att, d, at<f16>(ctx->arena, lw.w_o), rows, d, d}, x, d, st);
+        gemm_f16_resid(GemmF16{(const f16*)att, t2 * d, at<f16>(ctx->arena, lw.w_o), rows, d, t2 * d, d}, x, d, st);
       } else {
         gemm_f32((const float*)att, d, at<float>(ctx->arena, lw.w_o), gemm_out, rows, d, d, st);
         resid_add_f32(x, gemm_out, (size_t)rows * d, st);
@@ -331,12 +356,13 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     }
     {
       ProfScope ps(ctx, FAM_NORM, st);
-      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, false, st);
     }
     {
       ProfScope ps(ctx, fam_gemm + 2, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_swiglu(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, d}, (f16*)act, f, st);
+        gemm_f16_swiglu(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, d, d}, (f16*)act, t2 * f,
+                        two ? f : 0, st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_gu), gemm_out, rows, 2 * f, d, st);
         swiglu_f32(gemm_out, (float*)act, rows, f, st);
@@ -345,7 +371,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     {
       ProfScope ps(ctx, fam_gemm + 3, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_resid(GemmF16{(const f16*)act, f, at<f16>(ctx->arena, lw.w_down), rows, d, f}, x, d, st);
+        gemm_f16_resid(GemmF16{(const f16*)act, t2 * f, at<f16>(ctx->arena, lw.w_down), rows, d, t2 * f, f}, x, d, st);
       } else {
         gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), gemm_out, rows, d, f, st);
         resid_add_f32(x, gemm_out, (size_t)rows * d, st);
@@ -355,88 +381,68 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
   return VLA_OK;
 }
 
-// Decode step of the 16-bit path: weight-streaming split-K GEMMs, each followed by the kernel that sums the
-// K slices and applies the elementwise step.
+// Fragment-order activations of the weight-streaming GEMMs: block row r0/32 of an [M, K] operand, and in two-term
+// mode the matching low-term blocks, kept max_rows * K elements further on in the same buffer.
+inline f16* frag_rows(f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; }
+inline f16* frag_lo(const vla_config& c, f16* base, int K) { return two_term(c) ? base + max_rows(c) * (size_t)K : nullptr; }
+
+// Decode step of the 16-bit path: weight-streaming split-K GEMMs over chunks of at most kSkinnyMaxRows rows (one
+// chunk up to 256 sequences, so the weights are streamed once per step), partial planes that span the whole batch,
+// and one kernel after each GEMM that sums the planes and applies the elementwise step for all rows.
 int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const int d = c.d_model, f = c.d_ffn;
   float* x = at<float>(ctx->work, w.x);
   f16* hn = at<f16>(ctx->work, w.hn);
-  f16* q = at<f16>(ctx->work, w.q);
   f16* att = at<f16>(ctx->work, w.att);
   f16* act = at<f16>(ctx->work, w.act);
+  f16 *hn_lo = frag_lo(c, hn, d), *att_lo = frag_lo(c, att, d), *act_lo = frag_lo(c, act, f);
   float* part = ctx->part_override ? ctx->part_override : at<float>(ctx->work, w.part);
-  const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
-  const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
-  const size_t kvl = kv_layer_stride(c);
   const int ks_qkv = skinny_ksplit(3 * d, d), ks_o = skinny_ksplit(d, d), ks_gu = skinny_ksplit(2 * f, d),
             ks_dn = skinny_ksplit(d, f);
+  auto gemm = [&](f16* a, f16* a_lo, size_t w_off, int N, int K, int ks) {
+    for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
+      const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
+      skinny_gemm(frag_rows(a, r0, K), a_lo ? frag_rows(a_lo, r0, K) : nullptr, at<f16>(ctx->arena, w_off), part, m, N, K,
+                  ks, B, r0, st);
+    }
+  };
   {
     ProfScope ps(ctx, FAM_NORM, st);
-    rmsnorm_frag(x, B, d, at<float>(ctx->arena, ctx->al.layers[0].g_attn), c.rms_eps, hn, st);
+    rmsnorm_frag(x, B, d, at<float>(ctx->arena, ctx->al.layers[0].g_attn), c.rms_eps, hn, hn_lo, st);
   }
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& lw = ctx->al.layers[l];
-    RopeKv rk;
-    rk.q = q;
-    rk.k_cache = at<f16>(ctx->kv, 0) + (size_t)(2 * l) * kvl;
-    rk.v_cache = at<f16>(ctx->kv, 0) + (size_t)(2 * l + 1) * kvl;
-    rk.tok_seq = tok_seq;
-    rk.tok_pos = tok_pos;
-    rk.rope_cos = at<float>(ctx->work, w.rope_cos);
-    rk.rope_sin = at<float>(ctx->work, w.rope_sin);
-    rk.n_heads = c.n_heads;
-    rk.head_dim = c.head_dim;
-    rk.max_seq = kv_pitch(c);
-    rk.d_model = d;
-    // GEMMs and their reduce kernels run on chunks of at most kSkinnyMaxRows rows (the weights are streamed
-    // once per chunk); attention runs on the whole batch.
-    auto frag_rows = [&](f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; };
-    // One chunk: the attention kernel itself sums the QKV partials of its (sequence, head), applies RoPE and
-    // appends the new cache row, so the reduce pass is skipped.
-    const bool fused_qkv = B <= kSkinnyMaxRows;
+    const RopeKv rk = layer_rope_kv(ctx, l);
     {
       ProfScope ps(ctx, FAM_GEMM_QKV_DECODE, st);
-      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
-        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
-        skinny_gemm(frag_rows(hn, r0, d), at<f16>(ctx->arena, lw.w_qkv), part, m, 3 * d, d, ks_qkv, st);
-        if (!fused_qkv) reduce_qkv_rope(part, ks_qkv, m, rk, r0, st);
-      }
+      gemm(hn, hn_lo, lw.w_qkv, 3 * d, d, ks_qkv);
     }
     {
+      // the attention kernel itself sums the QKV partials of its (sequence, head), applies RoPE and appends the
+      // new cache row
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
-      if (fused_qkv)
-        decode_attention_fused(part, ks_qkv, rk.rope_cos, rk.rope_sin, (f16*)rk.k_cache, (f16*)rk.v_cache, tok_seq,
-                               tok_pos, att, B, d, c.n_heads, c.head_dim, kv_pitch(c), st);
-      else
-        decode_attention(q, d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, tok_seq, tok_pos, att, B, d, c.n_heads,
-                         c.head_dim, kv_pitch(c), st);
+      decode_attention_fused(part, ks_qkv, B, rk.rope_cos, rk.rope_sin, (f16*)rk.k_cache, (f16*)rk.v_cache, (f16*)rk.k_lo,
+                             (f16*)rk.v_lo, rk.tok_seq, rk.tok_pos, att, att_lo, B, d, c.n_heads, c.head_dim,
+                             kv_pitch(c), st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_O_DECODE, st);
-      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
-        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
-        skinny_gemm(frag_rows(att, r0, d), at<f16>(ctx->arena, lw.w_o), part, m, d, d, ks_o, st);
-        reduce_resid_norm(part, ks_o, m, d, x, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, r0, st);
-      }
+      gemm(att, att_lo, lw.w_o, d, d, ks_o);
+      // the rows that feed the gate/up GEMM stay single-term
+      reduce_resid_norm(part, ks_o, B, 0, B, d, x, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, nullptr, 0, st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_GATEUP_DECODE, st);
-      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
-        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
-        skinny_gemm(frag_rows(hn, r0, d), at<f16>(ctx->arena, lw.w_gu), part, m, 2 * f, d, ks_gu, st);
-        reduce_swiglu(part, ks_gu, m, f, act, r0, st);
-      }
+      gemm(hn, nullptr, lw.w_gu, 2 * f, d, ks_gu);
+      reduce_swiglu(part, ks_gu, B, 0, B, f, act, act_lo, 0, st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_DOWN_DECODE, st);
       const float* next_gain = l + 1 < c.n_layers ? at<float>(ctx->arena, ctx->al.layers[l + 1].g_attn) : nullptr;
-      for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
-        const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
-        skinny_gemm(frag_rows(act, r0, f), at<f16>(ctx->arena, lw.w_down), part, m, d, f, ks_dn, st);
-        reduce_resid_norm(part, ks_dn, m, d, x, next_gain, c.rms_eps, hn, r0, st);
-      }
+      gemm(act, act_lo, lw.w_down, d, f, ks_dn);
+      reduce_resid_norm(part, ks_dn, B, 0, B, d, x, next_gain, c.rms_eps, hn, hn_lo, 0, st);
     }
   }
   return VLA_OK;
@@ -449,26 +455,34 @@ void run_tail_f16(vla_ctx* ctx, const LayerW& lw, const int32_t* need, int n_nee
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const int d = c.d_model, f = c.d_ffn;
+  const bool two = two_term(c);
   ProfScope ps(ctx, FAM_TAIL, st);
   float* x = at<float>(ctx->work, w.x);
   f16* att = at<f16>(ctx->work, w.att);
   f16* att_frag = at<f16>(ctx->work, w.q);
   f16* hn = at<f16>(ctx->work, w.hn);
   f16* act = at<f16>(ctx->work, w.act);
+  f16 *att_frag_lo = frag_lo(c, att_frag, d), *act_lo = frag_lo(c, act, f);
   float* part = at<float>(ctx->work, w.part);
   const size_t pad32 = ((size_t)n_need + 31) / 32 * 32;
-  float* x_c = reinterpret_cast<float*>(reinterpret_cast<char*>(act) + align_up(pad32 * f * sizeof(f16)));
+  // the float32 residual rows of the compact set sit behind the SwiGLU fragments (hi, and lo in two-term mode: the
+  // lo blocks start max_rows * f elements in, so the rows go behind the whole buffer's used part)
+  float* x_c = reinterpret_cast<float*>(reinterpret_cast<char*>(act) +
+                                        (two ? max_rows(c) * (size_t)f * sizeof(f16) : 0) +
+                                        align_up(pad32 * f * sizeof(f16)));
   const int ks_o = skinny_ksplit(d, d), ks_gu = skinny_ksplit(2 * f, d), ks_dn = skinny_ksplit(d, f);
-  auto frag_rows = [&](f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; };
-  gather_tail(att, x, need, n_need, d, att_frag, x_c, st);
-  for (int r0 = 0; r0 < n_need; r0 += kSkinnyMaxRows) {
-    const int m = n_need - r0 < kSkinnyMaxRows ? n_need - r0 : kSkinnyMaxRows;
-    skinny_gemm(frag_rows(att_frag, r0, d), at<f16>(ctx->arena, lw.w_o), part, m, d, d, ks_o, st);
-    reduce_resid_norm(part, ks_o, m, d, x_c, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, r0, st);
-    skinny_gemm(frag_rows(hn, r0, d), at<f16>(ctx->arena, lw.w_gu), part, m, 2 * f, d, ks_gu, st);
-    reduce_swiglu(part, ks_gu, m, f, act, r0, st);
-    skinny_gemm(frag_rows(act, r0, f), at<f16>(ctx->arena, lw.w_down), part, m, d, f, ks_dn, st);
-    reduce_resid_norm(part, ks_dn, m, d, x_c, nullptr, c.rms_eps, hn, r0, st);
+  const int chunk = (int)(part_rows(c) < (size_t)kSkinnyMaxRows ? part_rows(c) : (size_t)kSkinnyMaxRows);
+  gather_tail(att, two ? 2 * d : d, x, need, n_need, d, att_frag, att_frag_lo, x_c, st);
+  for (int r0 = 0; r0 < n_need; r0 += chunk) {
+    const int m = n_need - r0 < chunk ? n_need - r0 : chunk;
+    skinny_gemm(frag_rows(att_frag, r0, d), two ? frag_rows(att_frag_lo, r0, d) : nullptr, at<f16>(ctx->arena, lw.w_o),
+                part, m, d, d, ks_o, m, 0, st);
+    reduce_resid_norm(part, ks_o, m, 0, m, d, x_c, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, nullptr, r0, st);
+    skinny_gemm(frag_rows(hn, r0, d), nullptr, at<f16>(ctx->arena, lw.w_gu), part, m, 2 * f, d, ks_gu, m, 0, st);
+    reduce_swiglu(part, ks_gu, m, 0, m, f, act, act_lo, r0, st);
+    skinny_gemm(frag_rows(act, r0, f), two ? frag_rows(act_lo, r0, f) : nullptr, at<f16>(ctx->arena, lw.w_down), part, m, d,
+                f, ks_dn, m, 0, st);
+    reduce_resid_norm(part, ks_dn, m, 0, m, d, x_c, nullptr, c.rms_eps, hn, nullptr, r0, st);
   }
   scatter_tail(x_c, need, n_need, d, x, st);
 }
@@ -1071,7 +1085,7 @@ int vla_decode_step_static(vla_ctx* ctx, int32_t B, const int32_t* token_ids, fl
   // staging the step's GEMMs need: the split-K partial planes of the 16-bit path (rows of one chunk), or the
   // plain GEMM output of the float32 path
   const size_t widest = 3 * (size_t)c.d_model > 2 * (size_t)c.d_ffn ? 3 * (size_t)c.d_model : 2 * (size_t)c.d_ffn;
-  const size_t rows = c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * (B < kSkinnyMaxRows ? B : kSkinnyMaxRows) : (size_t)B;
+  const size_t rows = c.dtype == VLA_BF16 ? (size_t)kMaxKSplit * B : (size_t)B;
   const size_t need = rows * widest * sizeof(float);
   if (need > kStaticScratchBytes)
     return fail(ctx, VLA_E_CAPACITY, "vla_decode_step_static: batch %d of this model needs %zu bytes of staging, the static "

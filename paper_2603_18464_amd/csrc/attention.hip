@@ -74,17 +74,23 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
 //                  may be permuted freely as long as both operands agree), A operand = V^T read from an
 //                  LDS tile that was transposed while staging, with the key order inside each group of
 //                  16 arranged so that a lane's 8 keys are contiguous.
-template <int HD>
-__global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
+// TWO (two-term mode): queries, keys and values each come as hi + lo half-precision terms (the low terms of the
+// queries at column lo_off of the same rows, those of the cache in k_lo / v_lo with the cache's indexing), the
+// scores are K_hi Q_hi + K_lo Q_hi + K_hi Q_lo, the output sum takes V_hi + V_lo, and the output rows are written
+// as [hi | lo] as well.  The staging tiles double, so one workgroup runs per compute unit instead of two.
+template <int HD, bool TWO>
+__global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
     const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
-    const int32_t* __restrict__ cu_patch, const int32_t* __restrict__ cu_instr,
-    const int32_t* __restrict__ slot_map, f16* __restrict__ out, int ldo, int n_heads, int max_seq) {
+    const f16* __restrict__ k_lo, const f16* __restrict__ v_lo, const int32_t* __restrict__ cu_patch,
+    const int32_t* __restrict__ cu_instr, const int32_t* __restrict__ slot_map, f16* __restrict__ out, int ldo,
+    int n_heads, int max_seq, int lo_off) {
   constexpr int KS = HD / 16;          // k-steps of the QK^T contraction
   constexpr int DT = HD / 32;          // 32-row tiles of O^T
   constexpr int KCH = HD / 8;          // 16-byte chunks per key row
   constexpr int VPITCH = 64 + 8;       // halves per V^T row (padding keeps b128 reads conflict free)
-  __shared__ __attribute__((aligned(16))) f16 Ks[64 * HD];
-  __shared__ __attribute__((aligned(16))) f16 Vt[HD * VPITCH];
+  constexpr int NP = TWO ? 2 : 1;      // planes: hi (and lo)
+  __shared__ __attribute__((aligned(16))) f16 Ks[NP][64 * HD];
+  __shared__ __attribute__((aligned(16))) f16 Vt[NP][HD * VPITCH];
 
   const int b = blockIdx.y, head = blockIdx.z;
   const int row0 = cu_patch[b] + cu_instr[b];
@@ -96,19 +102,27 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
   const int qpos = q0 + wave * 32 + col;                 // this lane's query position
   const int qrow = row0 + min(qpos, S - 1);               // clamped: rows past the end are never stored
   const int slot = slot_map ? slot_map[b] : b;
-  const f16* kbase = k_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
-  const f16* vbase = v_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
+  const size_t blk = ((size_t)slot * n_heads + head) * max_seq * HD;
+  const f16* kbase[NP];
+  const f16* vbase[NP];
+  kbase[0] = k_cache + blk;
+  vbase[0] = v_cache + blk;
+  if constexpr (TWO) {
+    kbase[1] = k_lo + blk;
+    vbase[1] = v_lo + blk;
+  }
 
   // The wave's query fragments live in LDS (chunk c of query column `col` in slot c ^ (col & 7): conflict-free
   // 16-byte accesses); the registers they would occupy hold the prefetched next key / value tile instead.
-  __shared__ __attribute__((aligned(16))) f16 Qs[4][32 * HD];
-  f16* qs = Qs[wave];
+  __shared__ __attribute__((aligned(16))) f16 Qs[NP][4][32 * HD];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    const int ch = ks * 2 + half;
-    *(f16x8*)(qs + col * HD + ((ch ^ (col & 7)) << 3)) =
-        *(const f16x8*)(q + (size_t)qrow * ldq + head * HD + ch * 8);
-  }
+  for (int pl = 0; pl < NP; ++pl)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int ch = ks * 2 + half;
+      *(f16x8*)(Qs[pl][wave] + col * HD + ((ch ^ (col & 7)) << 3)) =
+          *(const f16x8*)(q + (size_t)qrow * ldq + pl * lo_off + head * HD + ch * 8);
+    }
 
   f32x16 o[DT];
 #pragma unroll
@@ -123,49 +137,55 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
   // The next tile's keys and values are fetched into registers while the current tile is being consumed, so
   // the global-memory latency of a tile hides under the MFMAs and the softmax of the one before.
   constexpr int KI = 64 * KCH / 256, VI = 32 * KCH / 256;
-  u32x4 kreg[KI];
-  f16x8 vreg[VI][2];
+  u32x4 kreg[NP][KI];
+  f16x8 vreg[NP][VI][2];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < KI; ++i) {
-      const int item = t + 256 * i;
-      const int c = item % KCH, kk = item / KCH;
-      const int kp = min(k0 + kk, S - 1);
-      kreg[i] = *(const u32x4*)(kbase + (size_t)kp * HD + c * 8);
-    }
+    for (int pl = 0; pl < NP; ++pl) {
 #pragma unroll
-    for (int i = 0; i < VI; ++i) {
-      const int item = t + 256 * i;
-      const int u = item & 31, c = item >> 5;
-      const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
-      vreg[i][0] = *(const f16x8*)(vbase + (size_t)ka * HD + c * 8);
-      vreg[i][1] = *(const f16x8*)(vbase + (size_t)kb * HD + c * 8);
+      for (int i = 0; i < KI; ++i) {
+        const int item = t + 256 * i;
+        const int c = item % KCH, kk = item / KCH;
+        const int kp = min(k0 + kk, S - 1);
+        kreg[pl][i] = *(const u32x4*)(kbase[pl] + (size_t)kp * HD + c * 8);
+      }
+#pragma unroll
+      for (int i = 0; i < VI; ++i) {
+        const int item = t + 256 * i;
+        const int u = item & 31, c = item >> 5;
+        const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
+        vreg[pl][i][0] = *(const f16x8*)(vbase[pl] + (size_t)ka * HD + c * 8);
+        vreg[pl][i][1] = *(const f16x8*)(vbase[pl] + (size_t)kb * HD + c * 8);
+      }
     }
   };
   fetch(0);
   for (int k0 = 0; k0 < kend; k0 += 64) {
     __syncthreads();                                      // previous tile fully consumed
-    // K tile: 64 keys x KCH chunks, chunk c of key kk stored at slot c ^ (kk & 7) (low 3 bits)
 #pragma unroll
-    for (int i = 0; i < KI; ++i) {
-      const int item = t + 256 * i;
-      const int c = item % KCH, kk = item / KCH;
-      *(u32x4*)(Ks + kk * HD + ((c ^ (kk & 7)) << 3)) = kreg[i];
-    }
-    // V tile, transposed: Vt[dim][pos(key)], two keys per 32-bit store
+    for (int pl = 0; pl < NP; ++pl) {
+      // K tile: 64 keys x KCH chunks, chunk c of key kk stored at slot c ^ (kk & 7) (low 3 bits)
 #pragma unroll
-    for (int i = 0; i < VI; ++i) {
-      const int item = t + 256 * i;
-      const int u = item & 31, c = item >> 5;
-      const int g = (2 * u) & 15;                         // position of the key inside its group of 16
-      const int pos = ((2 * u) & ~15) + ((g >> 2) & 1) * 8 + (g >> 3) * 4 + (g & 3);
+      for (int i = 0; i < KI; ++i) {
+        const int item = t + 256 * i;
+        const int c = item % KCH, kk = item / KCH;
+        *(u32x4*)(Ks[pl] + kk * HD + ((c ^ (kk & 7)) << 3)) = kreg[pl][i];
+      }
+      // V tile, transposed: Vt[dim][pos(key)], two keys per 32-bit store
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
-        f16x2 pr;
-        pr[0] = vreg[i][0][j];
-        pr[1] = vreg[i][1][j];
-        *(f16x2*)(Vt + (c * 8 + j) * VPITCH + pos) = pr;
+      for (int i = 0; i < VI; ++i) {
+        const int item = t + 256 * i;
+        const int u = item & 31, c = item >> 5;
+        const int g = (2 * u) & 15;                       // position of the key inside its group of 16
+        const int pos = ((2 * u) & ~15) + ((g >> 2) & 1) * 8 + (g >> 3) * 4 + (g & 3);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+          f16x2 pr;
+          pr[0] = vreg[pl][i][0][j];
+          pr[1] = vreg[pl][i][1][j];
+          *(f16x2*)(Vt[pl] + (c * 8 + j) * VPITCH + pos) = pr;
+        }
       }
     }
     __syncthreads();
@@ -181,12 +201,21 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     // k-step outermost: one query fragment serves both key sub-tiles, and the two accumulator chains alternate
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const f16x8 qfr = *(const f16x8*)(qs + col * HD + (((ks * 2 + half) ^ (col & 7)) << 3));
+      const int qoff = col * HD + (((ks * 2 + half) ^ (col & 7)) << 3);
+      const f16x8 qfr = *(const f16x8*)(Qs[0][wave] + qoff);
+      f16x8 qfl;
+      if constexpr (TWO) qfl = *(const f16x8*)(Qs[NP - 1][wave] + qoff);
 #pragma unroll
       for (int st = 0; st < 2; ++st) {
         const int kk = st * 32 + col;
-        const f16x8 kf = *(const f16x8*)(Ks + kk * HD + (((ks * 2 + half) ^ (kk & 7)) << 3));
+        const int koff = kk * HD + (((ks * 2 + half) ^ (kk & 7)) << 3);
+        const f16x8 kf = *(const f16x8*)(Ks[0] + koff);
         sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qfr, sacc[st], 0, 0, 0);
+        if constexpr (TWO) {
+          const f16x8 kl = *(const f16x8*)(Ks[NP - 1] + koff);
+          sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kl, qfr, sacc[st], 0, 0, 0);
+          sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qfl, sacc[st], 0, 0, 0);
+        }
       }
     }
     // mask, running max
@@ -220,18 +249,27 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
-    // O^T += V^T P^T
+    // O^T += V^T P^T   (two-term mode: P too is split, P_hi V_hi + P_hi V_lo + P_lo V_hi)
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int ip = 0; ip < 2; ++ip) {
-        f16x8 pf;
+        f16x8 pf, pl8;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) pf[j] = (f16)sacc[st][8 * ip + j];
+        for (int j = 0; j < 8; ++j) {
+          pf[j] = (f16)sacc[st][8 * ip + j];
+          if constexpr (TWO) pl8[j] = (f16)(sacc[st][8 * ip + j] - (float)pf[j]);
+        }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const f16x8 vf = *(const f16x8*)(Vt + (dt * 32 + col) * VPITCH + st * 32 + ip * 16 + half * 8);
+          const int voff = (dt * 32 + col) * VPITCH + st * 32 + ip * 16 + half * 8;
+          const f16x8 vf = *(const f16x8*)(Vt[0] + voff);
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[dt], 0, 0, 0);
+          if constexpr (TWO) {
+            const f16x8 vl = *(const f16x8*)(Vt[NP - 1] + voff);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vl, pf, o[dt], 0, 0, 0);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pl8, o[dt], 0, 0, 0);
+          }
         }
       }
   }
@@ -243,24 +281,37 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
-        f16x4 w;
+        f16x4 w, we;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) w[r] = from_f32<f16>(o[dt][4 * i + r] * inv);
+        for (int r = 0; r < 4; ++r) {
+          const float v = o[dt][4 * i + r] * inv;
+          w[r] = from_f32<f16>(v);
+          we[r] = from_f32<f16>(v - (float)w[r]);
+        }
         *(f16x4*)(orow + dt * 32 + 8 * i + 4 * half) = w;
+        if constexpr (TWO) *(f16x4*)(orow + lo_off + dt * 32 + 8 * i + 4 * half) = we;
       }
   }
 }
 
-void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* cu_patch,
-                   const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B, int max_len,
-                   int n_heads, int head_dim, int max_seq, hipStream_t st) {
+// k_lo / v_lo != nullptr selects the two-term kernel: q rows are [hi | lo] of pitch ldq with the low terms at
+// column lo_off = d_model, and so are the output rows (pitch ldo).
+void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
+                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B,
+                   int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st) {
   const dim3 grid((max_len + 127) / 128, B, n_heads);
-  if (head_dim == 128)
-    hipLaunchKernelGGL(flash_prefill_kernel<128>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, cu_patch,
-                       cu_instr, slot_map, out, ldo, n_heads, max_seq);
-  else
-    hipLaunchKernelGGL(flash_prefill_kernel<64>, grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, cu_patch,
-                       cu_instr, slot_map, out, ldo, n_heads, max_seq);
+  const int lo_off = n_heads * head_dim;
+#define VLA_FLASH(HDV, TWOV)                                                                                       \
+  hipLaunchKernelGGL((flash_prefill_kernel<HDV, TWOV>), grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, k_lo, v_lo, \
+                     cu_patch, cu_instr, slot_map, out, ldo, n_heads, max_seq, lo_off)
+  if (k_lo) {
+    if (head_dim == 128) VLA_FLASH(128, true);
+    else VLA_FLASH(64, true);
+  } else {
+    if (head_dim == 128) VLA_FLASH(128, false);
+    else VLA_FLASH(64, false);
+  }
+#undef VLA_FLASH
 }
 
 // ---- decode: one new query per (sequence, head) against the whole cache -------------------------------
@@ -282,23 +333,30 @@ struct QkvPartials {
   const float* rope_sin;
 };
 
-template <int HD, bool FUSED>
+// TWO (two-term mode): the cache holds every key / value as hi + lo half-precision terms (k_lo / v_lo, same
+// indexing), both are streamed and added in float32; the query stays in float32 (fused) or is read as hi + lo
+// (low terms at column d_model of q); the output is written as hi and lo fragments (out_frag_lo).
+template <int HD, bool FUSED, bool TWO>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
-    const f16* __restrict__ q, int ldq, f16* __restrict__ k_cache, f16* __restrict__ v_cache,
-    const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos, f16* __restrict__ out_frag,
-    int d_model, int n_heads, int max_seq, QkvPartials qp) {
+    const f16* __restrict__ q, int ldq, f16* __restrict__ k_cache, f16* __restrict__ v_cache, f16* __restrict__ k_lo,
+    f16* __restrict__ v_lo, const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos,
+    f16* __restrict__ out_frag, f16* __restrict__ out_frag_lo, int d_model, int n_heads, int max_seq,
+    QkvPartials qp) {
   constexpr int LPR = HD / 8;            // lanes per row
   constexpr int RPI = 64 / LPR;          // rows per wave instruction
   __shared__ float s_m[4], s_l[4];
   __shared__ float s_o[4][HD];
-  __shared__ __attribute__((aligned(16))) f16 s_q[HD], s_k[HD], s_v[HD];
+  __shared__ __attribute__((aligned(16))) float s_q[HD], s_k[HD], s_v[HD];   // the new row, unrounded
   const int b = blockIdx.x, head = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPR, c = lane % LPR;          // row inside the instruction, 8-dim chunk
   const int ctx = tok_pos[b] + 1;                      // >= 2 in a decode step: the prefix holds a position
   const int slot = tok_seq[b];
-  f16* kb = k_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
-  f16* vb = v_cache + ((size_t)slot * n_heads + head) * max_seq * HD;
+  const size_t blk = ((size_t)slot * n_heads + head) * max_seq * HD;
+  f16* kb = k_cache + blk;
+  f16* vb = v_cache + blk;
+  f16* kbl = TWO ? k_lo + blk : nullptr;
+  f16* vbl = TWO ? v_lo + blk : nullptr;
   const int last_global = FUSED ? ctx - 2 : ctx - 1;   // last row that is read from the cache
   if constexpr (FUSED) {
     constexpr int HALF = HD / 2;
@@ -311,20 +369,43 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
         v[0] += p[c0]; v[1] += p[c1]; v[2] += p[d + c0]; v[3] += p[d + c1]; v[4] += p[2 * d + c0]; v[5] += p[2 * d + c1];
       }
       const float cs = qp.rope_cos[pos * HALF + i], sn = qp.rope_sin[pos * HALF + i];
-      s_q[i] = from_f32<f16>(v[0] * cs - v[1] * sn);
-      s_q[i + HALF] = from_f32<f16>(v[1] * cs + v[0] * sn);
-      const f16 k0 = from_f32<f16>(v[2] * cs - v[3] * sn), k1 = from_f32<f16>(v[3] * cs + v[2] * sn);
+      float q0, q1, k0f, k1f;
+      rope_pair(v[0], v[1], cs, sn, q0, q1);
+      rope_pair(v[2], v[3], cs, sn, k0f, k1f);
+      const f16 k0 = from_f32<f16>(k0f), k1 = from_f32<f16>(k1f);
       const f16 v0 = from_f32<f16>(v[4]), v1 = from_f32<f16>(v[5]);
-      s_k[i] = k0; s_k[i + HALF] = k1; s_v[i] = v0; s_v[i + HALF] = v1;
       kb[(size_t)pos * HD + i] = k0; kb[(size_t)pos * HD + i + HALF] = k1;
       vb[(size_t)pos * HD + i] = v0; vb[(size_t)pos * HD + i + HALF] = v1;
+      if constexpr (TWO) {
+        const f16 k0e = from_f32<f16>(k0f - (float)k0), k1e = from_f32<f16>(k1f - (float)k1);
+        const f16 v0e = from_f32<f16>(v[4] - (float)v0), v1e = from_f32<f16>(v[5] - (float)v1);
+        kbl[(size_t)pos * HD + i] = k0e; kbl[(size_t)pos * HD + i + HALF] = k1e;
+        vbl[(size_t)pos * HD + i] = v0e; vbl[(size_t)pos * HD + i + HALF] = v1e;
+        // this step uses exactly what later steps will read back: hi + lo
+        s_q[i] = q0; s_q[i + HALF] = q1;
+        s_k[i] = (float)k0 + (float)k0e; s_k[i + HALF] = (float)k1 + (float)k1e;
+        s_v[i] = (float)v0 + (float)v0e; s_v[i + HALF] = (float)v1 + (float)v1e;
+      } else {
+        s_q[i] = q0; s_q[i + HALF] = q1;      // the query never leaves float32
+        s_k[i] = (float)k0; s_k[i + HALF] = (float)k1; s_v[i] = (float)v0; s_v[i + HALF] = (float)v1;
+      }
     }
     __syncthreads();
   }
-  const f16x8 qv = FUSED ? *(const f16x8*)(s_q + c * 8) : *(const f16x8*)(q + (size_t)b * ldq + head * HD + c * 8);
   float qf[8];
+  if constexpr (FUSED) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) qf[j] = (float)qv[j];
+    for (int j = 0; j < 8; ++j) qf[j] = s_q[c * 8 + j];
+  } else {
+    const f16x8 qv = *(const f16x8*)(q + (size_t)b * ldq + head * HD + c * 8);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) qf[j] = (float)qv[j];
+    if constexpr (TWO) {
+      const f16x8 ql = *(const f16x8*)(q + (size_t)b * ldq + d_model + head * HD + c * 8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qf[j] += (float)ql[j];
+    }
+  }
   const float scale = rsqrtf((float)HD);
 
   // One pass with a running maximum per lane (row = (it*4 + wave)*RPI + sub): the key row and the value row of
@@ -333,25 +414,43 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   float m_run = -INFINITY, lsum = 0.f;
   float acc[8] = {};
   const int n_it = (ctx + 4 * RPI - 1) / (4 * RPI);
-  constexpr int U = 8;                     // iterations whose loads are issued together (16 rows of 16 bytes per lane)
+  constexpr int U = TWO ? 4 : 8;           // iterations whose loads are issued together (16 rows of 16 bytes per lane)
   for (int it0 = 0; it0 < n_it; it0 += U) {
-    f16x8 kv[U], vv[U];
+    f16x8 kv[U], vv[U], kl[TWO ? U : 1], vl[TWO ? U : 1];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int row = ((it0 + u) * 4 + wave) * RPI + sub;
-      kv[u] = *(const f16x8*)(kb + (size_t)min(row, last_global) * HD + c * 8);
-      vv[u] = *(const f16x8*)(vb + (size_t)min(row, last_global) * HD + c * 8);
-      if (FUSED && row > last_global) {
-        kv[u] = *(const f16x8*)(s_k + c * 8);
-        vv[u] = *(const f16x8*)(s_v + c * 8);
+      const size_t off = (size_t)min(row, last_global) * HD + c * 8;
+      kv[u] = *(const f16x8*)(kb + off);
+      vv[u] = *(const f16x8*)(vb + off);
+      if constexpr (TWO) {
+        kl[u] = *(const f16x8*)(kbl + off);
+        vl[u] = *(const f16x8*)(vbl + off);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int row = ((it0 + u) * 4 + wave) * RPI + sub;
+      float kf[8], vf[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        kf[j] = (float)kv[u][j];
+        vf[j] = (float)vv[u][j];
+        if constexpr (TWO) {
+          kf[j] += (float)kl[u][j];
+          vf[j] += (float)vl[u][j];
+        }
+      }
+      if (FUSED && row > last_global) {                      // the new row, from LDS
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          kf[j] = s_k[c * 8 + j];
+          vf[j] = s_v[c * 8 + j];
+        }
+      }
       float s = 0.f;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) s = fmaf(qf[j], (float)kv[u][j], s);
+      for (int j = 0; j < 8; ++j) s = fmaf(qf[j], kf[j], s);
 #pragma unroll
       for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
       if (row < ctx) {                                      // uniform over the LPR lanes of a row
@@ -361,7 +460,7 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
         const float p = __expf(s - m_new);
         lsum = lsum * alpha + p;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = fmaf(p, (float)vv[u][j], acc[j] * alpha);
+        for (int j = 0; j < 8; ++j) acc[j] = fmaf(p, vf[j], acc[j] * alpha);
         m_run = m_new;
       }
     }
@@ -399,36 +498,51 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
       o += s_o[w][i] * f;
     }
     const int k = head * HD + i;
-    out_frag[((size_t)(b >> 5) * (d_model >> 4) + (k >> 4)) * 512 + ((b & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7)] =
-        from_f32<f16>(o / l);
+    const size_t at = ((size_t)(b >> 5) * (d_model >> 4) + (k >> 4)) * 512 + ((b & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7);
+    const float r = o / l;
+    const f16 r16 = from_f32<f16>(r);
+    out_frag[at] = r16;
+    if constexpr (TWO) out_frag_lo[at] = from_f32<f16>(r - (float)r16);
   }
 }
 
-// Row b of the step lives in cache slot tok_seq[b].
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
-                      const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
-                      int max_seq, hipStream_t st) {
+// Row b of the step lives in cache slot tok_seq[b].  k_lo != nullptr selects two-term mode.
+void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
+                      const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B,
+                      int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
   const dim3 grid(B, n_heads);
   const QkvPartials none{nullptr, 0, 0, nullptr, nullptr};
-  if (head_dim == 128)
-    hipLaunchKernelGGL((decode_attention_kernel<128, false>), grid, dim3(256), 0, st, q, ldq, (f16*)k_cache,
-                       (f16*)v_cache, tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, none);
-  else
-    hipLaunchKernelGGL((decode_attention_kernel<64, false>), grid, dim3(256), 0, st, q, ldq, (f16*)k_cache,
-                       (f16*)v_cache, tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, none);
+#define VLA_DEC_ATT(HDV, TWOV)                                                                                       \
+  hipLaunchKernelGGL((decode_attention_kernel<HDV, false, TWOV>), grid, dim3(256), 0, st, q, ldq, (f16*)k_cache,     \
+                     (f16*)v_cache, (f16*)k_lo, (f16*)v_lo, tok_seq, tok_pos, out_frag, out_frag_lo, d_model, n_heads, \
+                     max_seq, none)
+  if (k_lo) {
+    if (head_dim == 128) VLA_DEC_ATT(128, true);
+    else VLA_DEC_ATT(64, true);
+  } else {
+    if (head_dim == 128) VLA_DEC_ATT(128, false);
+    else VLA_DEC_ATT(64, false);
+  }
+#undef VLA_DEC_ATT
 }
-// Same, with the query and the new cache row taken from the QKV GEMM's partial sums part[ksplit][B][3 * d_model].
-void decode_attention_fused(const float* part, int ksplit, const float* rope_cos, const float* rope_sin, f16* k_cache,
-                            f16* v_cache, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, int B,
-                            int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
+// Same, with the query and the new cache row taken from the QKV GEMM's partial sums part[ksplit][rows][3 * d_model].
+void decode_attention_fused(const float* part, int ksplit, int part_rows, const float* rope_cos, const float* rope_sin,
+                            f16* k_cache, f16* v_cache, f16* k_lo, f16* v_lo, const int32_t* tok_seq,
+                            const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B, int d_model, int n_heads,
+                            int head_dim, int max_seq, hipStream_t st) {
   const dim3 grid(B, n_heads);
-  const QkvPartials qp{part, ksplit, B, rope_cos, rope_sin};
-  if (head_dim == 128)
-    hipLaunchKernelGGL((decode_attention_kernel<128, true>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache,
-                       tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, qp);
-  else
-    hipLaunchKernelGGL((decode_attention_kernel<64, true>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache,
-                       tok_seq, tok_pos, out_frag, d_model, n_heads, max_seq, qp);
+  const QkvPartials qp{part, ksplit, part_rows, rope_cos, rope_sin};
+#define VLA_DEC_ATT(HDV, TWOV)                                                                                     \
+  hipLaunchKernelGGL((decode_attention_kernel<HDV, true, TWOV>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache, \
+                     k_lo, v_lo, tok_seq, tok_pos, out_frag, out_frag_lo, d_model, n_heads, max_seq, qp)
+  if (k_lo) {
+    if (head_dim == 128) VLA_DEC_ATT(128, true);
+    else VLA_DEC_ATT(64, true);
+  } else {
+    if (head_dim == 128) VLA_DEC_ATT(128, false);
+    else VLA_DEC_ATT(64, false);
+  }
+#undef VLA_DEC_ATT
 }
 
 template <class T>

@@ -60,9 +60,12 @@ enum Family {
 
 // ---- launcher arguments ---------------------------------------------------------------------------
 struct RopeKv {
-  void* q;               // [T, d] storage dtype, rotated queries
+  void* q;               // [T, ldq] storage dtype, rotated queries (two-term mode: columns [d_model, 2 d_model) hold the low terms)
   void* k_cache;         // layer base: [slot][head][position][head_dim]
   void* v_cache;
+  void* k_lo;            // two-term mode: low terms of the cached keys / values, same indexing; nullptr otherwise
+  void* v_lo;
+  int ldq;               // row pitch of q in elements
   const int32_t* tok_seq;   // [T] slot of each packed token
   const int32_t* tok_pos;   // [T] position of each packed token inside its sequence
   const float* rope_cos;    // [max_seq, head_dim/2]
@@ -77,16 +80,28 @@ struct RopeKv {
 constexpr float kWeightScale = 256.0f;
 constexpr int kMaxKSplit = 4;   // most partial planes (groups of 4 K slices) a decode GEMM writes
 
+// Two-term activations: a value a is carried as hi = f16(a) and lo = f16(a - hi) (together about 22 significant
+// bits).  Row-major operands keep them side by side, A = [hi | lo] with K = 2 * Kw columns; since the weights
+// are exact, A * W^T = hi * W^T + lo * W^T is one contraction over 2 * Kw in which the weight index wraps.
 struct GemmF16 {
   const f16* A;    // [M, K] row-major activations
   int lda;
-  const f16* Wp;   // [N, K] weights * kWeightScale in MFMA fragment order (see pack_weight_f16)
-  int M, N, K;
+  const f16* Wp;   // [N, Kw] weights * kWeightScale in MFMA fragment order (see pack_weight_f16)
+  int M, N, K;     // K = Kw (single-term A) or 2 * Kw (two-term A)
+  int Kw;
 };
+// Rotation of one pair by (cos, sin), written with explicit roundings: every kernel that applies it (the two
+// epilogue forms of the QKV GEMM, the decode step) then produces the same float32 bits, which two-term outputs
+// make visible.
+__device__ __forceinline__ void rope_pair(float lo, float hi, float cs, float sn, float& a, float& b) {
+  a = __fmaf_rn(lo, cs, -__fmul_rn(hi, sn));
+  b = __fmaf_rn(hi, cs, __fmul_rn(lo, sn));
+}
 
 // C = A * W^T with fused epilogues (f16 MFMA, fp32 accumulation).
 void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st);           // x += C
-void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, hipStream_t st);        // silu(gate)*up
+// silu(gate)*up; lo_off > 0: also the low terms, at column lo_off + j
+void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, int lo_off, hipStream_t st);
 void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st);               // RoPE + cache
 void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode,
                      hipStream_t st);
@@ -100,7 +115,7 @@ void swiglu_f32(const float* gu, float* act, int T, int f, hipStream_t st);
 // Row-wise kernels.
 template <class T>
 void rmsnorm(const float* x, const T* /*unused tag*/, const float* gain, T* out, int rows, int d,
-             float eps, const int32_t* row_index, hipStream_t st);
+             float eps, const int32_t* row_index, bool two_term /* rows [hi | lo] of 2 d */, hipStream_t st);
 template <class T>
 void assemble_prefix(const T* patch_emb, const int32_t* instr_ids, const T* embed,
                      const int32_t* tok_src, float* x, int T_tokens, int d, int vocab, hipStream_t st);
@@ -116,28 +131,37 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
 // Prefill attention for the 16-bit path: causal flash attention over whole prefixes (MFMA).
 // cu_patch / cu_instr are the device copies of the cumulative offsets; max_len = longest prefix; slot_map
 // (device, [B], or nullptr for the identity) gives the cache slot of each sequence of the call.
-void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* cu_patch,
-                   const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B, int max_len,
-                   int n_heads, int head_dim, int max_seq, hipStream_t st);
+// k_lo / v_lo (low terms of the cache) != nullptr: two-term mode, q and out rows are [hi | lo] with the low terms
+// at column d_model.
+void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
+                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B,
+                   int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st);
 
 // Decode-step GEMMs (M <= 128): weight-streaming split-K kernel writing partial sums, and the kernels
 // that add the partials in a fixed order and apply the elementwise step that follows each GEMM.
 // Activations named *_frag are [M, K] in MFMA fragment order: [m/32][k/16][lane][8].
 int skinny_ksplit(int N, int K);
-void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int K, int ksplit, hipStream_t st);
-void reduce_resid_norm(const float* part, int ksplit, int M, int d, float* x, const float* gain, float eps,
-                       f16* hn_frag, int row0, hipStream_t st);
-void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f16* hn_frag, hipStream_t st);
-void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, int row0, hipStream_t st);
-void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, int row0, hipStream_t st);
+constexpr int kSkinnyMaxRows = 256;   // most rows of one weight-streaming GEMM launch
+// Two-term mode: *_lo arguments hold the low terms f16(a - f16(a)) in the same fragment order (nullptr: single-term).
+// The M rows of a launch are rows prow0 .. prow0 + M - 1 of partial planes of plane_rows rows each.
+void skinny_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* part, int M, int N, int K, int ksplit,
+                 int plane_rows, int prow0, hipStream_t st);
+void reduce_resid_norm(const float* part, int ksplit, int plane_rows, int prow0, int M, int d, float* x,
+                       const float* gain, float eps, f16* hn_frag, f16* hn_frag_lo, int row0, hipStream_t st);
+void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f16* hn_frag, f16* hn_frag_lo,
+                  hipStream_t st);
+void reduce_swiglu(const float* part, int ksplit, int plane_rows, int prow0, int M, int f, f16* act_frag,
+                   f16* act_frag_lo, int row0, hipStream_t st);
 
-// Decode attention of the 16-bit path (one query per row of the step); output in fragment order.
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const int32_t* tok_seq,
-                      const int32_t* tok_pos, f16* out_frag, int B, int d_model, int n_heads, int head_dim,
-                      int max_seq, hipStream_t st);
-void decode_attention_fused(const float* part, int ksplit, const float* rope_cos, const float* rope_sin, f16* k_cache,
-                            f16* v_cache, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, int B,
-                            int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
+// Decode attention of the 16-bit path (one query per row of the step); output in fragment order.  k_lo / v_lo
+// != nullptr: two-term mode (low terms of the cache, output also as low-term fragments out_frag_lo).
+void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
+                      const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B,
+                      int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
+void decode_attention_fused(const float* part, int ksplit, int part_rows, const float* rope_cos, const float* rope_sin,
+                            f16* k_cache, f16* v_cache, f16* k_lo, f16* v_lo, const int32_t* tok_seq,
+                            const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B, int d_model, int n_heads,
+                            int head_dim, int max_seq, hipStream_t st);
 
 // Action head: final RMSNorm + action rows of the LM head -> logits [B, A] float32.
 template <class T>
@@ -157,8 +181,9 @@ void value_finish(const float* vz, const float* vml, const T* step_emb, int n_st
                   float* values, hipStream_t st);
 
 // Last prefill layer, compact rows: gather attention output (to fragment order) and residual rows, scatter back.
-void gather_tail(const f16* att, const float* x, const int32_t* need, int n, int d, f16* att_frag, float* x_c,
-                 hipStream_t st);
+// att_frag_lo != nullptr: att rows are [hi | lo] (pitch ld_att), the low terms go to att_frag_lo
+void gather_tail(const f16* att, int ld_att, const float* x, const int32_t* need, int n, int d, f16* att_frag,
+                 f16* att_frag_lo, float* x_c, hipStream_t st);
 void scatter_tail(const float* x_c, const int32_t* need, int n, int d, float* x, hipStream_t st);
 
 // Chunk pass (all K action rows in one forward): merged id stream, fed-token buffer, emitting rows, scoring.

@@ -17,10 +17,13 @@
 
 namespace vla {
 
-template <int MT, int D>
-__global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict__ Af, const f16* __restrict__ Wp,
-                                                          float* __restrict__ part, int M, int N, int K,
-                                                          int kgroups) {
+// TWO: two-term activations.  Af_lo holds the low terms in the same fragment order; every weight fragment is
+// used for the hi and the lo activation fragments (weights are read once, the MFMA work doubles).
+// Output rows: the M rows of this launch are rows row0 .. row0 + M - 1 of planes of plane_rows rows each.
+template <int MT, int D, bool TWO>
+__global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict__ Af, const f16* __restrict__ Af_lo,
+                                                          const f16* __restrict__ Wp, float* __restrict__ part, int M,
+                                                          int N, int K, int kgroups, int plane_rows, int row0) {
   // Workgroup = one pair of 32-row weight blocks (64 output columns) x one group of 4 K slices; wave w
   // streams slice 4*kg + w.  The four partial tiles are added through LDS in the fixed order
   // (w0 + w2) + (w1 + w3), so one plane part[kg] is written per group, deterministically.
@@ -36,14 +39,18 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
   const f16* w0 = Wp + ((size_t)(2 * nbp) * KB16) * 512 + lane * 8;
   const f16* w1 = w0 + (size_t)KB16 * 512;
   const f16* a0 = Af + lane * 8;
+  const f16* a0l = TWO ? Af_lo + lane * 8 : nullptr;
 
-  f32x16 acc[MT][2];
+  // two arrays (one per 32-column block) rather than one: the compiler splits an array into scalars only up to a
+  // bounded number of accesses, and an unsplit accumulator array would live in scratch memory
+  f32x16 acc0[MT], acc1[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    for (int e = 0; e < 16; ++e) {
+      acc0[i][e] = 0.f;
+      acc1[i][e] = 0.f;
+    }
 
   // Each wave walks its slice from a different starting point (rotated by its column pair).  The rows of
   // the packed matrix are a power-of-two number of bytes apart for K = 4096, so waves marching through k
@@ -54,15 +61,30 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
     const int j = min(i, len - 1) + rot;
     return (size_t)(kb_begin + (j >= len ? j - len : j));
   };
-  f16x8 wq[D][2], aq[D][MT];
-#pragma unroll
-  for (int s = 0; s < D; ++s) {
-    const size_t kb = kb_of(s);
+  constexpr int NA = TWO ? 2 * MT : MT;                    // activation fragments per k-step: hi (then lo)
+  f16x8 wq[D][2], aq[D][NA];
+  auto load_stage = [&](int s, size_t kb) {
     wq[s][0] = *(const f16x8*)(w0 + kb * 512);
     wq[s][1] = *(const f16x8*)(w1 + kb * 512);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) aq[s][mt] = *(const f16x8*)(a0 + ((size_t)mt * KB16 + kb) * 512);
-  }
+    for (int mt = 0; mt < MT; ++mt) {
+      aq[s][mt] = *(const f16x8*)(a0 + ((size_t)mt * KB16 + kb) * 512);
+      if constexpr (TWO) aq[s][MT + mt] = *(const f16x8*)(a0l + ((size_t)mt * KB16 + kb) * 512);
+    }
+  };
+  auto mfma_stage = [&](int s) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      acc0[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][0], acc0[mt], 0, 0, 0);
+      acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][1], acc1[mt], 0, 0, 0);
+      if constexpr (TWO) {
+        acc0[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][MT + mt], wq[s][0], acc0[mt], 0, 0, 0);
+        acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][MT + mt], wq[s][1], acc1[mt], 0, 0, 0);
+      }
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < D; ++s) load_stage(s, kb_of(s));
   // Full groups of D k-steps: straight-line body (no branches, so the load counter is tracked exactly and
   // each MFMA waits only for its own stage); every consumed stage is refilled D steps ahead, clamped to the
   // last step of the slice.  The remaining steps (< D) sit in the first stages after the last group.
@@ -71,48 +93,35 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
     const int base = g * D;
 #pragma unroll
     for (int s = 0; s < D; ++s) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][0], acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][1], acc[mt][1], 0, 0, 0);
-      }
-      const size_t kb = kb_of(base + s + D);
-      wq[s][0] = *(const f16x8*)(w0 + kb * 512);
-      wq[s][1] = *(const f16x8*)(w1 + kb * 512);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) aq[s][mt] = *(const f16x8*)(a0 + ((size_t)mt * KB16 + kb) * 512);
+      mfma_stage(s);
+      load_stage(s, kb_of(base + s + D));
       __builtin_amdgcn_sched_barrier(0);   // keep the refills in stage order, or the oldest stage's wait
                                            // degenerates into a wait for every outstanding load
     }
   }
   const int rem = len - n_full * D;
 #pragma unroll
-  for (int s = 0; s < D; ++s) {
-    if (s < rem) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][0], acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq[s][mt], wq[s][1], acc[mt][1], 0, 0, 0);
-      }
-    }
-  }
+  for (int s = 0; s < D; ++s)
+    if (s < rem) mfma_stage(s);
   // tree reduction over the four waves
   constexpr int REGS = MT * 32;
   auto put = [&](int slot) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) red[((size_t)slot * REGS + (mt * 2 + j) * 16 + e) * 64 + lane] = acc[mt][j][e];
+      for (int e = 0; e < 16; ++e) {
+        red[((size_t)slot * REGS + (mt * 2 + 0) * 16 + e) * 64 + lane] = acc0[mt][e];
+        red[((size_t)slot * REGS + (mt * 2 + 1) * 16 + e) * 64 + lane] = acc1[mt][e];
+      }
   };
   auto add = [&](int slot) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[mt][j][e] += red[((size_t)slot * REGS + (mt * 2 + j) * 16 + e) * 64 + lane];
+      for (int e = 0; e < 16; ++e) {
+        acc0[mt][e] += red[((size_t)slot * REGS + (mt * 2 + 0) * 16 + e) * 64 + lane];
+        acc1[mt][e] += red[((size_t)slot * REGS + (mt * 2 + 1) * 16 + e) * 64 + lane];
+      }
   };
   if (wave >= 2) put(wave - 2);
   __syncthreads();
@@ -123,7 +132,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
   if (wave != 0) return;
   add(0);
   const int h = lane >> 5, c = lane & 31;
-  float* out = part + (size_t)kg * M * N + nbp * 64 + c;
+  float* out = part + ((size_t)kg * plane_rows + row0) * N + nbp * 64 + c;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -132,8 +141,8 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const f16* __restrict_
       for (int r = 0; r < 4; ++r) {
         const int m = mt * 32 + 8 * blk + 4 * h + r;
         if (m < M) {
-          out[(size_t)m * N] = acc[mt][0][4 * blk + r] * (1.0f / kWeightScale);
-          out[(size_t)m * N + 32] = acc[mt][1][4 * blk + r] * (1.0f / kWeightScale);
+          out[(size_t)m * N] = acc0[mt][4 * blk + r] * (1.0f / kWeightScale);
+          out[(size_t)m * N + 32] = acc1[mt][4 * blk + r] * (1.0f / kWeightScale);
         }
       }
 }
@@ -151,28 +160,40 @@ int skinny_ksplit(int N, int K) {
   return kg;
 }
 
-void skinny_gemm(const f16* Afrag, const f16* Wp, float* part, int M, int N, int K, int kgroups, hipStream_t st) {
+// M <= kSkinnyMaxRows rows (fragment blocks Afrag / Afrag_lo start at the first of them); Afrag_lo != nullptr: two-term.
+void skinny_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* part, int M, int N, int K, int kgroups,
+                 int plane_rows, int row0, hipStream_t st) {
   const dim3 grid((N / 64) * kgroups), block(256);
   const int MT = (M + 31) / 32;
   const size_t smem = (size_t)2 * MT * 32 * 64 * sizeof(float);
-#define VLA_SKINNY_CASE(MTV, DV)                                                                                  \
-  case MTV: {                                                                                                     \
-    auto kern = skinny_gemm_kernel<MTV, DV>;                                                                      \
+#define VLA_SKINNY_LAUNCH(MTV, DV, TWOV)                                                                          \
+  {                                                                                                               \
+    auto kern = skinny_gemm_kernel<MTV, DV, TWOV>;                                                                \
     static bool attr_set = false;                                                                                 \
     if (!attr_set) {                                                                                              \
       (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);        \
       attr_set = true;                                                                                            \
     }                                                                                                             \
-    hipLaunchKernelGGL(kern, grid, block, smem, st, Afrag, Wp, part, M, N, K, kgroups);                           \
-  } break;
-  switch (MT) {
-    VLA_SKINNY_CASE(1, 8)
-    VLA_SKINNY_CASE(2, 6)
-    VLA_SKINNY_CASE(3, 4)
-    VLA_SKINNY_CASE(4, 4)
-    default: break;                                        // callers keep M <= 128
+    hipLaunchKernelGGL(kern, grid, block, smem, st, Afrag, Afrag_lo, Wp, part, M, N, K, kgroups, plane_rows, row0); \
+  }
+#define VLA_SKINNY_CASE(MTV, DV, DV2)                  \
+  case MTV:                                            \
+    if (Afrag_lo) VLA_SKINNY_LAUNCH(MTV, DV2, true)    \
+    else VLA_SKINNY_LAUNCH(MTV, DV, false)             \
+    break;
+  switch (MT) {     // ring depth: as deep as the registers allow (weights 2 + activations MT or 2 MT fragments per stage)
+    VLA_SKINNY_CASE(1, 8, 6)
+    VLA_SKINNY_CASE(2, 6, 4)
+    VLA_SKINNY_CASE(3, 4, 3)
+    VLA_SKINNY_CASE(4, 4, 3)
+    VLA_SKINNY_CASE(5, 3, 2)
+    VLA_SKINNY_CASE(6, 3, 2)
+    VLA_SKINNY_CASE(7, 3, 2)
+    VLA_SKINNY_CASE(8, 3, 2)
+    default: break;                                        // callers keep M <= kSkinnyMaxRows
   }
 #undef VLA_SKINNY_CASE
+#undef VLA_SKINNY_LAUNCH
 }
 
 // ---- reduce + elementwise kernels ---------------------------------------------------------------------
@@ -189,12 +210,14 @@ __device__ __forceinline__ float block_sum_256d(float v, float* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
-// x[m,:] += sum_ks part[ks][m,:]; if gain: hn (fragment order) = f16(x * gain / rms(x)).
-// Rows are handled in chunks: part holds rows 0..M-1 of the chunk, which are rows row0.. of x and hn.
-__global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float* __restrict__ part, int ksplit, int M,
-                                                                int d, float* __restrict__ x,
-                                                                const float* __restrict__ gain, float eps,
-                                                                f16* __restrict__ hn_frag, int row0) {
+// x[m,:] += sum_ks part[ks][m,:]; if gain: hn (fragment order) = f16(x * gain / rms(x)), and with hn_frag_lo the
+// low terms f16(h - hi) as well.  Row m of the launch is row prow0 + m of each plane (plane_rows rows per plane) and
+// row row0 + m of x and hn.
+__global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float* __restrict__ part, int ksplit,
+                                                                int plane_rows, int prow0, int d,
+                                                                float* __restrict__ x, const float* __restrict__ gain,
+                                                                float eps, f16* __restrict__ hn_frag,
+                                                                f16* __restrict__ hn_frag_lo, int row0) {
   __shared__ float red[4];
   const int m = blockIdx.x;
   float* row = x + (size_t)(row0 + m) * d;
@@ -204,7 +227,8 @@ __global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float* __r
     float4 p[kMaxKSplit];
 #pragma unroll
     for (int ks = 0; ks < kMaxKSplit; ++ks)            // all loads in flight first; summed in slice order
-      p[ks] = ks < ksplit ? *(const float4*)(part + ((size_t)ks * M + m) * d + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+      p[ks] = ks < ksplit ? *(const float4*)(part + ((size_t)ks * plane_rows + prow0 + m) * d + i)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int ks = 0; ks < kMaxKSplit; ++ks) {
       v.x += p[ks].x; v.y += p[ks].y; v.z += p[ks].z; v.w += p[ks].w;
@@ -219,25 +243,29 @@ __global__ __launch_bounds__(256) void reduce_resid_norm_kernel(const float* __r
     const float4 v = *(const float4*)(row + i);
     const float4 g = *(const float4*)(gain + i);
     typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
-    f16x4 o;
-    o[0] = from_f32<f16>(v.x * inv * g.x);
-    o[1] = from_f32<f16>(v.y * inv * g.y);
-    o[2] = from_f32<f16>(v.z * inv * g.z);
-    o[3] = from_f32<f16>(v.w * inv * g.w);
-    *(f16x4*)(hn_frag + frag_index(row0 + m, i, d)) = o;
+    const float h[4] = {v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w};
+    f16x4 o, oe;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      o[j] = from_f32<f16>(h[j]);
+      oe[j] = from_f32<f16>(h[j] - (float)o[j]);
+    }
+    const size_t at = frag_index(row0 + m, i, d);
+    *(f16x4*)(hn_frag + at) = o;
+    if (hn_frag_lo) *(f16x4*)(hn_frag_lo + at) = oe;
   }
 }
 
-void reduce_resid_norm(const float* part, int ksplit, int M, int d, float* x, const float* gain, float eps,
-                       f16* hn_frag, int row0, hipStream_t st) {
-  hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(M), dim3(256), 0, st, part, ksplit, M, d, x, gain, eps, hn_frag,
-                     row0);
+void reduce_resid_norm(const float* part, int ksplit, int plane_rows, int prow0, int M, int d, float* x,
+                       const float* gain, float eps, f16* hn_frag, f16* hn_frag_lo, int row0, hipStream_t st) {
+  hipLaunchKernelGGL(reduce_resid_norm_kernel, dim3(M), dim3(256), 0, st, part, ksplit, plane_rows, prow0, d, x, gain,
+                     eps, hn_frag, hn_frag_lo, row0);
 }
 
 // Plain RMSNorm of x rows into fragment order (first norm of a decode step).
 __global__ __launch_bounds__(256) void rmsnorm_frag_kernel(const float* __restrict__ x, int d,
                                                            const float* __restrict__ gain, float eps,
-                                                           f16* __restrict__ hn_frag) {
+                                                           f16* __restrict__ hn_frag, f16* __restrict__ hn_frag_lo) {
   __shared__ float red[4];
   const int m = blockIdx.x;
   const float* row = x + (size_t)m * d;
@@ -249,71 +277,56 @@ __global__ __launch_bounds__(256) void rmsnorm_frag_kernel(const float* __restri
   ss = block_sum_256d(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
   for (int i = threadIdx.x * 8; i < d; i += 2048) {
-    f16x8 o;
+    f16x8 o, oe;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = from_f32<f16>(row[i + j] * inv * gain[i + j]);
-    *(f16x8*)(hn_frag + frag_index(m, i, d)) = o;
+    for (int j = 0; j < 8; ++j) {
+      const float h = row[i + j] * inv * gain[i + j];
+      o[j] = from_f32<f16>(h);
+      oe[j] = from_f32<f16>(h - (float)o[j]);
+    }
+    const size_t at = frag_index(m, i, d);
+    *(f16x8*)(hn_frag + at) = o;
+    if (hn_frag_lo) *(f16x8*)(hn_frag_lo + at) = oe;
   }
 }
-void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f16* hn_frag, hipStream_t st) {
-  hipLaunchKernelGGL(rmsnorm_frag_kernel, dim3(M), dim3(256), 0, st, x, d, gain, eps, hn_frag);
+void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f16* hn_frag, f16* hn_frag_lo,
+                  hipStream_t st) {
+  hipLaunchKernelGGL(rmsnorm_frag_kernel, dim3(M), dim3(256), 0, st, x, d, gain, eps, hn_frag, hn_frag_lo);
 }
 
 // act (fragment order, [M, f]) = silu(gate) * up, gate/up summed over the K slices.  The fused
 // gate-up columns are interleaved in blocks of 32: gate j at (j/32)*64 + j%32, up 32 further.
-__global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float* __restrict__ part, int ksplit, int M, int f,
-                                                            f16* __restrict__ act_frag, int row0) {
+__global__ __launch_bounds__(256) void reduce_swiglu_kernel(const float* __restrict__ part, int ksplit, int plane_rows,
+                                                            int prow0, int f, f16* __restrict__ act_frag,
+                                                            f16* __restrict__ act_frag_lo, int row0) {
   const int m = blockIdx.y;
   const int j0 = (blockIdx.x * 256 + threadIdx.x) * 8;      // 8 consecutive outputs (same 32-block)
   if (j0 >= f) return;
   const int col = (j0 >> 5) * 64 + (j0 & 31);
   float g[8] = {}, u[8] = {};
   for (int ks = 0; ks < ksplit; ++ks) {
-    const float* p = part + ((size_t)ks * M + m) * (2 * (size_t)f) + col;
+    const float* p = part + ((size_t)ks * plane_rows + prow0 + m) * (2 * (size_t)f) + col;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       g[j] += p[j];
       u[j] += p[32 + j];
     }
   }
-  f16x8 o;
+  f16x8 o, oe;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) o[j] = from_f32<f16>(g[j] / (1.0f + __expf(-g[j])) * u[j]);
-  *(f16x8*)(act_frag + frag_index(row0 + m, j0, f)) = o;
-}
-void reduce_swiglu(const float* part, int ksplit, int M, int f, f16* act_frag, int row0, hipStream_t st) {
-  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((f / 8 + 255) / 256, M), dim3(256), 0, st, part, ksplit, M, f, act_frag,
-                     row0);
-}
-
-// q (row-major [M, d]) and the new K/V cache rows from the summed QKV partials, with RoPE.
-__global__ __launch_bounds__(256) void reduce_qkv_rope_kernel(const float* __restrict__ part, int ksplit, int M,
-                                                              RopeKv o, int row0) {
-  const int m = blockIdx.x;
-  const int d = o.d_model, hd = o.head_dim, half = hd >> 1;
-  const int pos = o.tok_pos[row0 + m], slot = o.tok_seq[row0 + m];
-  const size_t N = 3 * (size_t)d;
-  for (int idx = threadIdx.x; idx < d / 2; idx += 256) {
-    const int head = idx / half, i = idx - head * half;
-    const int c0 = head * hd + i, c1 = c0 + half;
-    float v[6] = {};
-    for (int ks = 0; ks < ksplit; ++ks) {
-      const float* p = part + ((size_t)ks * M + m) * N;
-      v[0] += p[c0]; v[1] += p[c1]; v[2] += p[d + c0]; v[3] += p[d + c1]; v[4] += p[2 * d + c0]; v[5] += p[2 * d + c1];
-    }
-    const float cs = o.rope_cos[pos * half + i], sn = o.rope_sin[pos * half + i];
-    f16* q = (f16*)o.q + (size_t)(row0 + m) * d;
-    q[c0] = from_f32<f16>(v[0] * cs - v[1] * sn);
-    q[c1] = from_f32<f16>(v[1] * cs + v[0] * sn);
-    const size_t kv = (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * hd;
-    ((f16*)o.k_cache)[kv + i] = from_f32<f16>(v[2] * cs - v[3] * sn);
-    ((f16*)o.k_cache)[kv + i + half] = from_f32<f16>(v[3] * cs + v[2] * sn);
-    ((f16*)o.v_cache)[kv + i] = from_f32<f16>(v[4]);
-    ((f16*)o.v_cache)[kv + i + half] = from_f32<f16>(v[5]);
+  for (int j = 0; j < 8; ++j) {
+    const float a = g[j] / (1.0f + __expf(-g[j])) * u[j];
+    o[j] = from_f32<f16>(a);
+    oe[j] = from_f32<f16>(a - (float)o[j]);
   }
+  const size_t at = frag_index(row0 + m, j0, f);
+  *(f16x8*)(act_frag + at) = o;
+  if (act_frag_lo) *(f16x8*)(act_frag_lo + at) = oe;
 }
-void reduce_qkv_rope(const float* part, int ksplit, int M, const RopeKv& o, int row0, hipStream_t st) {
-  hipLaunchKernelGGL(reduce_qkv_rope_kernel, dim3(M), dim3(256), 0, st, part, ksplit, M, o, row0);
+void reduce_swiglu(const float* part, int ksplit, int plane_rows, int prow0, int M, int f, f16* act_frag,
+                   f16* act_frag_lo, int row0, hipStream_t st) {
+  hipLaunchKernelGGL(reduce_swiglu_kernel, dim3((f / 8 + 255) / 256, M), dim3(256), 0, st, part, ksplit, plane_rows,
+                     prow0, f, act_frag, act_frag_lo, row0);
 }
 
 }  // namespace vla

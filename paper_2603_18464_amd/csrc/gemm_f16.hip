@@ -91,6 +91,7 @@ struct EpiResid {
 struct EpiSwiglu {
   f16* act;
   int ld;
+  int lo_off;   // two-term mode: the low term of act[m][j] goes to act[m][lo_off + j] (0: single-term)
   // the 128 tile columns are [gate 32 | up 32 | gate 32 | up 32] -> 64 outputs per row
   __device__ __forceinline__ void consume(const float* tile, int m_base, int nb, int lane, int M) const {
     typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
@@ -100,10 +101,17 @@ struct EpiSwiglu {
       const int r = it * 4 + rs, m = m_base + r;
       const f32x4 g = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + c4) * (1.0f / kWeightScale);
       const f32x4 u = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + 32 + c4) * (1.0f / kWeightScale);
-      f16x4 o;
+      f16x4 o, oe;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) o[j] = from_f32<f16>(g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j])) * u[j]);
-      if (m < M) *(f16x4*)(act + (size_t)m * ld + nb / 2 + jb * 32 + c4) = o;
+      for (int j = 0; j < 4; ++j) {
+        const float a = g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j])) * u[j];
+        o[j] = from_f32<f16>(a);
+        oe[j] = from_f32<f16>(a - (float)o[j]);
+      }
+      if (m < M) {
+        *(f16x4*)(act + (size_t)m * ld + nb / 2 + jb * 32 + c4) = o;
+        if (lo_off) *(f16x4*)(act + (size_t)m * ld + lo_off + nb / 2 + jb * 32 + c4) = oe;
+      }
     }
   }
   template <int MT, int NT>
@@ -123,7 +131,10 @@ struct EpiSwiglu {
             for (int j = 0; j < NT / 2; ++j) {
               const float g = acc[mt][2 * j][4 * blk + r] * (1.0f / kWeightScale);
               const float u = acc[mt][2 * j + 1][4 * blk + r] * (1.0f / kWeightScale);
-              row[j * 32] = from_f32<f16>(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u);
+              const float a = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+              const f16 a16 = from_f32<f16>(a);
+              row[j * 32] = a16;
+              if (lo_off) row[lo_off + j * 32] = from_f32<f16>(a - (float)a16);
             }
           }
         }
@@ -166,26 +177,39 @@ struct EpiQkv {
       f32x4 lo = *(const f32x4*)(tile + r * kStagePitch + hh * HD + c4) * (1.0f / kWeightScale);
       f32x4 hi = *(const f32x4*)(tile + r * kStagePitch + hh * HD + HALF + c4) * (1.0f / kWeightScale);
       f16* dst;
+      f16* dst_lo = nullptr;                 // two-term mode: where the low terms of the same elements go
       if (sect == 0) {
-        dst = (f16*)o.q + (size_t)min(m, M - 1) * d + (size_t)head * HD;
+        dst = (f16*)o.q + (size_t)min(m, M - 1) * o.ldq + (size_t)head * HD;
+        if (o.k_lo) dst_lo = dst + d;
       } else {
-        dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) +
-              (((size_t)slot[it] * o.n_heads + head) * o.max_seq + pos[it]) * HD;
+        const size_t at = (((size_t)slot[it] * o.n_heads + head) * o.max_seq + pos[it]) * HD;
+        dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) + at;
+        if (o.k_lo) dst_lo = (f16*)(sect == 1 ? o.k_lo : o.v_lo) + at;
       }
       if (sect < 2) {
-        const f32x4 a = lo * cs[it] - hi * sn[it], b = hi * cs[it] + lo * sn[it];
-        lo = a;
-        hi = b;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float a, b;
+          rope_pair(lo[j], hi[j], cs[it][j], sn[it][j], a, b);
+          lo[j] = a;
+          hi[j] = b;
+        }
       }
-      f16x4 l4, h4;
+      f16x4 l4, h4, l4e, h4e;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         l4[j] = from_f32<f16>(lo[j]);
         h4[j] = from_f32<f16>(hi[j]);
+        l4e[j] = from_f32<f16>(lo[j] - (float)l4[j]);
+        h4e[j] = from_f32<f16>(hi[j] - (float)h4[j]);
       }
       if (m < M) {
         *(f16x4*)(dst + c4) = l4;
         *(f16x4*)(dst + HALF + c4) = h4;
+        if (dst_lo) {
+          *(f16x4*)(dst_lo + c4) = l4e;
+          *(f16x4*)(dst_lo + HALF + c4) = h4e;
+        }
       }
     }
   }
@@ -214,22 +238,33 @@ struct EpiQkv {
           for (int hh = 0; hh < NT / HT; ++hh) {
             const int head = (col0 + hh * HD) / HD;
             f16* dst;
-            if (sect == 0) dst = (f16*)o.q + (size_t)m * d + (size_t)head * HD;
-            else dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) +
-                       (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * HD;
+            f16* dst_lo = nullptr;
+            if (sect == 0) {
+              dst = (f16*)o.q + (size_t)m * o.ldq + (size_t)head * HD;
+              if (o.k_lo) dst_lo = dst + d;
+            } else {
+              const size_t at = (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * HD;
+              dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) + at;
+              if (o.k_lo) dst_lo = (f16*)(sect == 1 ? o.k_lo : o.v_lo) + at;
+            }
 #pragma unroll
             for (int ht = 0; ht < HT / 2; ++ht) {
               const int j = ht * 32 + c;     // index of the pair inside the head
               float lo = acc[mt][hh * HT + ht][ai] * (1.0f / kWeightScale);
               float hi = acc[mt][hh * HT + ht + HT / 2][ai] * (1.0f / kWeightScale);
               if (sect < 2) {
-                const float cs = cs_row[j], sn = sn_row[j];
-                const float a = lo * cs - hi * sn, b = hi * cs + lo * sn;
+                float a, b;
+                rope_pair(lo, hi, cs_row[j], sn_row[j], a, b);
                 lo = a;
                 hi = b;
               }
-              dst[j] = from_f32<f16>(lo);
-              dst[j + HALF] = from_f32<f16>(hi);
+              const f16 l16 = from_f32<f16>(lo), h16 = from_f32<f16>(hi);
+              dst[j] = l16;
+              dst[j + HALF] = h16;
+              if (dst_lo) {
+                dst_lo[j] = from_f32<f16>(lo - (float)l16);
+                dst_lo[j + HALF] = from_f32<f16>(hi - (float)h16);
+              }
             }
           }
         }
@@ -239,7 +274,7 @@ struct EpiQkv {
 // ---- kernel -----------------------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN, class Epi>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
-    const f16* __restrict__ A, int lda, const f16* __restrict__ Wp, int M, int N, int K,
+    const f16* __restrict__ A, int lda, const f16* __restrict__ Wp, int M, int N, int K, int Kw,
     int tiles_m, int tiles_n, Epi epi) {
   constexpr int NTHR = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
@@ -268,7 +303,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int KB16 = K >> 4, KT = K / BK;
+  const int KB16 = Kw >> 4, KT = K / BK, KTw = Kw / BK;   // K == 2 * Kw: two-term A, the weight slabs wrap
 
   // Global -> register -> LDS staging.  Thread t moves 16-byte chunks: chunk (t & 7) of rows
   // (t >> 3) + i * NTHR/8 of the A slab (XOR-swizzled on the way into LDS), and the linear chunks
@@ -319,8 +354,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
     const int kn = min(kt + 1, KT - 1);
 #pragma unroll
     for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const u32x4*)(a_ptr[i] + kn * BK);
+    const int knw = kn >= KTw ? kn - KTw : kn;
 #pragma unroll
-    for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const u32x4*)(w_ptr[i] + (size_t)kn * 4 * 512);
+    for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const u32x4*)(w_ptr[i] + (size_t)knw * 4 * 512);
     __builtin_amdgcn_sched_barrier(0);   // keep the prefetch at the top: its latency hides under the MFMAs
     const f16* as = As + (kt & 1) * BM * BK;
     const f16* ws = Ws + (kt & 1) * BN * BK + w_off;
@@ -501,7 +537,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <int WGM, int WGN, class Epi>
 __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const f16* __restrict__ A, int lda,
                                                                          const f16* __restrict__ Wp, int M, int N,
-                                                                         int K, int tiles_m, int tiles_n, Epi epi) {
+                                                                         int K, int Kw, int tiles_m, int tiles_n,
+                                                                         Epi epi) {
   constexpr int BM = 256, BN = 256, NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
   constexpr int A_INSTR = (BM / 16) / NW;      // 16 rows per load instruction -> 2 per wave
@@ -528,7 +565,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
-  const int KB16 = K >> 4, KT = K / PK;
+  const int KB16 = Kw >> 4, KT = K / PK, KTw = Kw / PK;   // K == 2 * Kw: two-term A, the weight slabs wrap
 
   const f16* a_src[A_INSTR];
 #pragma unroll
@@ -546,12 +583,13 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   auto issue = [&](int kt) {                             // slab kt (clamped) into buffer kt % 4
     const int buf = kt & (P_STAGES - 1);
     const int ks = min(kt, KT - 1);
+    const int ksw = ks >= KTw ? ks - KTw : ks;
     f16* as = As + buf * P_STAGE_HALVES + wave * A_INSTR * 512;
     f16* ws = Ws + buf * P_STAGE_HALVES + wave * W_INSTR * 512;
 #pragma unroll
     for (int i = 0; i < A_INSTR; ++i) load_to_lds_16(a_src[i] + (size_t)ks * PK, as + i * 512);
 #pragma unroll
-    for (int i = 0; i < W_INSTR; ++i) load_to_lds_16(w_src[i] + (size_t)ks * 2 * 512, ws + i * 512);
+    for (int i = 0; i < W_INSTR; ++i) load_to_lds_16(w_src[i] + (size_t)ksw * 2 * 512, ws + i * 512);
   };
 
   f32x16 acc[MT][NT];
@@ -583,7 +621,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
     if (i < A_INSTR)
       load_to_lds_16(a_src[i] + (size_t)ks * PK, As + buf * P_STAGE_HALVES + (wave * A_INSTR + i) * 512);
     else
-      load_to_lds_16(w_src[i - A_INSTR] + (size_t)ks * 2 * 512,
+      load_to_lds_16(w_src[i - A_INSTR] + (size_t)(ks >= KTw ? ks - KTw : ks) * 2 * 512,
                      Ws + buf * P_STAGE_HALVES + (wave * W_INSTR + i - A_INSTR) * 512);
   };
   auto step = [&](int kt, int f) {           // f = kt & 1, passed as a constant by the unrolled caller
@@ -705,7 +743,8 @@ static void launch_pipe(const GemmF16& g, const Epi& epi, hipStream_t st) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, tiles_m, tiles_n, epi);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, g.Kw, tiles_m,
+                     tiles_n, epi);
 }
 
 template <int BM, int BN, int WGM, int WGN, class Epi>
@@ -720,7 +759,7 @@ static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, g.Kw,
                      tiles_m, tiles_n, epi);
 }
 
@@ -743,8 +782,8 @@ static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
 void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st) {
   dispatch<true>(g, EpiResid{x, ldx}, st);
 }
-void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, hipStream_t st) {
-  dispatch<true>(g, EpiSwiglu{act, ldact}, st);
+void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, int lo_off, hipStream_t st) {
+  dispatch<true>(g, EpiSwiglu{act, ldact, lo_off}, st);
 }
 void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st) {
   if (o.head_dim == 128) dispatch<false>(g, EpiQkv<128>{o}, st);

@@ -135,21 +135,30 @@ template void assemble_prefix<bf16>(const bf16*, const int32_t*, const bf16*, co
 // ---- last-layer tail: only the rows that feed the head go through the last O / feed-forward ------------
 // Row i of the compact set is packed row need[i]: its attention output goes to fragment order
 // [i/32][k/16][lane][8] (what the weight-streaming GEMMs read), its residual row to x_c[i].
-__global__ __launch_bounds__(256) void gather_tail_kernel(const f16* __restrict__ att, const float* __restrict__ x,
+__global__ __launch_bounds__(256) void gather_tail_kernel(const f16* __restrict__ att, int ld_att,
+                                                          const float* __restrict__ x,
                                                           const int32_t* __restrict__ need, int d,
-                                                          f16* __restrict__ att_frag, float* __restrict__ x_c) {
+                                                          f16* __restrict__ att_frag, f16* __restrict__ att_frag_lo,
+                                                          float* __restrict__ x_c) {
   const int i = blockIdx.x, src = need[i];
-  const u32x4* arow = (const u32x4*)(att + (size_t)src * d);
+  const u32x4* arow = (const u32x4*)(att + (size_t)src * ld_att);
   u32x4* ablk = (u32x4*)(att_frag + (size_t)(i >> 5) * (d >> 4) * 512);
   for (int kc = threadIdx.x; kc < (d >> 3); kc += blockDim.x)
     ablk[(size_t)(kc >> 1) * 64 + (i & 31) + 32 * (kc & 1)] = arow[kc];
+  if (att_frag_lo) {                       // two-term rows [hi | lo]: the low terms follow at column d
+    const u32x4* lrow = (const u32x4*)(att + (size_t)src * ld_att + d);
+    u32x4* lblk = (u32x4*)(att_frag_lo + (size_t)(i >> 5) * (d >> 4) * 512);
+    for (int kc = threadIdx.x; kc < (d >> 3); kc += blockDim.x)
+      lblk[(size_t)(kc >> 1) * 64 + (i & 31) + 32 * (kc & 1)] = lrow[kc];
+  }
   const f32x4* xr = (const f32x4*)(x + (size_t)src * d);
   f32x4* xo = (f32x4*)(x_c + (size_t)i * d);
   for (int j = threadIdx.x; j < (d >> 2); j += blockDim.x) xo[j] = xr[j];
 }
-void gather_tail(const f16* att, const float* x, const int32_t* need, int n, int d, f16* att_frag, float* x_c,
-                 hipStream_t st) {
-  hipLaunchKernelGGL(gather_tail_kernel, dim3(n), dim3(256), 0, st, att, x, need, d, att_frag, x_c);
+void gather_tail(const f16* att, int ld_att, const float* x, const int32_t* need, int n, int d, f16* att_frag,
+                 f16* att_frag_lo, float* x_c, hipStream_t st) {
+  hipLaunchKernelGGL(gather_tail_kernel, dim3(n), dim3(256), 0, st, att, ld_att, x, need, d, att_frag, att_frag_lo,
+                     x_c);
 }
 __global__ __launch_bounds__(256) void scatter_tail_kernel(const float* __restrict__ x_c,
                                                            const int32_t* __restrict__ need, int d,
@@ -284,7 +293,7 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 template <class T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                       T* __restrict__ out, int d, float eps,
-                                                      const int32_t* __restrict__ row_index) {
+                                                      const int32_t* __restrict__ row_index, int ldo, int lo_off) {
   typedef __attribute__((ext_vector_type(4))) T T4;
   __shared__ float red[4];
   const int r = blockIdx.x;
@@ -304,13 +313,18 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   }
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  T* o = out + (size_t)r * d;
-  auto emit = [&](int i, const f32x4& v) {
+  T* o = out + (size_t)r * ldo;
+  auto emit = [&](int i, const f32x4& v) {     // lo_off > 0 (two-term output): the low terms go to column lo_off + i
     const f32x4 g = *(const f32x4*)(gain + i);
-    T4 q;
+    T4 q, qe;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) q[j] = from_f32<T>(v[j] * inv * g[j]);
+    for (int j = 0; j < 4; ++j) {
+      const float h = v[j] * inv * g[j];
+      q[j] = from_f32<T>(h);
+      qe[j] = from_f32<T>(h - to_f32(q[j]));
+    }
     *(T4*)(o + i) = q;
+    if (lo_off) *(T4*)(o + lo_off + i) = qe;
   };
 #pragma unroll
   for (int it = 0; it < kHeld; ++it) {
@@ -321,13 +335,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 }
 template <class T>
 void rmsnorm(const float* x, const T*, const float* gain, T* out, int rows, int d, float eps,
-             const int32_t* row_index, hipStream_t st) {
-  hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(rows), dim3(256), 0, st, x, gain, out, d, eps, row_index);
+             const int32_t* row_index, bool two_term, hipStream_t st) {
+  hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(rows), dim3(256), 0, st, x, gain, out, d, eps, row_index,
+                     two_term ? 2 * d : d, two_term ? d : 0);
 }
 template void rmsnorm<float>(const float*, const float*, const float*, float*, int, int, float, const int32_t*,
-                             hipStream_t);
+                             bool, hipStream_t);
 template void rmsnorm<f16>(const float*, const f16*, const float*, f16*, int, int, float, const int32_t*,
-                           hipStream_t);
+                           bool, hipStream_t);
 
 // ---- action head ------------------------------------------------------------------------------------
 // Workgroup (b, g): final RMSNorm of sequence b's row (float32, kept in LDS), then 32 action rows of

@@ -26,11 +26,18 @@ from oracle import vla_oracle as O         # noqa: E402
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 
-def pick_rows(wl, obs):
+def pick_rows(wl, obs, n=8):
+    """n sequences of the batch: the first and last, the shortest and longest prefix, both sides of every
+    128-row boundary (decode and last-layer kernels work on groups of 128 rows), then evenly spaced ones."""
     lens = np.diff(obs["cu_instr"])
-    if wl.instr_len[0] != wl.instr_len[1]:
-        return sorted({int(np.argmin(lens)), int(np.argmax(lens))})
-    return [0, wl.batch - 1]
+    B = wl.batch
+    rows = [0, B - 1, int(np.argmin(lens)), int(np.argmax(lens))]
+    for edge in range(128, B, 128):
+        rows += [edge - 1, edge]
+    for r in np.linspace(0, B - 1, n + 2).astype(int)[1:-1]:
+        if len(set(rows)) < n:
+            rows.append(int(r))
+    return sorted(set(rows))
 
 
 def main(names, parallel=False):

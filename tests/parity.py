@@ -16,24 +16,21 @@ import numpy as np
 import workloads as W
 from oracle import vla_oracle as O
 
-# Tolerances.  float32 and the 16-bit path up to 12 layers use the stated bars: max-abs logit error
-# 1e-4 / 2e-2, log-prob error 1e-2 (1e-4 in float32), tokens identical unless the oracle's top-2 gap
-# of the selection scores is below 1e-2.  The 32-layer 7B-shaped workloads cannot meet 2e-2 with
-# 16-bit matrix-core operands of any kind: rounding the operands alone, in the oracle's own fp64
-# arithmetic (oracle/rounding_model.py), gives rms 3.6e-3 / max 1.1e-2 after 8 layers in half
-# precision (2.5e-2 / 8e-2 in bfloat16) at logit std 1.3, and grows like sqrt(depth), i.e. rms 7e-3 and
-# max 3e-2 over a few thousand logits at 32 layers.  They are held to max-abs 5e-2 and rms 1.2e-2
-# instead, and a token may differ where the oracle's top-2 gap is below 5e-2 (two logits, each within
-# tolerance, can swap order inside that gap).
+# Tolerances: the stated bars.  float32: max-abs logit error 1e-4.  16-bit path in its default two-term mode
+# (VLA_PREC_HIGH), at every depth: max-abs logit error 2e-2, log-prob error 1e-2, tokens identical unless the
+# oracle's top-2 gap of the selection scores is below 1e-2.  The single-term mode (VLA_PREC_FAST) is a named fast
+# mode, not the headline: it meets the same bars up to 12 layers; at 32 layers rounding every matrix-core operand
+# to one half-precision term costs rms 7e-3 / max 3e-2 in the oracle's own fp64 arithmetic
+# (oracle/rounding_model.py, tests/test_rounding_model.py), so its 7B runs are held to "fast_deep" only.
 TOL = {"bf16": dict(logit=2e-2, logp=1e-2, tie=1e-2, rms=None),
        "f32": dict(logit=1e-4, logp=1e-4, tie=1e-2, rms=None),
-       "bf16_deep": dict(logit=5e-2, logp=5e-2, tie=5e-2, rms=1.2e-2)}
+       "fast_deep": dict(logit=5e-2, logp=5e-2, tie=5e-2, rms=1.2e-2)}
 
 
-def tolerances(wl):
+def tolerances(wl, fast=False):
     if wl.shape.dtype == "f32":
         return TOL["f32"]
-    return TOL["bf16_deep"] if wl.shape.n_layers > 12 else TOL["bf16"]
+    return TOL["fast_deep"] if (fast and wl.shape.n_layers > 12) else TOL["bf16"]
 
 
 def split_obs(obs, rows):

@@ -28,16 +28,21 @@ def test_library_exports_every_declared_symbol():
 
 def test_config_validation_and_sizes():
     wl = W.get_workload("C3")
-    cfg = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
+    cfg = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290, precision=B.VLA_PREC_FAST)
     arena, kv, work = B.vla_query_sizes(cfg)
     s = wl.shape
     assert kv == 2 * s.n_layers * wl.batch * s.n_heads * (wl.max_seq | 1) * s.head_dim * 2     # odd position pitch
+    # two-term mode keeps a second set of planes with the low terms of the cached keys and values
+    hi = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
+    assert hi.precision == B.VLA_PREC_HIGH
+    arena_hi, kv_hi, work_hi = B.vla_query_sizes(hi)
+    assert kv_hi == 2 * kv and arena_hi == arena and work_hi > work
     assert arena >= 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model)
     assert arena < 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model) + (4 << 20)   # head is slimmed: no second [V,d] matrix
     ctx = B.vla_create(cfg)
     B.vla_destroy(ctx)
     for field, value in [("n_heads", 31), ("dtype", 5), ("n_action_bins", 0), ("n_action_bins", 40000),
-                         ("max_seq", 0), ("head_dim", 100), ("rope_theta", 0.0)]:
+                         ("max_seq", 0), ("head_dim", 100), ("rope_theta", 0.0), ("precision", 2)]:
         bad = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
         setattr(bad, field, value)
         with pytest.raises(B.VlaError) as e:

@@ -12,20 +12,26 @@ pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def make_policy(wl, weights, max_batch=None, extra_seq=0):
+def make_policy(wl, weights, max_batch=None, extra_seq=0, fast=False):
+    """fast=True: the single-term mode of the 16-bit path (VLA_PREC_FAST); default is the two-term mode."""
     from paper_2603_18464_amd import VlaPolicy
+    from paper_2603_18464_amd.binding import VLA_PREC_FAST, VLA_PREC_HIGH
     B = max_batch or wl.batch
     # token capacity: the longest prefix for every slot, plus the fed positions of the one-pass entry points
-    pol = VlaPolicy(wl.shape, B, wl.max_seq + extra_seq, B * (wl.n_patches + wl.instr_len[1] + wl.n_tokens - 1))
+    pol = VlaPolicy(wl.shape, B, wl.max_seq + extra_seq, B * (wl.n_patches + wl.instr_len[1] + wl.n_tokens - 1),
+                    precision=VLA_PREC_FAST if fast else VLA_PREC_HIGH)
     pol.load_weights(weights)
     return pol
 
 
-def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, offset=None):
+FAST_MODES = pytest.mark.parametrize("fast", [False, True], ids=["two_term", "fast"])
+
+
+def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, offset=None, fast=False):
     import torch
     weights = W.make_weights(wl.shape, wl.seed)
     obs = obs or W.make_observations(wl)
-    pol = make_policy(wl, weights)
+    pol = make_policy(wl, weights, fast=fast)
     dev = P.device_inputs(pol, obs, gumbel)
     temp = wl.temperature if wl.sampling == "gumbel" else 0.0
     sc = None if scale is None else torch.tensor(scale, dtype=torch.float32, device=pol.device)
@@ -40,10 +46,10 @@ def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, of
     if scale is not None:
         from oracle.vla_oracle import detokenise
         ora["actions"] = detokenise(ora["tokens"], wl.shape.n_action_bins, wl.action_dim, scale, offset)
-    tol = P.tolerances(wl)
+    tol = P.tolerances(wl, fast)
     stats = P.check_free_running(wl, gpu, ora, rows, tol)
     tf_err, tf_rms = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
-    print(f"\n[{wl.name}] free-running {stats}; teacher-forced logit err max {tf_err:.3e} rms {tf_rms:.3e}")
+    print(f"\n[{wl.name}{' fast' if fast else ''}] free-running {stats}; teacher-forced logit err max {tf_err:.3e} rms {tf_rms:.3e}")
     pol.close()
     return stats, gpu, ora
 
@@ -81,8 +87,9 @@ def test_fp32_ragged_with_sampling_and_affine_actions():
     run_both(wl, obs=obs, gumbel=gum, mode="recompute", scale=[2.0, 0.5, 1.0], offset=[0.1, -0.2, 0.0])
 
 
+@FAST_MODES
 @pytest.mark.parametrize("hd,heads", [(128, 2), (64, 4)])
-def test_bf16_small_ragged_spans_tiles(hd, heads):
+def test_bf16_small_ragged_spans_tiles(hd, heads, fast):
     """bf16 MFMA path: several 256-row tiles with a ragged tail, sequences of length 1, both head sizes."""
     shape = W.PolicyShape(2, 256, heads, hd, 704, 1024, dtype="bf16")
     lens = [0, 3, 17, 40, 9, 0, 25]
@@ -92,10 +99,11 @@ def test_bf16_small_ragged_spans_tiles(hd, heads):
     obs = ragged_obs(wl, nps, lens, seed=78)
     gum = W.make_gumbel(wl)
     assert int(obs["cu_patch"][-1] + obs["cu_instr"][-1]) > 2 * 256
-    run_both(wl, obs=obs, gumbel=gum)
+    run_both(wl, obs=obs, gumbel=gum, fast=fast)
 
 
-def test_bf16_tiny_prefixes_keep_every_row_in_the_last_layer():
+@FAST_MODES
+def test_bf16_tiny_prefixes_keep_every_row_in_the_last_layer(fast):
     """Prefixes of 1-3 tokens: more than half of the packed rows feed the head, so the last layer is not
     restricted to them (the other branch of the prefill), and all GEMMs take the small-tile path."""
     shape = W.PolicyShape(3, 256, 2, 128, 704, 1024, dtype="bf16")
@@ -104,11 +112,12 @@ def test_bf16_tiny_prefixes_keep_every_row_in_the_last_layer():
                     sampling="gumbel", temperature=0.8)
     obs = ragged_obs(wl, nps, lens, seed=83)
     assert int(obs["cu_patch"][-1] + obs["cu_instr"][-1]) < 2 * wl.batch
-    run_both(wl, obs=obs, gumbel=W.make_gumbel(wl))
+    run_both(wl, obs=obs, gumbel=W.make_gumbel(wl), fast=fast)
 
 
+@FAST_MODES
 @pytest.mark.parametrize("hd,heads", [(128, 2), (64, 4)])
-def test_bf16_long_context(hd, heads):
+def test_bf16_long_context(hd, heads, fast):
     """Contexts of 600+ positions: decode attention streams 40+ row groups per wave, prefill walks 11 key tiles."""
     shape = W.PolicyShape(2, 256, heads, hd, 704, 1024, dtype="bf16")
     nps, lens = [640, 600, 333], [41, 0, 17]
@@ -116,22 +125,25 @@ def test_bf16_long_context(hd, heads):
                     sampling="gumbel", temperature=0.9)
     assert wl.max_seq > 640
     obs = ragged_obs(wl, nps, lens, seed=85)
-    run_both(wl, obs=obs, gumbel=W.make_gumbel(wl))
+    run_both(wl, obs=obs, gumbel=W.make_gumbel(wl), fast=fast)
 
 
 @pytest.mark.timeout(600)
-def test_c2_bf16_whole_batch():
+@FAST_MODES
+def test_c2_bf16_whole_batch(fast):
     wl = W.get_workload("C2")
-    stats, _, _ = run_both(wl)
+    stats, _, _ = run_both(wl, fast=fast)
     assert stats["compared"] > 0.8 * wl.batch * wl.n_tokens
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
-def test_7b_workloads_against_stored_oracle_rows(name):
+@pytest.mark.parametrize("name,fast", [("C3", False), ("C4", False), ("C5", False), ("C3", True)],
+                         ids=["C3", "C4", "C5", "C3_fast_mode"])
+def test_7b_workloads_against_stored_oracle_rows(name, fast):
     """Full-size batch in the benchmark's launch configuration; the oracle's rows were written by
     tests/golden/make_7b_goldens.py (sequences are independent, so rows of a batched run must equal
-    the same sequences run alone)."""
+    the same sequences run alone).  The default two-term mode is held to the stated tolerances; the single-term
+    fast mode is run once (C3) against its own wider bars."""
     import torch
     path = os.path.join(GOLDEN, f"{name.lower()}_oracle.npz")
     if not os.path.exists(path):
@@ -145,7 +157,7 @@ def test_7b_workloads_against_stored_oracle_rows(name):
     weights = W.make_weights(wl.shape, wl.seed, threads=16)
     obs = W.make_observations(wl)
     gum = W.make_gumbel(wl) if wl.sampling == "gumbel" else None
-    pol = make_policy(wl, weights)
+    pol = make_policy(wl, weights, fast=fast)
     del weights
     dev = P.device_inputs(pol, obs, gum)
     temp = wl.temperature if wl.sampling == "gumbel" else 0.0
@@ -157,7 +169,7 @@ def test_7b_workloads_against_stored_oracle_rows(name):
     assert np.isfinite(gpu["logits"]).all() and np.isfinite(gpu["logp"]).all()
     assert (gpu["tokens"] >= 0).all() and (gpu["tokens"] < wl.shape.n_action_bins).all()
     assert (gpu["logp"] <= 0).all()
-    tol = P.tolerances(wl)
+    tol = P.tolerances(wl, fast)
     stats = P.check_free_running(wl, gpu, ora, rows, tol)
     print(f"[{name}] teacher-forced pass", flush=True)
     tf_err, tf_rms = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
