@@ -130,6 +130,10 @@ def main():
     ap.add_argument("--prof-mask", type=lambda v: int(v, 0), default=0x3fff)
     ap.add_argument("--no-weight-update", action="store_true",
                     help="skip the (untimed, reported under detail) in-place weight update measurement")
+    ap.add_argument("--precision", choices=["high", "fast"], default="high",
+                    help="arithmetic of the 16-bit path: high = two-term operands (meets the stated tolerances at 32 "
+                         "layers; the headline), fast = single-term operands")
+    ap.add_argument("--no-other-mode", action="store_true", help="skip the short run of the other precision mode")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the policy shards by "
@@ -149,7 +153,10 @@ def main():
     gum = W.make_gumbel(wl) if wl.sampling == "gumbel" else None
     cu_seq = obs["cu_patch"] + obs["cu_instr"]
     nums = model_numbers(wl, cu_seq)
-    pol = VlaPolicy(wl.shape, wl.batch, wl.max_seq, nums["T"] + wl.batch * (wl.n_tokens - 1), value_max_steps=64)
+    from paper_2603_18464_amd.binding import VLA_PREC_FAST, VLA_PREC_HIGH
+    prec = VLA_PREC_HIGH if args.precision == "high" else VLA_PREC_FAST
+    pol = VlaPolicy(wl.shape, wl.batch, wl.max_seq, nums["T"] + wl.batch * (wl.n_tokens - 1), value_max_steps=64,
+                    precision=prec)
     pol.load_weights(weights)
     pol.load_value_head(W.make_value_weights(wl.shape, wl.seed, 64))
     if args.no_weight_update:

@@ -118,6 +118,15 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
  * VLA_E_DRAINING while an update opened by vla_update_begin is not committed. */
 int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors, void* hip_stream);
 
+/* VLA_BF16 only: the re-encoding of a weight matrix element as f16(w * 2^8) is exact for 2^-25 <= |w| <= 255 (and
+ * w = 0); a smaller nonzero value is rounded with an absolute error below 2^-33.  The load kernels check every
+ * matrix element; a value above 255 in magnitude, or not finite, is never accepted silently: once the load's
+ * device work has completed, every compute call returns VLA_E_WEIGHTS until a
+ * whole set is loaded again with vla_load_weights (a partial update does not clear the finding).  Compute calls
+ * look at the result without waiting (a call enqueued while the load is still running goes ahead);
+ * vla_check_weights waits for the last load / update on the host and returns VLA_OK or VLA_E_WEIGHTS. */
+int vla_check_weights(vla_ctx* ctx);
+
 /* Prefill: sequence slot b (0 <= b < B) gets the prefix
  *   [patch_emb rows cu_patch[b] .. cu_patch[b+1]) ; embed[instr_ids[cu_instr[b] .. cu_instr[b+1])]]
  * at positions 0 .. S_b-1; its keys/values are written to the cache and its length is set to S_b.

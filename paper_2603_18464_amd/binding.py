@@ -15,7 +15,7 @@ STATUS = {0: "VLA_OK", -1: "VLA_E_NULL", -2: "VLA_E_CONFIG", -3: "VLA_E_SHAPE", 
 VLA_E_STATE, VLA_E_DRAINING = -5, -8
 VLA_ACCEPTING, VLA_DRAINING, VLA_UPDATING = 0, 1, 2
 EXPORTS = ["vla_create", "vla_destroy", "vla_last_error", "vla_query_sizes", "vla_bind_buffers",
-           "vla_load_weights", "vla_prefill", "vla_decode_step", "vla_decode_step_static", "vla_policy_step", "vla_select",
+           "vla_load_weights", "vla_check_weights", "vla_prefill", "vla_decode_step", "vla_decode_step_static", "vla_policy_step", "vla_select",
            "vla_load_value_head", "vla_policy_step_value",
            "vla_policy_step_parallel", "vla_score_tokens",
            "vla_prefill_slots", "vla_decode_slots", "vla_release_slots",
@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
         L.vla_query_sizes.argtypes = [C.POINTER(vla_config)] + [C.POINTER(C.c_size_t)] * 3
         L.vla_bind_buffers.argtypes = [vp, vp, vp, vp]
         L.vla_load_weights.argtypes = [vp, C.POINTER(vla_tensor), i32, vp]
+        L.vla_check_weights.argtypes = [vp]
         L.vla_prefill.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
         L.vla_decode_step.argtypes = [vp, i32, vp, vp, vp]
         L.vla_decode_step_static.argtypes = [vp, i32, vp, vp, vp]
@@ -155,6 +156,10 @@ def vla_load_weights(ctx, tensors: Dict[str, "object"], dtype: int, stream: int 
         for j, s in enumerate(t.shape):
             arr[i].shape[j] = s
     _check(ctx, lib().vla_load_weights(ctx, arr, len(tensors), stream))
+
+
+def vla_check_weights(ctx) -> None:
+    _check(ctx, lib().vla_check_weights(ctx))
 
 
 def _tensor_array(tensors: Dict[str, "object"], dtype: int):
@@ -392,6 +397,7 @@ class VlaPolicy:
             dev[n] = self.to_device(t) if isinstance(t, np.ndarray) else t
         vla_load_weights(self.ctx, dev, self.dtype_code, self._stream())
         self.torch.cuda.current_stream(self.device).synchronize()   # sources may now be freed
+        vla_check_weights(self.ctx)                                 # raises VLA_E_WEIGHTS for unrepresentable values
 
     def load_value_head(self, weights: Dict[str, "object"]):
         dev = {n: (self.to_device(t) if isinstance(t, np.ndarray) else t) for n, t in weights.items()}

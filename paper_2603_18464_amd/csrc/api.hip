@@ -35,7 +35,8 @@ struct ArenaLayout {
 };
 struct WorkLayout {
   size_t x, hn, q, att, act, scratch, part, rope_cos, rope_sin, tok_seq, tok_pos, tok_src, last_row, seq_len,
-      cu_patch, cu_instr, cur_ids, logits, vz, vml, vu, vh, ids2, tail, chunk_rows, chunk_logits, slot_map, total;
+      cu_patch, cu_instr, cur_ids, logits, vz, vml, vu, vh, ids2, tail, chunk_rows, chunk_logits, slot_map, range_flag,
+      total;
 };
 
 size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
@@ -132,6 +133,7 @@ WorkLayout work_layout(const vla_config& c) {
   w.chunk_rows = take(B * (size_t)kMaxChunk * 4);
   w.chunk_logits = take(B * (size_t)kMaxChunk * c.n_action_bins * 4);
   w.slot_map = take(B * 4);
+  w.range_flag = take(4);
   w.total = off;
   return w;
 }
@@ -207,6 +209,10 @@ struct vla_ctx {
   // pinned staging ring for the host offset arrays
   static constexpr int kRing = 8;
   int32_t* stage = nullptr;
+  // weight range check of the 16-bit path: the pack kernels OR bits into a device flag, a copy to range_host
+  // (pinned) follows every load / update, and the first compute call that finds the copy complete reports it
+  int32_t* range_host = nullptr;
+  bool range_pending = false, weights_bad = false;
   hipEvent_t stage_ev[kRing];
   bool stage_used[kRing];
   int stage_next = 0;
@@ -503,9 +509,40 @@ void run_value_accumulate(vla_ctx* ctx, int B, const int32_t* row_index, bool fi
                    first, at<float>(ctx->work, ctx->wl.vz), at<float>(ctx->work, ctx->wl.vml), st);
 }
 
+// Result of the weight range check of the last load / update, once its device work has completed (wait: block
+// until then).  Out-of-range weights make every compute call fail until a good set is loaded.
+int poll_weight_range(vla_ctx* ctx, bool wait) {
+  if (ctx->range_pending) {
+    hipError_t e = wait ? hipEventSynchronize(ctx->ev_update) : hipEventQuery(ctx->ev_update);
+    if (e == hipSuccess) {
+      ctx->range_pending = false;
+      ctx->weights_bad = *ctx->range_host != 0;
+    } else if (e != hipErrorNotReady) {
+      return fail(ctx, VLA_E_HIP, "weight range check: %s", hipGetErrorString(e));
+    }
+  }
+  if (ctx->weights_bad)
+    return fail(ctx, VLA_E_WEIGHTS, "a loaded weight matrix holds a value that the half-precision re-encoding cannot "
+                "represent (|w| > 255 or not finite)");
+  return VLA_OK;
+}
+
 int check_ready(vla_ctx* ctx) {
   if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
   if (!ctx->weights) return fail(ctx, VLA_E_STATE, "weights are not loaded (vla_load_weights)");
+  return poll_weight_range(ctx, false);
+}
+
+// Start / end of the device work of a load or an update with respect to the range flag.
+int range_check_begin(vla_ctx* ctx, hipStream_t st) {
+  if (ctx->cfg.dtype != VLA_BF16) return VLA_OK;
+  HIP_TRY(ctx, hipMemsetAsync(at<int32_t>(ctx->work, ctx->wl.range_flag), 0, 4, st));
+  return VLA_OK;
+}
+int range_check_end(vla_ctx* ctx, hipStream_t st) {    // before the event that marks the end of the load is recorded
+  if (ctx->cfg.dtype != VLA_BF16) return VLA_OK;
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->range_host, at<int32_t>(ctx->work, ctx->wl.range_flag), 4, hipMemcpyDeviceToHost, st));
+  ctx->range_pending = true;
   return VLA_OK;
 }
 
@@ -755,6 +792,7 @@ int vla_create(const vla_config* cfg, vla_ctx** out) {
 int vla_destroy(vla_ctx* ctx) {
   if (!ctx) return VLA_E_NULL;
   if (ctx->stage) (void)hipHostFree(ctx->stage);
+  if (ctx->range_host) (void)hipHostFree(ctx->range_host);
   for (int i = 0; i < vla_ctx::kRing; ++i)
     if (ctx->stage_ev[i]) (void)hipEventDestroy(ctx->stage_ev[i]);
   if (ctx->ev_work) (void)hipEventDestroy(ctx->ev_work);
@@ -783,6 +821,8 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
     return fail(ctx, VLA_E_SHAPE, "buffers must be %zu-byte aligned", kAlign);
   if (!ctx->stage) {
     HIP_TRY(ctx, hipHostMalloc((void**)&ctx->stage, (size_t)vla_ctx::kRing * 3 * (ctx->cfg.max_batch + 1) * sizeof(int32_t), hipHostMallocDefault));
+    HIP_TRY(ctx, hipHostMalloc((void**)&ctx->range_host, 64, hipHostMallocDefault));
+    *ctx->range_host = 0;
     for (int i = 0; i < vla_ctx::kRing; ++i) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming));
     HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_work, hipEventDisableTiming));
     HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_update, hipEventDisableTiming));
@@ -798,6 +838,7 @@ int vla_bind_buffers(vla_ctx* ctx, void* weight_arena, void* kv, void* workspace
   ctx->len.assign(ctx->cfg.max_batch, 0);
   ctx->serving = VLA_ACCEPTING;
   ctx->have_work = ctx->have_update = false;
+  ctx->range_pending = ctx->weights_bad = false;
   return VLA_OK;
 }
 
@@ -891,7 +932,8 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
   };
   auto matrix = [&](size_t off, int64_t rows, int64_t K, int64_t row0, int mode) {
     if (bf) {
-      pack_weight_f16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<f16>(ctx->arena, off), (int)row0, mode, st);
+      pack_weight_f16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<f16>(ctx->arena, off), (int)row0, mode,
+                      at<int32_t>(ctx->work, ctx->wl.range_flag), st);
     } else {
       const int64_t r0 = mode == 2 ? rows : row0;   // float32 path keeps [gate rows | up rows]
       plain_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off) + r0 * K, (size_t)(rows * K), st);
@@ -935,11 +977,14 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
 
 // A whole-set load outside an update: ordered after the compute calls enqueued so far and before the
 // ones that follow, on whatever streams those run.
-int load_slots(vla_ctx* ctx, const std::vector<const vla_tensor*>& slot, hipStream_t st) {
+int load_slots(vla_ctx* ctx, const std::vector<const vla_tensor*>& slot, bool whole_policy_set, hipStream_t st) {
   if (ctx->have_work) HIP_TRY(ctx, hipStreamWaitEvent(st, ctx->ev_work, 0));
+  int rc = VLA_OK;
+  if (whole_policy_set && (rc = range_check_begin(ctx, st))) return rc;   // every matrix is rewritten: start clean
   for (size_t s = 0; s < slot.size(); ++s)
     if (slot[s]) write_slot(ctx, (int)s, slot[s], st);
   HIP_TRY(ctx, hipGetLastError());
+  if ((rc = range_check_end(ctx, st))) return rc;
   HIP_TRY(ctx, hipEventRecord(ctx->ev_update, st));
   ctx->have_update = true;
   ctx->version += 1;
@@ -967,7 +1012,7 @@ int vla_load_weights(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensors,
   if ((rc = parse_tensors(ctx, tensors, n_tensors, slot))) return rc;
   if ((rc = require_slots(ctx, slot, 0, policy_slots(ctx->cfg), true))) return rc;
   if ((rc = require_slots(ctx, slot, policy_slots(ctx->cfg), all_slots(ctx->cfg), false))) return rc;
-  if ((rc = load_slots(ctx, slot, (hipStream_t)hip_stream))) return rc;
+  if ((rc = load_slots(ctx, slot, true, (hipStream_t)hip_stream))) return rc;
   ctx->weights = true;
   return VLA_OK;
 }
@@ -981,9 +1026,15 @@ int vla_load_value_head(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tenso
   if ((rc = parse_tensors(ctx, tensors, n_tensors, slot))) return rc;
   if ((rc = require_slots(ctx, slot, 0, policy_slots(ctx->cfg), false))) return rc;
   if ((rc = require_slots(ctx, slot, policy_slots(ctx->cfg), all_slots(ctx->cfg), true))) return rc;
-  if ((rc = load_slots(ctx, slot, (hipStream_t)hip_stream))) return rc;
+  if ((rc = load_slots(ctx, slot, false, (hipStream_t)hip_stream))) return rc;
   ctx->value_weights = true;
   return VLA_OK;
+}
+
+int vla_check_weights(vla_ctx* ctx) {
+  if (!ctx) return VLA_E_NULL;
+  if (!ctx->bound) return fail(ctx, VLA_E_STATE, "buffers are not bound (vla_bind_buffers)");
+  return poll_weight_range(ctx, true);
 }
 
 int vla_get_state(const vla_ctx* ctx, int32_t* state, int64_t* version) {
@@ -1031,6 +1082,8 @@ int vla_update_tensors(vla_ctx* ctx, const vla_tensor* tensors, int32_t n_tensor
 int vla_update_commit(vla_ctx* ctx, void* hip_stream, int64_t* version_out) {
   if (!ctx) return VLA_E_NULL;
   if (ctx->serving != VLA_UPDATING) return fail(ctx, VLA_E_STATE, "no update is open (vla_update_begin)");
+  int rc = range_check_end(ctx, (hipStream_t)hip_stream);
+  if (rc) return rc;
   HIP_TRY(ctx, hipEventRecord(ctx->ev_update, (hipStream_t)hip_stream));
   ctx->have_update = true;
   ctx->version += 1;

@@ -21,10 +21,10 @@ __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
 __device__ __forceinline__ float to_f32(f16 v) { return (float)v; }
 template <class T> __device__ __forceinline__ T from_f32(float v);
-// float -> half, saturating at the largest finite half instead of overflowing to infinity
-template <> __device__ __forceinline__ f16 from_f32<f16>(float v) {
-  return (f16)fminf(fmaxf(v, -65504.0f), 65504.0f);
-}
+// float -> half, IEEE round to nearest even: a value beyond the half-precision range becomes an infinity and a
+// NaN stays a NaN, so an overflow or a non-finite input reaches the logits and the log-probs as NaN instead of
+// being clamped to something plausible.
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return (f16)v; }
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }
 
@@ -103,7 +103,8 @@ void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st);       
 // silu(gate)*up; lo_off > 0: also the low terms, at column lo_off + j
 void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, int lo_off, hipStream_t st);
 void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st);               // RoPE + cache
-void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode,
+// range_flag: device int, bits are OR-ed in when a weight cannot be re-encoded exactly (see pack_weight_kernel)
+void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode, int* range_flag,
                      hipStream_t st);
 
 // fp32 path (plain, unfused).

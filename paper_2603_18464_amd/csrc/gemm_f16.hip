@@ -797,32 +797,43 @@ void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st) {
 // row0 + r.  1 (gate) / 2 (up): rows go to the even / odd 32-row blocks of the fused gate-up matrix.
 // One workgroup re-encodes 32 source rows x 512 k: 128-byte row segments are read coalesced, transposed through
 // LDS, and each 1 KiB fragment block is written by one wave in one piece.
+// range_flag (device int): bit 0 is set if a weight is too large for the re-encoding (|w| > 255) or not finite.
+// (At the other end nothing is reported: 0 < |w| < 2^-25 falls between half-precision subnormals and is rounded
+// with an absolute error below 2^-33, which is far below what any tolerance can see; random weights contain
+// such values.)
 __global__ __launch_bounds__(256) void pack_weight_kernel(const bf16* __restrict__ src, int K,
-                                                          f16* __restrict__ dst, int row0, int mode) {
+                                                          f16* __restrict__ dst, int row0, int mode,
+                                                          int* __restrict__ range_flag) {
   __shared__ u32x4 tile[32 * 8];
   const int r0 = blockIdx.x * 32;                       // first source row of this workgroup
   const int nb = mode == 0 ? (row0 + r0) >> 5 : (r0 >> 5) * 2 + (mode == 2 ? 1 : 0);
   const int t = threadIdx.x, rr = t >> 3, cc = t & 7;   // load role: row, 16-byte chunk of a 64-k span
   const int blk = t >> 6, lane = t & 63;                // store role: fragment block of the span, lane
   const int k_end = min(K, (int)(blockIdx.y + 1) * 512);
+  int bad = 0;
   for (int k0 = blockIdx.y * 512; k0 < k_end; k0 += 64) {
     const bf16x8 v = *(const bf16x8*)(src + (size_t)(r0 + rr) * K + k0 + cc * 8);
     f16x8 o;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = from_f32<f16>((float)v[j] * kWeightScale);
+    for (int j = 0; j < 8; ++j) {
+      const float w = (float)v[j], a = fabsf(w);
+      if (!(a <= 255.0f)) bad |= 1;                     // also true for NaN
+      o[j] = from_f32<f16>(w * kWeightScale);
+    }
     __syncthreads();                                    // the previous span has been read out
     tile[rr * 8 + (cc ^ (rr & 7))] = __builtin_bit_cast(u32x4, o);
     __syncthreads();
     const int sr = lane & 31, sc = 2 * blk + (lane >> 5);
     *(u32x4*)(dst + ((size_t)nb * (K >> 4) + (k0 >> 4) + blk) * 512 + lane * 8) = tile[sr * 8 + (sc ^ (sr & 7))];
   }
+  if (bad) atomicOr(range_flag, bad);
 }
 
-void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode,
+void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode, int* range_flag,
                      hipStream_t st) {
   // rows, row0 multiples of 32 and K a multiple of 64: guaranteed by the configuration checks
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)(rows / 32), (unsigned)((K + 511) / 512)), dim3(256), 0, st,
-                     src, K, dst, row0, interleave_mode);
+                     src, K, dst, row0, interleave_mode, range_flag);
 }
 
 }  // namespace vla

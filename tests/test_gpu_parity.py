@@ -27,9 +27,9 @@ def make_policy(wl, weights, max_batch=None, extra_seq=0, fast=False):
 FAST_MODES = pytest.mark.parametrize("fast", [False, True], ids=["two_term", "fast"])
 
 
-def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, offset=None, fast=False):
+def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, offset=None, fast=False, weights=None):
     import torch
-    weights = W.make_weights(wl.shape, wl.seed)
+    weights = weights if weights is not None else W.make_weights(wl.shape, wl.seed)
     obs = obs or W.make_observations(wl)
     pol = make_policy(wl, weights, fast=fast)
     dev = P.device_inputs(pol, obs, gumbel)
