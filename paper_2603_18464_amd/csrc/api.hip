@@ -27,6 +27,7 @@ constexpr int kMaxDevices = 64;
 
 struct LayerW {
   size_t g_attn, w_qkv, w_o, g_ffn, w_gu, w_down;   // byte offsets into the weight arena
+  size_t w_qkv8, w_o8, w_down8;                     // 8-bit copies for 8-bit low terms (two-term mode), else unused
 };
 struct ArenaLayout {
   size_t embed, g_final, head, total;
@@ -40,6 +41,16 @@ struct WorkLayout {
 };
 
 size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
+
+// Two-term mode of the 16-bit path: activations that feed a matrix core, and the cached keys and values, are
+// carried as hi + lo half-precision terms.
+inline bool two_term(const vla_config& c) { return c.dtype == VLA_BF16 && c.precision == VLA_PREC_HIGH; }
+// Row-major two-term operands of the prefill GEMMs with contraction length K carry their low terms as bytes (and
+// the GEMM uses the 8-bit copy of its weights for them) when K allows whole pairs of 64-k slabs; otherwise as
+// half precision.  Row pitch of such an operand in halves; mode as the producing kernels take it.
+inline bool lo8(const vla_config& c, int K) { return two_term(c) && K % 128 == 0; }
+inline int lo_mode(const vla_config& c, int K) { return !two_term(c) ? 0 : (lo8(c, K) ? 2 : 1); }
+inline int two_pitch(const vla_config& c, int K) { return !two_term(c) ? K : (lo8(c, K) ? K + K / 2 : 2 * K); }
 
 ArenaLayout arena_layout(const vla_config& c) {
   ArenaLayout a;
@@ -55,6 +66,9 @@ ArenaLayout arena_layout(const vla_config& c) {
     l.g_ffn = take(d * 4);
     l.w_gu = take(2 * f * d * es);
     l.w_down = take(d * f * es);
+    l.w_qkv8 = take(lo8(c, (int)d) ? 3 * d * d : 0);
+    l.w_o8 = take(lo8(c, (int)d) ? d * d : 0);
+    l.w_down8 = take(lo8(c, (int)f) ? d * f : 0);
   }
   a.g_final = take(d * 4);
   a.head = take((size_t)c.n_action_bins * d * es);
@@ -79,9 +93,6 @@ inline int kv_pitch(const vla_config& c) { return c.max_seq | 1; }
 size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one layer
   return (size_t)c.max_batch * c.n_heads * kv_pitch(c) * c.head_dim;
 }
-// Two-term mode of the 16-bit path: activations that feed a matrix core, and the cached keys and values, are
-// carried as hi + lo half-precision terms.
-inline bool two_term(const vla_config& c) { return c.dtype == VLA_BF16 && c.precision == VLA_PREC_HIGH; }
 // one set of planes [layer][K|V][slot][head][position][head_dim]; two-term mode appends a second set with the low terms
 size_t kv_plane_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
 size_t kv_bytes(const vla_config& c) { return kv_plane_bytes(c) * (two_term(c) ? 2 : 1); }
@@ -301,8 +312,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const int d = c.d_model, f = c.d_ffn;
-  const bool two = two_term(c);
-  const int t2 = two ? 2 : 1;
+  const int pd = two_pitch(c, d), pf = two_pitch(c, f);     // row pitch of two-term operands with K = d, f
+  const f16* no8 = nullptr;
   float* x = at<float>(ctx->work, w.x);
   T* hn = at<T>(ctx->work, w.hn);
   T* q = at<T>(ctx->work, w.q);
@@ -318,12 +329,13 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     const RopeKv rk = layer_rope_kv(ctx, l);
     {
       ProfScope ps(ctx, FAM_NORM, st);
-      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, two, st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, lo_mode(c, d), st);
     }
     {
       ProfScope ps(ctx, fam_gemm + 0, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_qkv(GemmF16{(const f16*)hn, t2 * d, at<f16>(ctx->arena, lw.w_qkv), rows, 3 * d, t2 * d, d}, rk, st);
+        gemm_f16_qkv(GemmF16{(const f16*)hn, pd, at<f16>(ctx->arena, lw.w_qkv), rows, 3 * d, pd, d,
+                             lo8(c, d) ? at<f16>(ctx->arena, lw.w_qkv8) : no8}, rk, st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_qkv), gemm_out, rows, 3 * d, d, st);
         rope_kv_f32(gemm_out, rows, rk, st);
@@ -332,9 +344,9 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     {
       ProfScope ps(ctx, fam_attn, st);
       if constexpr (sizeof(T) == 2) {
-        flash_prefill((const f16*)q, t2 * d, (const f16*)rk.k_cache, (const f16*)rk.v_cache, (const f16*)rk.k_lo,
+        flash_prefill((const f16*)q, rk.ldq, (const f16*)rk.k_cache, (const f16*)rk.v_cache, (const f16*)rk.k_lo,
                       (const f16*)rk.v_lo, at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr),
-                      ctx->run_slots, (f16*)att, t2 * d, ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim,
+                      ctx->run_slots, (f16*)att, pd, lo8(c, d), ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim,
                       kv_pitch(c), st);
       } else {
         attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
@@ -354,7 +366,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     {
       ProfScope ps(ctx, fam_gemm + 1, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_resid(GemmF16{(const f16*)att, t2 * d, at<f16>(ctx->arena, lw.w_o), rows, d, t2 * d, d}, x, d, st);
+        gemm_f16_resid(GemmF16{(const f16*)att, pd, at<f16>(ctx->arena, lw.w_o), rows, d, pd, d,
+                               lo8(c, d) ? at<f16>(ctx->arena, lw.w_o8) : no8}, x, d, st);
       } else {
         gemm_f32((const float*)att, d, at<float>(ctx->arena, lw.w_o), gemm_out, rows, d, d, st);
         resid_add_f32(x, gemm_out, (size_t)rows * d, st);
@@ -362,13 +375,13 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     }
     {
       ProfScope ps(ctx, FAM_NORM, st);
-      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, false, st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, 0, st);
     }
     {
       ProfScope ps(ctx, fam_gemm + 2, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_swiglu(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, d, d}, (f16*)act, t2 * f,
-                        two ? f : 0, st);
+        gemm_f16_swiglu(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, d, d, no8}, (f16*)act, pf,
+                        lo_mode(c, f), st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_gu), gemm_out, rows, 2 * f, d, st);
         swiglu_f32(gemm_out, (float*)act, rows, f, st);
@@ -377,7 +390,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     {
       ProfScope ps(ctx, fam_gemm + 3, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_resid(GemmF16{(const f16*)act, t2 * f, at<f16>(ctx->arena, lw.w_down), rows, d, t2 * f, f}, x, d, st);
+        gemm_f16_resid(GemmF16{(const f16*)act, pf, at<f16>(ctx->arena, lw.w_down), rows, d, pf, f,
+                               lo8(c, f) ? at<f16>(ctx->arena, lw.w_down8) : no8}, x, d, st);
       } else {
         gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), gemm_out, rows, d, f, st);
         resid_add_f32(x, gemm_out, (size_t)rows * d, st);
@@ -478,7 +492,7 @@ void run_tail_f16(vla_ctx* ctx, const LayerW& lw, const int32_t* need, int n_nee
                                         align_up(pad32 * f * sizeof(f16)));
   const int ks_o = skinny_ksplit(d, d), ks_gu = skinny_ksplit(2 * f, d), ks_dn = skinny_ksplit(d, f);
   const int chunk = (int)(part_rows(c) < (size_t)kSkinnyMaxRows ? part_rows(c) : (size_t)kSkinnyMaxRows);
-  gather_tail(att, two ? 2 * d : d, x, need, n_need, d, att_frag, att_frag_lo, x_c, st);
+  gather_tail(att, two_pitch(c, d), lo8(c, d), x, need, n_need, d, att_frag, att_frag_lo, x_c, st);
   for (int r0 = 0; r0 < n_need; r0 += chunk) {
     const int m = n_need - r0 < chunk ? n_need - r0 : chunk;
     skinny_gemm(frag_rows(att_frag, r0, d), two ? frag_rows(att_frag_lo, r0, d) : nullptr, at<f16>(ctx->arena, lw.w_o),
@@ -930,9 +944,11 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
     if (bf) convert_copy<bf16>((const bf16*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
     else convert_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
   };
-  auto matrix = [&](size_t off, int64_t rows, int64_t K, int64_t row0, int mode) {
+  // off8: where the 8-bit copy of the same (fused) matrix starts, used when its low terms are 8-bit
+  auto matrix = [&](size_t off, size_t off8, int64_t rows, int64_t K, int64_t row0, int mode) {
     if (bf) {
-      pack_weight_f16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<f16>(ctx->arena, off), (int)row0, mode,
+      pack_weight_f16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<f16>(ctx->arena, off),
+                      (mode == 0 && lo8(c, (int)K)) ? at<unsigned char>(ctx->arena, off8) : nullptr, (int)row0, mode,
                       at<int32_t>(ctx->work, ctx->wl.range_flag), st);
     } else {
       const int64_t r0 = mode == 2 ? rows : row0;   // float32 path keeps [gate rows | up rows]
@@ -953,14 +969,14 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
     const LayerW& lw = a.layers[(s - 3) / 9];
     switch ((s - 3) % 9) {
       case 0: to_f32(lw.g_attn, d); break;
-      case 1: matrix(lw.w_qkv, d, d, 0, 0); break;
-      case 2: matrix(lw.w_qkv, d, d, d, 0); break;
-      case 3: matrix(lw.w_qkv, d, d, 2 * d, 0); break;
-      case 4: matrix(lw.w_o, d, d, 0, 0); break;
+      case 1: matrix(lw.w_qkv, lw.w_qkv8, d, d, 0, 0); break;
+      case 2: matrix(lw.w_qkv, lw.w_qkv8, d, d, d, 0); break;
+      case 3: matrix(lw.w_qkv, lw.w_qkv8, d, d, 2 * d, 0); break;
+      case 4: matrix(lw.w_o, lw.w_o8, d, d, 0, 0); break;
       case 5: to_f32(lw.g_ffn, d); break;
-      case 6: matrix(lw.w_gu, f, d, 0, 1); break;
-      case 7: matrix(lw.w_gu, f, d, 0, 2); break;
-      default: matrix(lw.w_down, d, f, 0, 0); break;
+      case 6: matrix(lw.w_gu, 0, f, d, 0, 1); break;     // the rows that feed gate / up stay single-term
+      case 7: matrix(lw.w_gu, 0, f, d, 0, 2); break;
+      default: matrix(lw.w_down, lw.w_down8, d, f, 0, 0); break;
     }
   } else {
     switch (s - np) {

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
     const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
     const f16* __restrict__ k_lo, const f16* __restrict__ v_lo, const int32_t* __restrict__ cu_patch,
     const int32_t* __restrict__ cu_instr, const int32_t* __restrict__ slot_map, f16* __restrict__ out, int ldo,
-    int n_heads, int max_seq, int lo_off) {
+    int n_heads, int max_seq, int lo_off, int out_lo8) {
   constexpr int KS = HD / 16;          // k-steps of the QK^T contraction
   constexpr int DT = HD / 32;          // 32-row tiles of O^T
   constexpr int KCH = HD / 8;          // 16-byte chunks per key row
@@ -282,28 +282,37 @@ __global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
       for (int i = 0; i < 4; ++i) {
         typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
         f16x4 w, we;
+        float e[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float v = o[dt][4 * i + r] * inv;
           w[r] = from_f32<f16>(v);
-          we[r] = from_f32<f16>(v - (float)w[r]);
+          e[r] = v - (float)w[r];
+          we[r] = from_f32<f16>(e[r]);
         }
         *(f16x4*)(orow + dt * 32 + 8 * i + 4 * half) = w;
-        if constexpr (TWO) *(f16x4*)(orow + lo_off + dt * 32 + 8 * i + 4 * half) = we;
+        if constexpr (TWO) {
+          if (out_lo8)                                     // 8-bit low terms: bytes behind the row's lo_off high terms
+            *(int*)((unsigned char*)(out + (size_t)(row0 + qpos) * ldo + lo_off) + head * HD + dt * 32 + 8 * i + 4 * half) =
+                pack_lo8(e[0], e[1], e[2], e[3]);
+          else
+            *(f16x4*)(orow + lo_off + dt * 32 + 8 * i + 4 * half) = we;
+        }
       }
   }
 }
 
 // k_lo / v_lo != nullptr selects the two-term kernel: q rows are [hi | lo] of pitch ldq with the low terms at
-// column lo_off = d_model, and so are the output rows (pitch ldo).
+// column lo_off = d_model, and so are the output rows (pitch ldo), unless out_lo8 asks for 8-bit low terms (bytes
+// behind the d_model high terms of each row).
 void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
-                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B,
-                   int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st) {
+                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo,
+                   bool out_lo8, int B, int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st) {
   const dim3 grid((max_len + 127) / 128, B, n_heads);
   const int lo_off = n_heads * head_dim;
 #define VLA_FLASH(HDV, TWOV)                                                                                       \
   hipLaunchKernelGGL((flash_prefill_kernel<HDV, TWOV>), grid, dim3(256), 0, st, q, ldq, k_cache, v_cache, k_lo, v_lo, \
-                     cu_patch, cu_instr, slot_map, out, ldo, n_heads, max_seq, lo_off)
+                     cu_patch, cu_instr, slot_map, out, ldo, n_heads, max_seq, lo_off, out_lo8 ? 1 : 0)
   if (k_lo) {
     if (head_dim == 128) VLA_FLASH(128, true);
     else VLA_FLASH(64, true);

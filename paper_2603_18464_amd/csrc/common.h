@@ -87,9 +87,35 @@ struct GemmF16 {
   const f16* A;    // [M, K] row-major activations
   int lda;
   const f16* Wp;   // [N, Kw] weights * kWeightScale in MFMA fragment order (see pack_weight_f16)
-  int M, N, K;     // K = Kw (single-term A) or 2 * Kw (two-term A)
-  int Kw;
+  int M, N, K;     // K = Kw (single-term A), 2 * Kw (two-term A, half-precision low terms) or, with W8, 1.5 * Kw
+  int Kw;          //   (two-term A whose low terms are bytes: row = [hi: Kw halves | lo8: Kw bytes]; Kw % 128 == 0)
+  const f16* W8;   // 8-bit copy of the weights for 8-bit low terms (see gemm_f16.hip), or nullptr
 };
+// 8-bit low terms (see gemm_f16.hip): lo8 = bf8(16 * (a - f16(a))), four at a time.
+constexpr float kLo8Scale = 16.0f;
+__device__ __forceinline__ int pack_lo8(float e0, float e1, float e2, float e3) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  int p = __builtin_amdgcn_cvt_pk_bf8_f32(e0 * kLo8Scale, e1 * kLo8Scale, 0, false);
+  return __builtin_amdgcn_cvt_pk_bf8_f32(e2 * kLo8Scale, e3 * kLo8Scale, p, true);
+#else
+  return 0;
+#endif
+}
+__device__ __forceinline__ float unpack_lo8(int word, int byte) {   // byte must be a compile-time constant 0..3
+#if defined(__HIP_DEVICE_COMPILE__)
+  float v;
+  switch (byte) {
+    case 0: v = __builtin_amdgcn_cvt_f32_bf8(word, 0); break;
+    case 1: v = __builtin_amdgcn_cvt_f32_bf8(word, 1); break;
+    case 2: v = __builtin_amdgcn_cvt_f32_bf8(word, 2); break;
+    default: v = __builtin_amdgcn_cvt_f32_bf8(word, 3); break;
+  }
+  return v * (1.0f / kLo8Scale);
+#else
+  return 0.f;
+#endif
+}
+
 // Rotation of one pair by (cos, sin), written with explicit roundings: every kernel that applies it (the two
 // epilogue forms of the QKV GEMM, the decode step) then produces the same float32 bits, which two-term outputs
 // make visible.
@@ -100,12 +126,13 @@ __device__ __forceinline__ void rope_pair(float lo, float hi, float cs, float sn
 
 // C = A * W^T with fused epilogues (f16 MFMA, fp32 accumulation).
 void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st);           // x += C
-// silu(gate)*up; lo_off > 0: also the low terms, at column lo_off + j
-void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, int lo_off, hipStream_t st);
+// silu(gate)*up; lo_mode 1: also half-precision low terms at column f + j; 2: 8-bit low terms, bytes behind the f halves
+void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, int lo_mode, hipStream_t st);
 void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st);               // RoPE + cache
-// range_flag: device int, bits are OR-ed in when a weight cannot be re-encoded exactly (see pack_weight_kernel)
-void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode, int* range_flag,
-                     hipStream_t st);
+// range_flag: device int, bits are OR-ed in when a weight cannot be re-encoded exactly (see pack_weight_kernel);
+// dst8 != nullptr: also the 8-bit copy fp8(w * 16) for 8-bit low terms (K % 64 == 0)
+void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, unsigned char* dst8, int row0, int interleave_mode,
+                     int* range_flag, hipStream_t st);
 
 // fp32 path (plain, unfused).
 void gemm_f32(const float* A, int lda, const float* W, float* C, int M, int N, int K, hipStream_t st);
@@ -116,7 +143,8 @@ void swiglu_f32(const float* gu, float* act, int T, int f, hipStream_t st);
 // Row-wise kernels.
 template <class T>
 void rmsnorm(const float* x, const T* /*unused tag*/, const float* gain, T* out, int rows, int d,
-             float eps, const int32_t* row_index, bool two_term /* rows [hi | lo] of 2 d */, hipStream_t st);
+             float eps, const int32_t* row_index, int lo_mode /* 0: rows of d; 1: [hi | lo] of 2 d; 2: [hi | lo8] of 1.5 d */,
+             hipStream_t st);
 template <class T>
 void assemble_prefix(const T* patch_emb, const int32_t* instr_ids, const T* embed,
                      const int32_t* tok_src, float* x, int T_tokens, int d, int vocab, hipStream_t st);
@@ -132,11 +160,11 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
 // Prefill attention for the 16-bit path: causal flash attention over whole prefixes (MFMA).
 // cu_patch / cu_instr are the device copies of the cumulative offsets; max_len = longest prefix; slot_map
 // (device, [B], or nullptr for the identity) gives the cache slot of each sequence of the call.
-// k_lo / v_lo (low terms of the cache) != nullptr: two-term mode, q and out rows are [hi | lo] with the low terms
-// at column d_model.
+// k_lo / v_lo (low terms of the cache) != nullptr: two-term mode, q rows are [hi | lo] with the low terms at column
+// d_model, and so are the output rows, or (out_lo8) [hi | 8-bit low terms].
 void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
-                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo, int B,
-                   int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st);
+                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo,
+                   bool out_lo8, int B, int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st);
 
 // Decode-step GEMMs (M <= 128): weight-streaming split-K kernel writing partial sums, and the kernels
 // that add the partials in a fixed order and apply the elementwise step that follows each GEMM.
@@ -182,9 +210,10 @@ void value_finish(const float* vz, const float* vml, const T* step_emb, int n_st
                   float* values, hipStream_t st);
 
 // Last prefill layer, compact rows: gather attention output (to fragment order) and residual rows, scatter back.
-// att_frag_lo != nullptr: att rows are [hi | lo] (pitch ld_att), the low terms go to att_frag_lo
-void gather_tail(const f16* att, int ld_att, const float* x, const int32_t* need, int n, int d, f16* att_frag,
-                 f16* att_frag_lo, float* x_c, hipStream_t st);
+// att_frag_lo != nullptr: att rows are [hi | lo] (pitch ld_att; lo8: the low terms are bytes), the low terms go to
+// att_frag_lo as half precision
+void gather_tail(const f16* att, int ld_att, bool lo8, const float* x, const int32_t* need, int n, int d,
+                 f16* att_frag, f16* att_frag_lo, float* x_c, hipStream_t st);
 void scatter_tail(const float* x_c, const int32_t* need, int n, int d, float* x, hipStream_t st);
 
 // Chunk pass (all K action rows in one forward): merged id stream, fed-token buffer, emitting rows, scoring.

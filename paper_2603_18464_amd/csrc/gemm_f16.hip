@@ -91,7 +91,8 @@ struct EpiResid {
 struct EpiSwiglu {
   f16* act;
   int ld;
-  int lo_off;   // two-term mode: the low term of act[m][j] goes to act[m][lo_off + j] (0: single-term)
+  int f;        // number of outputs per row
+  int lo_mode;  // 0: single-term; 1: half-precision low terms at act[m][f + j]; 2: bytes at ((char*)&act[m][f])[j]
   // the 128 tile columns are [gate 32 | up 32 | gate 32 | up 32] -> 64 outputs per row
   __device__ __forceinline__ void consume(const float* tile, int m_base, int nb, int lane, int M) const {
     typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
@@ -102,15 +103,19 @@ struct EpiSwiglu {
       const f32x4 g = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + c4) * (1.0f / kWeightScale);
       const f32x4 u = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + 32 + c4) * (1.0f / kWeightScale);
       f16x4 o, oe;
+      float e[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float a = g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j])) * u[j];
         o[j] = from_f32<f16>(a);
-        oe[j] = from_f32<f16>(a - (float)o[j]);
+        e[j] = a - (float)o[j];
+        oe[j] = from_f32<f16>(e[j]);
       }
       if (m < M) {
-        *(f16x4*)(act + (size_t)m * ld + nb / 2 + jb * 32 + c4) = o;
-        if (lo_off) *(f16x4*)(act + (size_t)m * ld + lo_off + nb / 2 + jb * 32 + c4) = oe;
+        f16* row = act + (size_t)m * ld;
+        *(f16x4*)(row + nb / 2 + jb * 32 + c4) = o;
+        if (lo_mode == 1) *(f16x4*)(row + f + nb / 2 + jb * 32 + c4) = oe;
+        if (lo_mode == 2) *(int*)((unsigned char*)(row + f) + nb / 2 + jb * 32 + c4) = pack_lo8(e[0], e[1], e[2], e[3]);
       }
     }
   }
@@ -134,7 +139,10 @@ struct EpiSwiglu {
               const float a = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
               const f16 a16 = from_f32<f16>(a);
               row[j * 32] = a16;
-              if (lo_off) row[lo_off + j * 32] = from_f32<f16>(a - (float)a16);
+              if (lo_mode == 1) row[f + j * 32] = from_f32<f16>(a - (float)a16);
+              if (lo_mode == 2)
+                ((unsigned char*)(act + (size_t)m * ld + f))[nb / 2 + c + j * 32] =
+                    (unsigned char)(pack_lo8(a - (float)a16, 0.f, 0.f, 0.f) & 0xff);
             }
           }
         }
@@ -271,11 +279,35 @@ struct EpiQkv {
   }
 };
 
+// ---- 8-bit low terms --------------------------------------------------------------------------------------
+// Two-term activations may carry their low term as one byte: lo8 = bf8(16 * (a - f16(a))) (1-5-2 format), stored
+// behind the high terms of the same row, A row = [hi: Kw halves | lo8: Kw bytes].  The low-term product then runs
+// on v_mfma_f32_32x32x64 in 8-bit formats (twice the rate of the half-precision instruction) against a second
+// copy of the weights, W8 = fp8(w * 16) (1-4-3 format, saturating at +-448, i.e. |w| = 28), so that
+// lo8 * W8 = 2^8 * lo * w lands in the same accumulator as hi * (w * 2^8).  The correction term only has to be good
+// to a few percent (it is itself 2^-12 of the result), which three and two mantissa bits give.
+// Layout: a 64-byte row slab of lo8 has the geometry of a 32-half slab of hi (64-byte rows), and W8 is packed so
+// that its 64-k slab of a 32-row block is two 1 KiB pieces, lane (n, g) of piece j holding k = 32 j + 16 g .. + 15;
+// a lane's operand is its 16 bytes of "k-step 0" followed by its 16 bytes of "k-step 1", for both operands.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+__device__ __forceinline__ f32x16 mfma_lo8(const f16x8& a0, const f16x8& a1, const f16x8& b0, const f16x8& b1,
+                                           const f32x16& c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const i32x8 a = __builtin_shufflevector(__builtin_bit_cast(i32x4, a0), __builtin_bit_cast(i32x4, a1), 0, 1, 2, 3, 4, 5, 6, 7);
+  const i32x8 b = __builtin_shufflevector(__builtin_bit_cast(i32x4, b0), __builtin_bit_cast(i32x4, b1), 0, 1, 2, 3, 4, 5, 6, 7);
+  // A: bf8 (format 1), B: fp8 (format 0), no block scales
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 1, 0, 0, 0, 0, 0);
+#else
+  return c;
+#endif
+}
+
 // ---- kernel -----------------------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN, class Epi>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
-    const f16* __restrict__ A, int lda, const f16* __restrict__ Wp, int M, int N, int K, int Kw,
-    int tiles_m, int tiles_n, Epi epi) {
+    const f16* __restrict__ A, int lda, const f16* __restrict__ Wp, const f16* __restrict__ W8, int M, int N, int K,
+    int Kw, int tiles_m, int tiles_n, Epi epi) {
   constexpr int NTHR = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
   constexpr int A_ITERS = BM * 8 / NTHR;   // 16-byte chunks of the A slab per thread
@@ -303,7 +335,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int KB16 = Kw >> 4, KT = K / BK, KTw = Kw / BK;   // K == 2 * Kw: two-term A, the weight slabs wrap
+  // K == 2 * Kw: two-term A with half-precision low terms, the weight slabs wrap; K == 1.5 * Kw and W8: 8-bit low
+  // terms (128 k per slab) against W8
+  const int KB16 = Kw >> 4, KT = K / BK, KTw = Kw / BK;
 
   // Global -> register -> LDS staging.  Thread t moves 16-byte chunks: chunk (t & 7) of rows
   // (t >> 3) + i * NTHR/8 of the A slab (XOR-swizzled on the way into LDS), and the linear chunks
@@ -319,6 +353,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
   for (int i = 0; i < W_ITERS; ++i) {
     const int q = t + i * NTHR;
     w_ptr[i] = Wp + ((size_t)(n0 / 32 + (q >> 8)) * KB16) * 512 + (q & 255) * 8;
+  }
+  const f16* w8_ptr[W_ITERS];
+#pragma unroll
+  for (int i = 0; i < W_ITERS; ++i) {
+    const int q = t + i * NTHR;
+    w8_ptr[i] = W8 + ((size_t)(n0 / 32 + (q >> 8)) * KB16) * 256 + (q & 255) * 8;
   }
 
   f32x16 acc[MT][NT];
@@ -356,10 +396,37 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_f16_kernel(
     for (int i = 0; i < A_ITERS; ++i) ra[i] = *(const u32x4*)(a_ptr[i] + kn * BK);
     const int knw = kn >= KTw ? kn - KTw : kn;
 #pragma unroll
-    for (int i = 0; i < W_ITERS; ++i) rw[i] = *(const u32x4*)(w_ptr[i] + (size_t)knw * 4 * 512);
+    for (int i = 0; i < W_ITERS; ++i)
+      rw[i] = *(const u32x4*)((W8 && kn >= KTw ? w8_ptr[i] : w_ptr[i]) + (size_t)knw * 4 * 512);
     __builtin_amdgcn_sched_barrier(0);   // keep the prefetch at the top: its latency hides under the MFMAs
     const f16* as = As + (kt & 1) * BM * BK;
     const f16* ws = Ws + (kt & 1) * BN * BK + w_off;
+    if (W8 && kt >= KTw) {               // a slab of 8-bit low terms: two 64-k products per accumulator tile
+      f16x8 a4[4][MT], b4[4][NT];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a4[kk][mt] = *(const f16x8*)(as + a_off[kk] + mt * 32 * BK);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) b4[kk][nt] = *(const f16x8*)(ws + (nt * 4 + kk) * 512);
+      }
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[mt][nt] = mfma_lo8(a4[2 * m][mt], a4[2 * m + 1][mt], b4[2 * m][nt], b4[2 * m + 1][nt], acc[mt][nt]);
+      __builtin_amdgcn_sched_barrier(0);
+      f16* asn = As + ((kt + 1) & 1) * BM * BK;
+      f16* wsn = Ws + ((kt + 1) & 1) * BN * BK;
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i) *(u32x4*)(asn + a_dst + i * (NTHR / 8) * BK) = ra[i];
+#pragma unroll
+      for (int i = 0; i < W_ITERS; ++i) *(u32x4*)(wsn + (t + i * NTHR) * 8) = rw[i];
+      __syncthreads();
+      continue;
+    }
     f16x8 af[2][MT], bfr[2][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) af[0][mt] = *(const f16x8*)(as + a_off[0] + mt * 32 * BK);
@@ -536,7 +603,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 template <int WGM, int WGN, class Epi>
 __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const f16* __restrict__ A, int lda,
-                                                                         const f16* __restrict__ Wp, int M, int N,
+                                                                         const f16* __restrict__ Wp,
+                                                                         const f16* __restrict__ W8, int M, int N,
                                                                          int K, int Kw, int tiles_m, int tiles_n,
                                                                          Epi epi) {
   constexpr int BM = 256, BN = 256, NW = WGM * WGN;
@@ -565,7 +633,9 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
-  const int KB16 = Kw >> 4, KT = K / PK, KTw = Kw / PK;   // K == 2 * Kw: two-term A, the weight slabs wrap
+  // K == 2 * Kw: two-term A with half-precision low terms, the weight slabs wrap; K == 1.5 * Kw and W8: 8-bit low
+  // terms, whose slabs (64 k each, same bytes as a 32-k slab of halves) come after the KTw slabs of high terms
+  const int KB16 = Kw >> 4, KT = K / PK, KTw = Kw / PK;
 
   const f16* a_src[A_INSTR];
 #pragma unroll
@@ -580,16 +650,24 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
     const int j = wave * W_INSTR + i;                    // KiB of the slab: block row j/2, k-step j%2
     w_src[i] = Wp + ((size_t)(n0 / 32 + (j >> 1)) * KB16 + (j & 1)) * 512 + lane * 8;
   }
+  const f16* w8_src[W_INSTR];
+#pragma unroll
+  for (int i = 0; i < W_INSTR; ++i) {
+    const int j = wave * W_INSTR + i;
+    w8_src[i] = W8 + (size_t)(n0 / 32 + (j >> 1)) * KB16 * 256 + (j & 1) * 512 + lane * 8;
+  }
+  auto w_slab = [&](int i, int ks) {                     // source of the i-th weight load of slab ks
+    return ks < KTw ? w_src[i] + (size_t)ks * 2 * 512 : (W8 ? w8_src[i] : w_src[i]) + (size_t)(ks - KTw) * 2 * 512;
+  };
   auto issue = [&](int kt) {                             // slab kt (clamped) into buffer kt % 4
     const int buf = kt & (P_STAGES - 1);
     const int ks = min(kt, KT - 1);
-    const int ksw = ks >= KTw ? ks - KTw : ks;
     f16* as = As + buf * P_STAGE_HALVES + wave * A_INSTR * 512;
     f16* ws = Ws + buf * P_STAGE_HALVES + wave * W_INSTR * 512;
 #pragma unroll
     for (int i = 0; i < A_INSTR; ++i) load_to_lds_16(a_src[i] + (size_t)ks * PK, as + i * 512);
 #pragma unroll
-    for (int i = 0; i < W_INSTR; ++i) load_to_lds_16(w_src[i] + (size_t)ksw * 2 * 512, ws + i * 512);
+    for (int i = 0; i < W_INSTR; ++i) load_to_lds_16(w_slab(i, ks), ws + i * 512);
   };
 
   f32x16 acc[MT][NT];
@@ -621,8 +699,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
     if (i < A_INSTR)
       load_to_lds_16(a_src[i] + (size_t)ks * PK, As + buf * P_STAGE_HALVES + (wave * A_INSTR + i) * 512);
     else
-      load_to_lds_16(w_src[i - A_INSTR] + (size_t)(ks >= KTw ? ks - KTw : ks) * 2 * 512,
-                     Ws + buf * P_STAGE_HALVES + (wave * W_INSTR + i - A_INSTR) * 512);
+      load_to_lds_16(w_slab(i - A_INSTR, ks), Ws + buf * P_STAGE_HALVES + (wave * W_INSTR + i - A_INSTR) * 512);
   };
   auto step = [&](int kt, int f) {           // f = kt & 1, passed as a constant by the unrolled caller
     wait_vmcnt<LPS>();                       // this wave's loads of slab kt+1 have landed (kt+2 may be in flight)
@@ -704,6 +781,48 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
     }
     if constexpr (NW == 8) frags_arrived(af[f ^ 1], bfr[f ^ 1]);
   };
+  // The same step for a slab of 8-bit low terms: one 64-k product per accumulator tile (as long as two of the
+  // half-precision ones), operands = the lane's k-step 0 and k-step 1 fragments of the slab taken together.  All
+  // fragment reads of slab kt+1 go into the first half of the step, so they have landed when it ends.
+  auto step8 = [&](int kt, int f) {
+    wait_vmcnt<LPS>();
+    __builtin_amdgcn_s_barrier();
+    frags_arrived(af[f], bfr[f]);            // both k-steps of slab kt are needed at once
+    const unsigned so = stage_off(kt + 1);
+    const unsigned ra0 = a_k0 + so, ra1 = a_k1 + so, rw = w_b + so;
+#define VLA_MF8(mt, nt) acc[mt][nt] = mfma_lo8(af[f][0][mt], af[f][1][mt], bfr[f][0][nt], bfr[f][1][nt], acc[mt][nt])
+#define VLA_SB __builtin_amdgcn_sched_barrier(0)
+    if constexpr (NW == 8) {
+      VLA_MF8(0, 0); read_frag_asm<0>(af[f ^ 1][0][0], ra0); read_frag_asm<0>(bfr[f ^ 1][0][0], rw); VLA_SB;
+      VLA_MF8(0, 1); read_frag_asm<2048>(af[f ^ 1][0][1], ra0); read_frag_asm<2048>(bfr[f ^ 1][0][1], rw); VLA_SB;
+      VLA_MF8(0, 2); read_frag_asm<4096>(bfr[f ^ 1][0][2], rw); read_frag_asm<6144>(bfr[f ^ 1][0][3], rw); VLA_SB;
+      VLA_MF8(0, 3); read_frag_asm<0>(af[f ^ 1][1][0], ra1); read_frag_asm<2048>(af[f ^ 1][1][1], ra1); VLA_SB;
+      VLA_MF8(1, 0); read_frag_asm<1024>(bfr[f ^ 1][1][0], rw); read_frag_asm<3072>(bfr[f ^ 1][1][1], rw); VLA_SB;
+      VLA_MF8(1, 1); read_frag_asm<5120>(bfr[f ^ 1][1][2], rw); read_frag_asm<7168>(bfr[f ^ 1][1][3], rw); VLA_SB;
+      VLA_MF8(1, 2); issue_one(kt + 3, 0); issue_one(kt + 3, 1); VLA_SB;
+      VLA_MF8(1, 3); issue_one(kt + 3, 2); issue_one(kt + 3, 3); VLA_SB;
+    } else {
+      VLA_MF8(0, 0); read_frag_asm<0>(af[f ^ 1][0][0], ra0); read_frag_asm<0>(bfr[f ^ 1][0][0], rw); VLA_SB;
+      VLA_MF8(0, 1); read_frag_asm<2048>(af[f ^ 1][0][1], ra0); read_frag_asm<2048>(bfr[f ^ 1][0][1], rw); VLA_SB;
+      VLA_MF8(0, 2); read_frag_asm<4096>(af[f ^ 1][0][2], ra0); read_frag_asm<4096>(bfr[f ^ 1][0][2], rw); VLA_SB;
+      VLA_MF8(0, 3); read_frag_asm<6144>(af[f ^ 1][0][3], ra0); read_frag_asm<6144>(bfr[f ^ 1][0][3], rw); VLA_SB;
+      VLA_MF8(1, 0); read_frag_asm<0>(af[f ^ 1][1][0], ra1); read_frag_asm<1024>(bfr[f ^ 1][1][0], rw); VLA_SB;
+      VLA_MF8(1, 1); read_frag_asm<2048>(af[f ^ 1][1][1], ra1); read_frag_asm<3072>(bfr[f ^ 1][1][1], rw); VLA_SB;
+      VLA_MF8(1, 2); read_frag_asm<4096>(af[f ^ 1][1][2], ra1); read_frag_asm<5120>(bfr[f ^ 1][1][2], rw); VLA_SB;
+      VLA_MF8(1, 3); read_frag_asm<6144>(af[f ^ 1][1][3], ra1); read_frag_asm<7168>(bfr[f ^ 1][1][3], rw); VLA_SB;
+      VLA_MF8(2, 0); issue_one(kt + 3, 0); VLA_SB;
+      VLA_MF8(2, 1); issue_one(kt + 3, 1); VLA_SB;
+      VLA_MF8(2, 2); issue_one(kt + 3, 2); VLA_SB;
+      VLA_MF8(2, 3); issue_one(kt + 3, 3); VLA_SB;
+      VLA_MF8(3, 0); issue_one(kt + 3, 4); VLA_SB;
+      VLA_MF8(3, 1); issue_one(kt + 3, 5); VLA_SB;
+      VLA_MF8(3, 2); issue_one(kt + 3, 6); VLA_SB;
+      VLA_MF8(3, 3); issue_one(kt + 3, 7); VLA_SB;
+    }
+#undef VLA_MF8
+#undef VLA_SB
+    frags_arrived(af[f ^ 1], bfr[f ^ 1]);
+  };
   issue(0);
   issue(1);
   issue(2);
@@ -711,9 +830,14 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   __builtin_amdgcn_s_barrier();
   read_frags_asm(af[0], bfr[0], a_k0, a_k1, w_b);
   frags_arrived(af[0], bfr[0]);
-  for (int kt = 0; kt < KT; kt += 2) {       // K is a multiple of 64: KT is even
+  const int KTh = W8 ? KTw : KT;             // slabs of half-precision terms; the rest are 8-bit low terms
+  for (int kt = 0; kt < KTh; kt += 2) {      // Kw is a multiple of 64: an even number of slabs
     step(kt, 0);
     step(kt + 1, 1);
+  }
+  for (int kt = KTh; kt < KT; kt += 2) {     // Kw a multiple of 128 (the launcher checks): again an even number
+    step8(kt, 0);
+    step8(kt + 1, 1);
   }
   if constexpr (NW == 4) {                   // the last step leaves eight fragment reads in flight: they must land
     frags_arrived(af[0], bfr[0]);            // before the registers they write are used for anything else
@@ -743,8 +867,8 @@ static void launch_pipe(const GemmF16& g, const Epi& epi, hipStream_t st) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, g.Kw, tiles_m,
-                     tiles_n, epi);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.W8, g.M, g.N, g.K, g.Kw,
+                     tiles_m, tiles_n, epi);
 }
 
 template <int BM, int BN, int WGM, int WGN, class Epi>
@@ -759,7 +883,7 @@ static void launch(const GemmF16& g, const Epi& epi, hipStream_t st) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.M, g.N, g.K, g.Kw,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.W8, g.M, g.N, g.K, g.Kw,
                      tiles_m, tiles_n, epi);
 }
 
@@ -782,8 +906,8 @@ static void dispatch(const GemmF16& g, const Epi& epi, hipStream_t st) {
 void gemm_f16_resid(const GemmF16& g, float* x, int ldx, hipStream_t st) {
   dispatch<true>(g, EpiResid{x, ldx}, st);
 }
-void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, int lo_off, hipStream_t st) {
-  dispatch<true>(g, EpiSwiglu{act, ldact, lo_off}, st);
+void gemm_f16_swiglu(const GemmF16& g, f16* act, int ldact, int lo_mode, hipStream_t st) {
+  dispatch<true>(g, EpiSwiglu{act, ldact, g.N / 2, lo_mode}, st);
 }
 void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st) {
   if (o.head_dim == 128) dispatch<false>(g, EpiQkv<128>{o}, st);
@@ -801,9 +925,11 @@ void gemm_f16_qkv(const GemmF16& g, const RopeKv& o, hipStream_t st) {
 // (At the other end nothing is reported: 0 < |w| < 2^-25 falls between half-precision subnormals and is rounded
 // with an absolute error below 2^-33, which is far below what any tolerance can see; random weights contain
 // such values.)
+// dst8 != nullptr: the same 32 x 64 spans also go, as fp8(w * 16) saturated at +-448, to the 8-bit copy
+// [n/32][k/64][2 KiB]: piece j (1 KiB) of a span holds, for lane (n, g), the 16 bytes k = 32 j + 16 g .. + 15.
 __global__ __launch_bounds__(256) void pack_weight_kernel(const bf16* __restrict__ src, int K,
-                                                          f16* __restrict__ dst, int row0, int mode,
-                                                          int* __restrict__ range_flag) {
+                                                          f16* __restrict__ dst, unsigned char* __restrict__ dst8,
+                                                          int row0, int mode, int* __restrict__ range_flag) {
   __shared__ u32x4 tile[32 * 8];
   const int r0 = blockIdx.x * 32;                       // first source row of this workgroup
   const int nb = mode == 0 ? (row0 + r0) >> 5 : (r0 >> 5) * 2 + (mode == 2 ? 1 : 0);
@@ -825,15 +951,32 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const bf16* __restrict
     __syncthreads();
     const int sr = lane & 31, sc = 2 * blk + (lane >> 5);
     *(u32x4*)(dst + ((size_t)nb * (K >> 4) + (k0 >> 4) + blk) * 512 + lane * 8) = tile[sr * 8 + (sc ^ (sr & 7))];
+    if (dst8) {
+#if defined(__HIP_DEVICE_COMPILE__)
+      const int j8 = t >> 7, l8 = (t >> 1) & 63, h8 = t & 1;       // piece, lane, 8-byte half of the lane's 16 bytes
+      const int n8 = l8 & 31, c8 = 4 * j8 + 2 * (l8 >> 5) + h8;    // row, 8-k chunk of the span
+      const f16x8 w8 = __builtin_bit_cast(f16x8, tile[n8 * 8 + (c8 ^ (n8 & 7))]);
+      float v8[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v8[j] = fminf(fmaxf((float)w8[j] * (kLo8Scale / kWeightScale), -448.0f), 448.0f);
+      int p0 = __builtin_amdgcn_cvt_pk_fp8_f32(v8[0], v8[1], 0, false);
+      p0 = __builtin_amdgcn_cvt_pk_fp8_f32(v8[2], v8[3], p0, true);
+      int p1 = __builtin_amdgcn_cvt_pk_fp8_f32(v8[4], v8[5], 0, false);
+      p1 = __builtin_amdgcn_cvt_pk_fp8_f32(v8[6], v8[7], p1, true);
+      int* o8 = (int*)(dst8 + ((size_t)nb * (K >> 6) + (k0 >> 6)) * 2048 + j8 * 1024 + l8 * 16 + h8 * 8);
+      o8[0] = p0;
+      o8[1] = p1;
+#endif
+    }
   }
   if (bad) atomicOr(range_flag, bad);
 }
 
-void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, int row0, int interleave_mode, int* range_flag,
-                     hipStream_t st) {
+void pack_weight_f16(const bf16* src, int rows, int K, f16* dst, unsigned char* dst8, int row0, int interleave_mode,
+                     int* range_flag, hipStream_t st) {
   // rows, row0 multiples of 32 and K a multiple of 64: guaranteed by the configuration checks
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)(rows / 32), (unsigned)((K + 511) / 512)), dim3(256), 0, st,
-                     src, K, dst, row0, interleave_mode, range_flag);
+                     src, K, dst, dst8, row0, interleave_mode, range_flag);
 }
 
 }  // namespace vla

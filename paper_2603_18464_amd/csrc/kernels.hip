@@ -135,7 +135,7 @@ template void assemble_prefix<bf16>(const bf16*, const int32_t*, const bf16*, co
 // ---- last-layer tail: only the rows that feed the head go through the last O / feed-forward ------------
 // Row i of the compact set is packed row need[i]: its attention output goes to fragment order
 // [i/32][k/16][lane][8] (what the weight-streaming GEMMs read), its residual row to x_c[i].
-__global__ __launch_bounds__(256) void gather_tail_kernel(const f16* __restrict__ att, int ld_att,
+__global__ __launch_bounds__(256) void gather_tail_kernel(const f16* __restrict__ att, int ld_att, int lo8,
                                                           const float* __restrict__ x,
                                                           const int32_t* __restrict__ need, int d,
                                                           f16* __restrict__ att_frag, f16* __restrict__ att_frag_lo,
@@ -146,19 +146,30 @@ __global__ __launch_bounds__(256) void gather_tail_kernel(const f16* __restrict_
   for (int kc = threadIdx.x; kc < (d >> 3); kc += blockDim.x)
     ablk[(size_t)(kc >> 1) * 64 + (i & 31) + 32 * (kc & 1)] = arow[kc];
   if (att_frag_lo) {                       // two-term rows [hi | lo]: the low terms follow at column d
-    const u32x4* lrow = (const u32x4*)(att + (size_t)src * ld_att + d);
     u32x4* lblk = (u32x4*)(att_frag_lo + (size_t)(i >> 5) * (d >> 4) * 512);
-    for (int kc = threadIdx.x; kc < (d >> 3); kc += blockDim.x)
-      lblk[(size_t)(kc >> 1) * 64 + (i & 31) + 32 * (kc & 1)] = lrow[kc];
+    if (lo8) {                             // ... as bytes: widened to half precision (exact)
+      const int* lrow = (const int*)(att + (size_t)src * ld_att + d);
+      for (int kc = threadIdx.x; kc < (d >> 3); kc += blockDim.x) {
+        const int w0 = lrow[2 * kc], w1 = lrow[2 * kc + 1];
+        f16x8 h;
+        h[0] = (f16)unpack_lo8(w0, 0); h[1] = (f16)unpack_lo8(w0, 1); h[2] = (f16)unpack_lo8(w0, 2); h[3] = (f16)unpack_lo8(w0, 3);
+        h[4] = (f16)unpack_lo8(w1, 0); h[5] = (f16)unpack_lo8(w1, 1); h[6] = (f16)unpack_lo8(w1, 2); h[7] = (f16)unpack_lo8(w1, 3);
+        lblk[(size_t)(kc >> 1) * 64 + (i & 31) + 32 * (kc & 1)] = __builtin_bit_cast(u32x4, h);
+      }
+    } else {
+      const u32x4* lrow = (const u32x4*)(att + (size_t)src * ld_att + d);
+      for (int kc = threadIdx.x; kc < (d >> 3); kc += blockDim.x)
+        lblk[(size_t)(kc >> 1) * 64 + (i & 31) + 32 * (kc & 1)] = lrow[kc];
+    }
   }
   const f32x4* xr = (const f32x4*)(x + (size_t)src * d);
   f32x4* xo = (f32x4*)(x_c + (size_t)i * d);
   for (int j = threadIdx.x; j < (d >> 2); j += blockDim.x) xo[j] = xr[j];
 }
-void gather_tail(const f16* att, int ld_att, const float* x, const int32_t* need, int n, int d, f16* att_frag,
-                 f16* att_frag_lo, float* x_c, hipStream_t st) {
-  hipLaunchKernelGGL(gather_tail_kernel, dim3(n), dim3(256), 0, st, att, ld_att, x, need, d, att_frag, att_frag_lo,
-                     x_c);
+void gather_tail(const f16* att, int ld_att, bool lo8, const float* x, const int32_t* need, int n, int d,
+                 f16* att_frag, f16* att_frag_lo, float* x_c, hipStream_t st) {
+  hipLaunchKernelGGL(gather_tail_kernel, dim3(n), dim3(256), 0, st, att, ld_att, lo8 ? 1 : 0, x, need, d, att_frag,
+                     att_frag_lo, x_c);
 }
 __global__ __launch_bounds__(256) void scatter_tail_kernel(const float* __restrict__ x_c,
                                                            const int32_t* __restrict__ need, int d,
@@ -293,7 +304,7 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 template <class T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                       T* __restrict__ out, int d, float eps,
-                                                      const int32_t* __restrict__ row_index, int ldo, int lo_off) {
+                                                      const int32_t* __restrict__ row_index, int ldo, int lo_mode) {
   typedef __attribute__((ext_vector_type(4))) T T4;
   __shared__ float red[4];
   const int r = blockIdx.x;
@@ -314,17 +325,21 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
   T* o = out + (size_t)r * ldo;
-  auto emit = [&](int i, const f32x4& v) {     // lo_off > 0 (two-term output): the low terms go to column lo_off + i
+  // lo_mode 1 (two-term output): the low terms go to column d + i; 2: as bytes behind the d high terms
+  auto emit = [&](int i, const f32x4& v) {
     const f32x4 g = *(const f32x4*)(gain + i);
     T4 q, qe;
+    float e[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float h = v[j] * inv * g[j];
       q[j] = from_f32<T>(h);
-      qe[j] = from_f32<T>(h - to_f32(q[j]));
+      e[j] = h - to_f32(q[j]);
+      qe[j] = from_f32<T>(e[j]);
     }
     *(T4*)(o + i) = q;
-    if (lo_off) *(T4*)(o + lo_off + i) = qe;
+    if (lo_mode == 1) *(T4*)(o + d + i) = qe;
+    if (lo_mode == 2) *(int*)((unsigned char*)(o + d) + i) = pack_lo8(e[0], e[1], e[2], e[3]);
   };
 #pragma unroll
   for (int it = 0; it < kHeld; ++it) {
@@ -335,14 +350,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 }
 template <class T>
 void rmsnorm(const float* x, const T*, const float* gain, T* out, int rows, int d, float eps,
-             const int32_t* row_index, bool two_term, hipStream_t st) {
+             const int32_t* row_index, int lo_mode, hipStream_t st) {
   hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(rows), dim3(256), 0, st, x, gain, out, d, eps, row_index,
-                     two_term ? 2 * d : d, two_term ? d : 0);
+                     lo_mode == 1 ? 2 * d : (lo_mode == 2 ? d + d / 2 : d), lo_mode);
 }
 template void rmsnorm<float>(const float*, const float*, const float*, float*, int, int, float, const int32_t*,
-                             bool, hipStream_t);
+                             int, hipStream_t);
 template void rmsnorm<f16>(const float*, const f16*, const float*, f16*, int, int, float, const int32_t*,
-                           bool, hipStream_t);
+                           int, hipStream_t);
 
 // ---- action head ------------------------------------------------------------------------------------
 // Workgroup (b, g): final RMSNorm of sequence b's row (float32, kept in LDS), then 32 action rows of

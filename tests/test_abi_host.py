@@ -36,7 +36,9 @@ def test_config_validation_and_sizes():
     hi = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
     assert hi.precision == B.VLA_PREC_HIGH
     arena_hi, kv_hi, work_hi = B.vla_query_sizes(hi)
-    assert kv_hi == 2 * kv and arena_hi == arena and work_hi > work
+    assert kv_hi == 2 * kv and work_hi > work
+    # ... and an 8-bit copy of the matrices whose operand carries 8-bit low terms (QKV, output, down projections)
+    assert arena_hi - arena >= s.n_layers * (4 * s.d_model ** 2 + s.d_model * s.d_ffn)
     assert arena >= 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model)
     assert arena < 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model) + (4 << 20)   # head is slimmed: no second [V,d] matrix
     ctx = B.vla_create(cfg)
