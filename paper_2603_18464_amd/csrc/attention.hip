@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
 // scores are K_hi Q_hi + K_lo Q_hi + K_hi Q_lo, the output sum takes V_hi + V_lo, and the output rows are written
 // as [hi | lo] as well.  The staging tiles double, so one workgroup runs per compute unit instead of two.
 template <int HD, bool TWO>
-__global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
+__global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
     const f16* __restrict__ k_lo, const f16* __restrict__ v_lo, const int32_t* __restrict__ cu_patch,
     const int32_t* __restrict__ cu_instr, const int32_t* __restrict__ slot_map, f16* __restrict__ out, int ldo,
@@ -112,17 +112,23 @@ __global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
     vbase[1] = v_lo + blk;
   }
 
-  // The wave's query fragments live in LDS (chunk c of query column `col` in slot c ^ (col & 7): conflict-free
-  // 16-byte accesses); the registers they would occupy hold the prefetched next key / value tile instead.
-  __shared__ __attribute__((aligned(16))) f16 Qs[NP][4][32 * HD];
+  // Single-term: the wave's query fragments live in LDS (chunk c of query column `col` in slot c ^ (col & 7):
+  // conflict-free 16-byte accesses); the registers they would occupy hold the prefetched next key / value tile
+  // instead.  Two-term: the doubled key / value tiles take the LDS (two workgroups per compute unit must fit), so
+  // the query fragments, high and low terms, stay in registers.
+  __shared__ __attribute__((aligned(16))) f16 Qs[TWO ? 1 : 4][TWO ? 8 : 32 * HD];
+  f16x8 qreg[TWO ? 2 : 1][TWO ? KS : 1];
 #pragma unroll
-  for (int pl = 0; pl < NP; ++pl)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int ch = ks * 2 + half;
-      *(f16x8*)(Qs[pl][wave] + col * HD + ((ch ^ (col & 7)) << 3)) =
-          *(const f16x8*)(q + (size_t)qrow * ldq + pl * lo_off + head * HD + ch * 8);
+  for (int ks = 0; ks < KS; ++ks) {
+    const int ch = ks * 2 + half;
+    if constexpr (TWO) {
+      qreg[0][ks] = *(const f16x8*)(q + (size_t)qrow * ldq + head * HD + ch * 8);
+      qreg[1][ks] = *(const f16x8*)(q + (size_t)qrow * ldq + lo_off + head * HD + ch * 8);
+    } else {
+      *(f16x8*)(Qs[wave] + col * HD + ((ch ^ (col & 7)) << 3)) =
+          *(const f16x8*)(q + (size_t)qrow * ldq + head * HD + ch * 8);
     }
+  }
 
   f32x16 o[DT];
 #pragma unroll
@@ -139,28 +145,28 @@ __global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
   constexpr int KI = 64 * KCH / 256, VI = 32 * KCH / 256;
   u32x4 kreg[NP][KI];
   f16x8 vreg[NP][VI][2];
-  auto fetch = [&](int k0) {
+  auto fetch = [&](int k0, int pl) {                      // plane pl of the tile at k0
 #pragma unroll
-    for (int pl = 0; pl < NP; ++pl) {
+    for (int i = 0; i < KI; ++i) {
+      const int item = t + 256 * i;
+      const int c = item % KCH, kk = item / KCH;
+      const int kp = min(k0 + kk, S - 1);
+      kreg[pl][i] = *(const u32x4*)(kbase[pl] + (size_t)kp * HD + c * 8);
+    }
 #pragma unroll
-      for (int i = 0; i < KI; ++i) {
-        const int item = t + 256 * i;
-        const int c = item % KCH, kk = item / KCH;
-        const int kp = min(k0 + kk, S - 1);
-        kreg[pl][i] = *(const u32x4*)(kbase[pl] + (size_t)kp * HD + c * 8);
-      }
-#pragma unroll
-      for (int i = 0; i < VI; ++i) {
-        const int item = t + 256 * i;
-        const int u = item & 31, c = item >> 5;
-        const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
-        vreg[pl][i][0] = *(const f16x8*)(vbase[pl] + (size_t)ka * HD + c * 8);
-        vreg[pl][i][1] = *(const f16x8*)(vbase[pl] + (size_t)kb * HD + c * 8);
-      }
+    for (int i = 0; i < VI; ++i) {
+      const int item = t + 256 * i;
+      const int u = item & 31, c = item >> 5;
+      const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
+      vreg[pl][i][0] = *(const f16x8*)(vbase[pl] + (size_t)ka * HD + c * 8);
+      vreg[pl][i][1] = *(const f16x8*)(vbase[pl] + (size_t)kb * HD + c * 8);
     }
   };
-  fetch(0);
+  fetch(0, 0);
   for (int k0 = 0; k0 < kend; k0 += 64) {
+    // Two-term: only the high-term plane is prefetched a tile ahead (the registers do not hold both); the low terms
+    // are requested here, and the other workgroup on the compute unit covers their latency.
+    if constexpr (TWO) fetch(k0, 1);
     __syncthreads();                                      // previous tile fully consumed
 #pragma unroll
     for (int pl = 0; pl < NP; ++pl) {
@@ -189,7 +195,7 @@ __global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
       }
     }
     __syncthreads();
-    if (k0 + 64 < kend) fetch(k0 + 64);                   // uniform across the workgroup
+    if (k0 + 64 < kend) fetch(k0 + 64, 0);                // uniform across the workgroup
     if (k0 > wave_last || q0 + wave * 32 >= S) continue;  // tile above this wave's diagonal, or no live query in the wave
 
     // S^T for the two 32-key sub-tiles
@@ -201,10 +207,13 @@ __global__ __launch_bounds__(256, TWO ? 1 : 2) void flash_prefill_kernel(
     // k-step outermost: one query fragment serves both key sub-tiles, and the two accumulator chains alternate
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int qoff = col * HD + (((ks * 2 + half) ^ (col & 7)) << 3);
-      const f16x8 qfr = *(const f16x8*)(Qs[0][wave] + qoff);
-      f16x8 qfl;
-      if constexpr (TWO) qfl = *(const f16x8*)(Qs[NP - 1][wave] + qoff);
+      f16x8 qfr, qfl;
+      if constexpr (TWO) {
+        qfr = qreg[0][ks];
+        qfl = qreg[1][ks];
+      } else {
+        qfr = *(const f16x8*)(Qs[wave] + col * HD + (((ks * 2 + half) ^ (col & 7)) << 3));
+      }
 #pragma unroll
       for (int st = 0; st < 2; ++st) {
         const int kk = st * 32 + col;
