@@ -95,7 +95,8 @@ size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one l
 }
 // one set of planes [layer][K|V][slot][head][position][head_dim]; two-term mode appends a second set with the low terms
 size_t kv_plane_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
-size_t kv_bytes(const vla_config& c) { return kv_plane_bytes(c) * (two_term(c) ? 2 : 1); }
+size_t kv_lo_bytes(const vla_config& c) { return two_term(c) ? 2 * (size_t)c.n_layers * kv_layer_stride(c) : 0; }   // one byte each
+size_t kv_bytes(const vla_config& c) { return kv_plane_bytes(c) + align_up(kv_lo_bytes(c)); }
 
 size_t max_rows(const vla_config& c) {
   const size_t b32 = ((size_t)c.max_batch + 31) / 32 * 32;   // fragment-order activations come in 32-row blocks
@@ -289,8 +290,8 @@ RopeKv layer_rope_kv(vla_ctx* ctx, int l) {
   rk.q = ctx->work + w.q;
   rk.k_cache = ctx->kv + (size_t)(2 * l) * kvl;
   rk.v_cache = ctx->kv + (size_t)(2 * l + 1) * kvl;
-  rk.k_lo = two ? ctx->kv + kv_plane_bytes(c) + (size_t)(2 * l) * kvl : nullptr;
-  rk.v_lo = two ? ctx->kv + kv_plane_bytes(c) + (size_t)(2 * l + 1) * kvl : nullptr;
+  rk.k_lo = two ? ctx->kv + kv_plane_bytes(c) + (size_t)(2 * l) * kv_layer_stride(c) : nullptr;
+  rk.v_lo = two ? ctx->kv + kv_plane_bytes(c) + (size_t)(2 * l + 1) * kv_layer_stride(c) : nullptr;
   rk.ldq = two ? 2 * c.d_model : c.d_model;
   rk.tok_seq = at<int32_t>(ctx->work, w.tok_seq);
   rk.tok_pos = at<int32_t>(ctx->work, w.tok_pos);
@@ -344,8 +345,8 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     {
       ProfScope ps(ctx, fam_attn, st);
       if constexpr (sizeof(T) == 2) {
-        flash_prefill((const f16*)q, rk.ldq, (const f16*)rk.k_cache, (const f16*)rk.v_cache, (const f16*)rk.k_lo,
-                      (const f16*)rk.v_lo, at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr),
+        flash_prefill((const f16*)q, rk.ldq, (const f16*)rk.k_cache, (const f16*)rk.v_cache, (const unsigned char*)rk.k_lo,
+                      (const unsigned char*)rk.v_lo, at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr),
                       ctx->run_slots, (f16*)att, pd, lo8(c, d), ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim,
                       kv_pitch(c), st);
       } else {
@@ -443,8 +444,8 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
       // the attention kernel itself sums the QKV partials of its (sequence, head), applies RoPE and appends the
       // new cache row
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
-      decode_attention_fused(part, ks_qkv, B, rk.rope_cos, rk.rope_sin, (f16*)rk.k_cache, (f16*)rk.v_cache, (f16*)rk.k_lo,
-                             (f16*)rk.v_lo, rk.tok_seq, rk.tok_pos, att, att_lo, B, d, c.n_heads, c.head_dim,
+      decode_attention_fused(part, ks_qkv, B, rk.rope_cos, rk.rope_sin, (f16*)rk.k_cache, (f16*)rk.v_cache,
+                             (unsigned char*)rk.k_lo, (unsigned char*)rk.v_lo, rk.tok_seq, rk.tok_pos, att, att_lo, B, d, c.n_heads, c.head_dim,
                              kv_pitch(c), st);
     }
     {

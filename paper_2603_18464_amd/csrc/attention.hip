@@ -74,14 +74,16 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
 //                  may be permuted freely as long as both operands agree), A operand = V^T read from an
 //                  LDS tile that was transposed while staging, with the key order inside each group of
 //                  16 arranged so that a lane's 8 keys are contiguous.
-// TWO (two-term mode): queries, keys and values each come as hi + lo half-precision terms (the low terms of the
-// queries at column lo_off of the same rows, those of the cache in k_lo / v_lo with the cache's indexing), the
+// TWO (two-term mode): queries, keys and values each come as hi + lo terms (the low terms of the queries in half
+// precision at column lo_off of the same rows, those of the cache as bytes, lo8 = bf8(16 * lo), in k_lo / v_lo
+// with the cache's indexing; they are widened exactly to half precision while the tile is staged), the
 // scores are K_hi Q_hi + K_lo Q_hi + K_hi Q_lo, the output sum takes V_hi + V_lo, and the output rows are written
 // as [hi | lo] as well.  The staging tiles double, so one workgroup runs per compute unit instead of two.
 template <int HD, bool TWO>
 __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     const f16* __restrict__ q, int ldq, const f16* __restrict__ k_cache, const f16* __restrict__ v_cache,
-    const f16* __restrict__ k_lo, const f16* __restrict__ v_lo, const int32_t* __restrict__ cu_patch,
+    const unsigned char* __restrict__ k_lo, const unsigned char* __restrict__ v_lo,
+    const int32_t* __restrict__ cu_patch,
     const int32_t* __restrict__ cu_instr, const int32_t* __restrict__ slot_map, f16* __restrict__ out, int ldo,
     int n_heads, int max_seq, int lo_off, int out_lo8) {
   constexpr int KS = HD / 16;          // k-steps of the QK^T contraction
@@ -103,14 +105,10 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
   const int qrow = row0 + min(qpos, S - 1);               // clamped: rows past the end are never stored
   const int slot = slot_map ? slot_map[b] : b;
   const size_t blk = ((size_t)slot * n_heads + head) * max_seq * HD;
-  const f16* kbase[NP];
-  const f16* vbase[NP];
-  kbase[0] = k_cache + blk;
-  vbase[0] = v_cache + blk;
-  if constexpr (TWO) {
-    kbase[1] = k_lo + blk;
-    vbase[1] = v_lo + blk;
-  }
+  const f16* kbase = k_cache + blk;
+  const f16* vbase = v_cache + blk;
+  const unsigned char* kbase8 = TWO ? k_lo + blk : nullptr;   // low terms of the cache: one byte per element
+  const unsigned char* vbase8 = TWO ? v_lo + blk : nullptr;
 
   // Single-term: the wave's query fragments live in LDS (chunk c of query column `col` in slot c ^ (col & 7):
   // conflict-free 16-byte accesses); the registers they would occupy hold the prefetched next key / value tile
@@ -143,30 +141,55 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
   // The next tile's keys and values are fetched into registers while the current tile is being consumed, so
   // the global-memory latency of a tile hides under the MFMAs and the softmax of the one before.
   constexpr int KI = 64 * KCH / 256, VI = 32 * KCH / 256;
-  u32x4 kreg[NP][KI];
-  f16x8 vreg[NP][VI][2];
-  auto fetch = [&](int k0, int pl) {                      // plane pl of the tile at k0
+  typedef __attribute__((ext_vector_type(2))) int i32x2;
+  u32x4 kreg[KI];
+  f16x8 vreg[VI][2];
+  i32x2 kreg8[TWO ? KI : 1], vreg8[TWO ? VI : 1][2];       // the same items of the low-term planes, 8 bytes each
+  auto fetch = [&](int k0) {                               // high terms of the tile at k0
 #pragma unroll
     for (int i = 0; i < KI; ++i) {
       const int item = t + 256 * i;
       const int c = item % KCH, kk = item / KCH;
       const int kp = min(k0 + kk, S - 1);
-      kreg[pl][i] = *(const u32x4*)(kbase[pl] + (size_t)kp * HD + c * 8);
+      kreg[i] = *(const u32x4*)(kbase + (size_t)kp * HD + c * 8);
     }
 #pragma unroll
     for (int i = 0; i < VI; ++i) {
       const int item = t + 256 * i;
       const int u = item & 31, c = item >> 5;
       const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
-      vreg[pl][i][0] = *(const f16x8*)(vbase[pl] + (size_t)ka * HD + c * 8);
-      vreg[pl][i][1] = *(const f16x8*)(vbase[pl] + (size_t)kb * HD + c * 8);
+      vreg[i][0] = *(const f16x8*)(vbase + (size_t)ka * HD + c * 8);
+      vreg[i][1] = *(const f16x8*)(vbase + (size_t)kb * HD + c * 8);
     }
   };
-  fetch(0, 0);
+  auto fetch8 = [&](int k0) {                              // low terms of the tile at k0
+#pragma unroll
+    for (int i = 0; i < KI; ++i) {
+      const int item = t + 256 * i;
+      const int c = item % KCH, kk = item / KCH;
+      const int kp = min(k0 + kk, S - 1);
+      kreg8[i] = *(const i32x2*)(kbase8 + (size_t)kp * HD + c * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < VI; ++i) {
+      const int item = t + 256 * i;
+      const int u = item & 31, c = item >> 5;
+      const int ka = min(k0 + 2 * u, S - 1), kb = min(k0 + 2 * u + 1, S - 1);
+      vreg8[i][0] = *(const i32x2*)(vbase8 + (size_t)ka * HD + c * 8);
+      vreg8[i][1] = *(const i32x2*)(vbase8 + (size_t)kb * HD + c * 8);
+    }
+  };
+  auto widen8 = [&](const i32x2& w) {                      // 8 low-term bytes -> half precision (exact)
+    f16x8 h;
+    h[0] = (f16)unpack_lo8(w[0], 0); h[1] = (f16)unpack_lo8(w[0], 1); h[2] = (f16)unpack_lo8(w[0], 2); h[3] = (f16)unpack_lo8(w[0], 3);
+    h[4] = (f16)unpack_lo8(w[1], 0); h[5] = (f16)unpack_lo8(w[1], 1); h[6] = (f16)unpack_lo8(w[1], 2); h[7] = (f16)unpack_lo8(w[1], 3);
+    return h;
+  };
+  fetch(0);
   for (int k0 = 0; k0 < kend; k0 += 64) {
-    // Two-term: only the high-term plane is prefetched a tile ahead (the registers do not hold both); the low terms
+    // Two-term: only the high terms are prefetched a tile ahead (the registers do not hold both); the low terms
     // are requested here, and the other workgroup on the compute unit covers their latency.
-    if constexpr (TWO) fetch(k0, 1);
+    if constexpr (TWO) fetch8(k0);
     __syncthreads();                                      // previous tile fully consumed
 #pragma unroll
     for (int pl = 0; pl < NP; ++pl) {
@@ -175,7 +198,11 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
       for (int i = 0; i < KI; ++i) {
         const int item = t + 256 * i;
         const int c = item % KCH, kk = item / KCH;
-        *(u32x4*)(Ks[pl] + kk * HD + ((c ^ (kk & 7)) << 3)) = kreg[pl][i];
+        u32x4 v = kreg[i];
+        if constexpr (TWO) {
+          if (pl == 1) v = __builtin_bit_cast(u32x4, widen8(kreg8[i]));
+        }
+        *(u32x4*)(Ks[pl] + kk * HD + ((c ^ (kk & 7)) << 3)) = v;
       }
       // V tile, transposed: Vt[dim][pos(key)], two keys per 32-bit store
 #pragma unroll
@@ -184,18 +211,25 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
         const int u = item & 31, c = item >> 5;
         const int g = (2 * u) & 15;                       // position of the key inside its group of 16
         const int pos = ((2 * u) & ~15) + ((g >> 2) & 1) * 8 + (g >> 3) * 4 + (g & 3);
+        f16x8 va = vreg[i][0], vb = vreg[i][1];
+        if constexpr (TWO) {
+          if (pl == 1) {
+            va = widen8(vreg8[i][0]);
+            vb = widen8(vreg8[i][1]);
+          }
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
           f16x2 pr;
-          pr[0] = vreg[pl][i][0][j];
-          pr[1] = vreg[pl][i][1][j];
+          pr[0] = va[j];
+          pr[1] = vb[j];
           *(f16x2*)(Vt[pl] + (c * 8 + j) * VPITCH + pos) = pr;
         }
       }
     }
     __syncthreads();
-    if (k0 + 64 < kend) fetch(k0 + 64, 0);                // uniform across the workgroup
+    if (k0 + 64 < kend) fetch(k0 + 64);                   // uniform across the workgroup
     if (k0 > wave_last || q0 + wave * 32 >= S) continue;  // tile above this wave's diagonal, or no live query in the wave
 
     // S^T for the two 32-key sub-tiles
@@ -314,9 +348,10 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
 // k_lo / v_lo != nullptr selects the two-term kernel: q rows are [hi | lo] of pitch ldq with the low terms at
 // column lo_off = d_model, and so are the output rows (pitch ldo), unless out_lo8 asks for 8-bit low terms (bytes
 // behind the d_model high terms of each row).
-void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
-                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo,
-                   bool out_lo8, int B, int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st) {
+void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const unsigned char* k_lo,
+                   const unsigned char* v_lo, const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map,
+                   f16* out, int ldo, bool out_lo8, int B, int max_len, int n_heads, int head_dim, int max_seq,
+                   hipStream_t st) {
   const dim3 grid((max_len + 127) / 128, B, n_heads);
   const int lo_off = n_heads * head_dim;
 #define VLA_FLASH(HDV, TWOV)                                                                                       \
@@ -356,8 +391,9 @@ struct QkvPartials {
 // (low terms at column d_model of q); the output is written as hi and lo fragments (out_frag_lo).
 template <int HD, bool FUSED, bool TWO>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
-    const f16* __restrict__ q, int ldq, f16* __restrict__ k_cache, f16* __restrict__ v_cache, f16* __restrict__ k_lo,
-    f16* __restrict__ v_lo, const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos,
+    const f16* __restrict__ q, int ldq, f16* __restrict__ k_cache, f16* __restrict__ v_cache,
+    unsigned char* __restrict__ k_lo, unsigned char* __restrict__ v_lo, const int32_t* __restrict__ tok_seq,
+    const int32_t* __restrict__ tok_pos,
     f16* __restrict__ out_frag, f16* __restrict__ out_frag_lo, int d_model, int n_heads, int max_seq,
     QkvPartials qp) {
   constexpr int LPR = HD / 8;            // lanes per row
@@ -373,8 +409,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   const size_t blk = ((size_t)slot * n_heads + head) * max_seq * HD;
   f16* kb = k_cache + blk;
   f16* vb = v_cache + blk;
-  f16* kbl = TWO ? k_lo + blk : nullptr;
-  f16* vbl = TWO ? v_lo + blk : nullptr;
+  unsigned char* kbl = TWO ? k_lo + blk : nullptr;     // low terms: one byte per element, bf8(16 * lo)
+  unsigned char* vbl = TWO ? v_lo + blk : nullptr;
   const int last_global = FUSED ? ctx - 2 : ctx - 1;   // last row that is read from the cache
   if constexpr (FUSED) {
     constexpr int HALF = HD / 2;
@@ -395,14 +431,13 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
       kb[(size_t)pos * HD + i] = k0; kb[(size_t)pos * HD + i + HALF] = k1;
       vb[(size_t)pos * HD + i] = v0; vb[(size_t)pos * HD + i + HALF] = v1;
       if constexpr (TWO) {
-        const f16 k0e = from_f32<f16>(k0f - (float)k0), k1e = from_f32<f16>(k1f - (float)k1);
-        const f16 v0e = from_f32<f16>(v[4] - (float)v0), v1e = from_f32<f16>(v[5] - (float)v1);
-        kbl[(size_t)pos * HD + i] = k0e; kbl[(size_t)pos * HD + i + HALF] = k1e;
-        vbl[(size_t)pos * HD + i] = v0e; vbl[(size_t)pos * HD + i + HALF] = v1e;
+        const int ke = pack_lo8(k0f - (float)k0, k1f - (float)k1, v[4] - (float)v0, v[5] - (float)v1);
+        kbl[(size_t)pos * HD + i] = (unsigned char)(ke & 0xff); kbl[(size_t)pos * HD + i + HALF] = (unsigned char)((ke >> 8) & 0xff);
+        vbl[(size_t)pos * HD + i] = (unsigned char)((ke >> 16) & 0xff); vbl[(size_t)pos * HD + i + HALF] = (unsigned char)((ke >> 24) & 0xff);
         // this step uses exactly what later steps will read back: hi + lo
         s_q[i] = q0; s_q[i + HALF] = q1;
-        s_k[i] = (float)k0 + (float)k0e; s_k[i + HALF] = (float)k1 + (float)k1e;
-        s_v[i] = (float)v0 + (float)v0e; s_v[i + HALF] = (float)v1 + (float)v1e;
+        s_k[i] = (float)k0 + unpack_lo8(ke, 0); s_k[i + HALF] = (float)k1 + unpack_lo8(ke, 1);
+        s_v[i] = (float)v0 + unpack_lo8(ke, 2); s_v[i + HALF] = (float)v1 + unpack_lo8(ke, 3);
       } else {
         s_q[i] = q0; s_q[i + HALF] = q1;      // the query never leaves float32
         s_k[i] = (float)k0; s_k[i + HALF] = (float)k1; s_v[i] = (float)v0; s_v[i + HALF] = (float)v1;
@@ -432,9 +467,11 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   float m_run = -INFINITY, lsum = 0.f;
   float acc[8] = {};
   const int n_it = (ctx + 4 * RPI - 1) / (4 * RPI);
-  constexpr int U = TWO ? 4 : 8;           // iterations whose loads are issued together (16 rows of 16 bytes per lane)
+  typedef __attribute__((ext_vector_type(2))) int i32x2;
+  constexpr int U = 8;                     // iterations whose loads are issued together (16 rows of 16 bytes per lane)
   for (int it0 = 0; it0 < n_it; it0 += U) {
-    f16x8 kv[U], vv[U], kl[TWO ? U : 1], vl[TWO ? U : 1];
+    f16x8 kv[U], vv[U];
+    i32x2 kl[TWO ? U : 1], vl[TWO ? U : 1];               // low terms of the same rows: 8 bytes per lane
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int row = ((it0 + u) * 4 + wave) * RPI + sub;
@@ -442,8 +479,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
       kv[u] = *(const f16x8*)(kb + off);
       vv[u] = *(const f16x8*)(vb + off);
       if constexpr (TWO) {
-        kl[u] = *(const f16x8*)(kbl + off);
-        vl[u] = *(const f16x8*)(vbl + off);
+        kl[u] = *(const i32x2*)(kbl + off);
+        vl[u] = *(const i32x2*)(vbl + off);
       }
     }
 #pragma unroll
@@ -455,8 +492,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
         kf[j] = (float)kv[u][j];
         vf[j] = (float)vv[u][j];
         if constexpr (TWO) {
-          kf[j] += (float)kl[u][j];
-          vf[j] += (float)vl[u][j];
+          kf[j] += unpack_lo8(kl[u][j >> 2], j & 3);
+          vf[j] += unpack_lo8(vl[u][j >> 2], j & 3);
         }
       }
       if (FUSED && row > last_global) {                      // the new row, from LDS
@@ -525,14 +562,15 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
 }
 
 // Row b of the step lives in cache slot tok_seq[b].  k_lo != nullptr selects two-term mode.
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
-                      const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B,
-                      int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
+void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const unsigned char* k_lo,
+                      const unsigned char* v_lo, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag,
+                      f16* out_frag_lo, int B, int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
   const dim3 grid(B, n_heads);
   const QkvPartials none{nullptr, 0, 0, nullptr, nullptr};
 #define VLA_DEC_ATT(HDV, TWOV)                                                                                       \
   hipLaunchKernelGGL((decode_attention_kernel<HDV, false, TWOV>), grid, dim3(256), 0, st, q, ldq, (f16*)k_cache,     \
-                     (f16*)v_cache, (f16*)k_lo, (f16*)v_lo, tok_seq, tok_pos, out_frag, out_frag_lo, d_model, n_heads, \
+                     (f16*)v_cache, (unsigned char*)k_lo, (unsigned char*)v_lo, tok_seq, tok_pos, out_frag, out_frag_lo,  \
+                     d_model, n_heads,                                                                               \
                      max_seq, none)
   if (k_lo) {
     if (head_dim == 128) VLA_DEC_ATT(128, true);
@@ -545,7 +583,7 @@ void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_ca
 }
 // Same, with the query and the new cache row taken from the QKV GEMM's partial sums part[ksplit][rows][3 * d_model].
 void decode_attention_fused(const float* part, int ksplit, int part_rows, const float* rope_cos, const float* rope_sin,
-                            f16* k_cache, f16* v_cache, f16* k_lo, f16* v_lo, const int32_t* tok_seq,
+                            f16* k_cache, f16* v_cache, unsigned char* k_lo, unsigned char* v_lo, const int32_t* tok_seq,
                             const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B, int d_model, int n_heads,
                             int head_dim, int max_seq, hipStream_t st) {
   const dim3 grid(B, n_heads);

@@ -63,8 +63,8 @@ struct RopeKv {
   void* q;               // [T, ldq] storage dtype, rotated queries (two-term mode: columns [d_model, 2 d_model) hold the low terms)
   void* k_cache;         // layer base: [slot][head][position][head_dim]
   void* v_cache;
-  void* k_lo;            // two-term mode: low terms of the cached keys / values, same indexing; nullptr otherwise
-  void* v_lo;
+  void* k_lo;            // two-term mode: low terms of the cached keys / values, same indexing, one byte per element
+  void* v_lo;            //   (bf8(16 * lo)); nullptr otherwise
   int ldq;               // row pitch of q in elements
   const int32_t* tok_seq;   // [T] slot of each packed token
   const int32_t* tok_pos;   // [T] position of each packed token inside its sequence
@@ -162,9 +162,10 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
 // (device, [B], or nullptr for the identity) gives the cache slot of each sequence of the call.
 // k_lo / v_lo (low terms of the cache) != nullptr: two-term mode, q rows are [hi | lo] with the low terms at column
 // d_model, and so are the output rows, or (out_lo8) [hi | 8-bit low terms].
-void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
-                   const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map, f16* out, int ldo,
-                   bool out_lo8, int B, int max_len, int n_heads, int head_dim, int max_seq, hipStream_t st);
+void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const unsigned char* k_lo,
+                   const unsigned char* v_lo, const int32_t* cu_patch, const int32_t* cu_instr, const int32_t* slot_map,
+                   f16* out, int ldo, bool out_lo8, int B, int max_len, int n_heads, int head_dim, int max_seq,
+                   hipStream_t st);
 
 // Decode-step GEMMs (M <= 128): weight-streaming split-K kernel writing partial sums, and the kernels
 // that add the partials in a fixed order and apply the elementwise step that follows each GEMM.
@@ -184,11 +185,11 @@ void reduce_swiglu(const float* part, int ksplit, int plane_rows, int prow0, int
 
 // Decode attention of the 16-bit path (one query per row of the step); output in fragment order.  k_lo / v_lo
 // != nullptr: two-term mode (low terms of the cache, output also as low-term fragments out_frag_lo).
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const f16* k_lo, const f16* v_lo,
-                      const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B,
-                      int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
+void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const unsigned char* k_lo,
+                      const unsigned char* v_lo, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag,
+                      f16* out_frag_lo, int B, int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
 void decode_attention_fused(const float* part, int ksplit, int part_rows, const float* rope_cos, const float* rope_sin,
-                            f16* k_cache, f16* v_cache, f16* k_lo, f16* v_lo, const int32_t* tok_seq,
+                            f16* k_cache, f16* v_cache, unsigned char* k_lo, unsigned char* v_lo, const int32_t* tok_seq,
                             const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B, int d_model, int n_heads,
                             int head_dim, int max_seq, hipStream_t st);
 

@@ -185,14 +185,15 @@ struct EpiQkv {
       f32x4 lo = *(const f32x4*)(tile + r * kStagePitch + hh * HD + c4) * (1.0f / kWeightScale);
       f32x4 hi = *(const f32x4*)(tile + r * kStagePitch + hh * HD + HALF + c4) * (1.0f / kWeightScale);
       f16* dst;
-      f16* dst_lo = nullptr;                 // two-term mode: where the low terms of the same elements go
+      f16* dst_lo = nullptr;                 // two-term mode: low terms of the queries (half precision, column d + ...)
+      unsigned char* dst_lo8 = nullptr;      // ... and of the cached keys / values (one byte each)
       if (sect == 0) {
         dst = (f16*)o.q + (size_t)min(m, M - 1) * o.ldq + (size_t)head * HD;
         if (o.k_lo) dst_lo = dst + d;
       } else {
         const size_t at = (((size_t)slot[it] * o.n_heads + head) * o.max_seq + pos[it]) * HD;
         dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) + at;
-        if (o.k_lo) dst_lo = (f16*)(sect == 1 ? o.k_lo : o.v_lo) + at;
+        if (o.k_lo) dst_lo8 = (unsigned char*)(sect == 1 ? o.k_lo : o.v_lo) + at;
       }
       if (sect < 2) {
 #pragma unroll
@@ -204,12 +205,15 @@ struct EpiQkv {
         }
       }
       f16x4 l4, h4, l4e, h4e;
+      float le[4], he[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         l4[j] = from_f32<f16>(lo[j]);
         h4[j] = from_f32<f16>(hi[j]);
-        l4e[j] = from_f32<f16>(lo[j] - (float)l4[j]);
-        h4e[j] = from_f32<f16>(hi[j] - (float)h4[j]);
+        le[j] = lo[j] - (float)l4[j];
+        he[j] = hi[j] - (float)h4[j];
+        l4e[j] = from_f32<f16>(le[j]);
+        h4e[j] = from_f32<f16>(he[j]);
       }
       if (m < M) {
         *(f16x4*)(dst + c4) = l4;
@@ -217,6 +221,10 @@ struct EpiQkv {
         if (dst_lo) {
           *(f16x4*)(dst_lo + c4) = l4e;
           *(f16x4*)(dst_lo + HALF + c4) = h4e;
+        }
+        if (dst_lo8) {
+          *(int*)(dst_lo8 + c4) = pack_lo8(le[0], le[1], le[2], le[3]);
+          *(int*)(dst_lo8 + HALF + c4) = pack_lo8(he[0], he[1], he[2], he[3]);
         }
       }
     }
@@ -247,13 +255,14 @@ struct EpiQkv {
             const int head = (col0 + hh * HD) / HD;
             f16* dst;
             f16* dst_lo = nullptr;
+            unsigned char* dst_lo8 = nullptr;
             if (sect == 0) {
               dst = (f16*)o.q + (size_t)m * o.ldq + (size_t)head * HD;
               if (o.k_lo) dst_lo = dst + d;
             } else {
               const size_t at = (((size_t)slot * o.n_heads + head) * o.max_seq + pos) * HD;
               dst = (f16*)(sect == 1 ? o.k_cache : o.v_cache) + at;
-              if (o.k_lo) dst_lo = (f16*)(sect == 1 ? o.k_lo : o.v_lo) + at;
+              if (o.k_lo) dst_lo8 = (unsigned char*)(sect == 1 ? o.k_lo : o.v_lo) + at;
             }
 #pragma unroll
             for (int ht = 0; ht < HT / 2; ++ht) {
@@ -272,6 +281,10 @@ struct EpiQkv {
               if (dst_lo) {
                 dst_lo[j] = from_f32<f16>(lo - (float)l16);
                 dst_lo[j + HALF] = from_f32<f16>(hi - (float)h16);
+              }
+              if (dst_lo8) {
+                dst_lo8[j] = (unsigned char)(pack_lo8(lo - (float)l16, 0.f, 0.f, 0.f) & 0xff);
+                dst_lo8[j + HALF] = (unsigned char)(pack_lo8(hi - (float)h16, 0.f, 0.f, 0.f) & 0xff);
               }
             }
           }

@@ -32,11 +32,11 @@ def test_config_validation_and_sizes():
     arena, kv, work = B.vla_query_sizes(cfg)
     s = wl.shape
     assert kv == 2 * s.n_layers * wl.batch * s.n_heads * (wl.max_seq | 1) * s.head_dim * 2     # odd position pitch
-    # two-term mode keeps a second set of planes with the low terms of the cached keys and values
+    # two-term mode keeps a second set of planes with the low terms of the cached keys and values, one byte each
     hi = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
     assert hi.precision == B.VLA_PREC_HIGH
     arena_hi, kv_hi, work_hi = B.vla_query_sizes(hi)
-    assert kv_hi == 2 * kv and work_hi > work
+    assert kv_hi == kv + kv // 2 and work_hi > work
     # ... and an 8-bit copy of the matrices whose operand carries 8-bit low terms (QKV, output, down projections)
     assert arena_hi - arena >= s.n_layers * (4 * s.d_model ** 2 + s.d_model * s.d_ffn)
     assert arena >= 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model)
