@@ -407,9 +407,11 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
 inline f16* frag_rows(f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; }
 inline f16* frag_lo(const vla_config& c, f16* base, int K) { return two_term(c) ? base + max_rows(c) * (size_t)K : nullptr; }
 
-// Decode step of the 16-bit path: weight-streaming split-K GEMMs over chunks of at most kSkinnyMaxRows rows (one
-// chunk up to 256 sequences, so the weights are streamed once per step), partial planes that span the whole batch,
-// and one kernel after each GEMM that sums the planes and applies the elementwise step for all rows.
+// Decode step of the 16-bit path: weight-streaming split-K GEMMs over chunks of at most kSkinnyMaxRows rows (a
+// 128-row accumulator tile is what a wave's registers hold without spilling; for larger batches the launches of
+// the later chunks follow the first at once and find the matrix they re-read in the 256 MB last-level cache, the
+// largest one being 180 MB), partial planes that span the whole batch, and one kernel after each GEMM that sums the
+// planes and applies the elementwise step for all rows.
 int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;

@@ -171,7 +171,7 @@ void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache
 // that add the partials in a fixed order and apply the elementwise step that follows each GEMM.
 // Activations named *_frag are [M, K] in MFMA fragment order: [m/32][k/16][lane][8].
 int skinny_ksplit(int N, int K);
-constexpr int kSkinnyMaxRows = 256;   // most rows of one weight-streaming GEMM launch
+constexpr int kSkinnyMaxRows = 128;   // most rows of one weight-streaming GEMM launch
 // Two-term mode: *_lo arguments hold the low terms f16(a - f16(a)) in the same fragment order (nullptr: single-term).
 // The M rows of a launch are rows prow0 .. prow0 + M - 1 of partial planes of plane_rows rows each.
 void skinny_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* part, int M, int N, int K, int ksplit,

@@ -186,10 +186,6 @@ void skinny_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* pa
     VLA_SKINNY_CASE(2, 6, 4)
     VLA_SKINNY_CASE(3, 4, 3)
     VLA_SKINNY_CASE(4, 4, 3)
-    VLA_SKINNY_CASE(5, 3, 2)
-    VLA_SKINNY_CASE(6, 3, 2)
-    VLA_SKINNY_CASE(7, 3, 2)
-    VLA_SKINNY_CASE(8, 3, 2)
     default: break;                                        // callers keep M <= kSkinnyMaxRows
   }
 #undef VLA_SKINNY_CASE
