@@ -25,22 +25,32 @@ def round_f16(x: np.ndarray) -> np.ndarray:
     return x.astype(np.float16).astype(np.float64)
 
 
-def prefix_logits(pol: O.OraclePolicy, x: np.ndarray, rnd=None, points=("hn", "q", "k", "v", "att", "act")):
-    """Action logits at the last of the prefix rows x [S, d]; rnd(None = exact) is applied at `points`."""
+POINTS = ("hn_a", "hn_f", "q", "k", "v", "att", "act")
+# The operands the two-term mode of the HIP path carries as hi + lo (their rounding error drops by 2^-11 or, with
+# 8-bit low terms, by a factor of about 12, i.e. out of the picture); what is left is the one point it keeps in a
+# single half-precision term: the normalised rows that feed the gate / up projections.
+TWO_TERM_POINTS = ("hn_a", "q", "k", "v", "att", "act")
+SINGLE_TERM_LEFT = ("hn_f",)
+
+
+def prefix_logits(pol: O.OraclePolicy, x: np.ndarray, rnd=None, points=POINTS, n_layers=None):
+    """Action logits at the last of the prefix rows x [S, d]; rnd (None = exact) is applied at `points`:
+    hn_a / hn_f = the normalised rows that feed the QKV / the gate-up projections, q, k (after the rotary
+    embedding), v, att = attention output, act = SwiGLU output."""
     s = pol.s
     H, hd = s.n_heads, s.head_dim
     n = x.shape[0]
     pos = np.arange(n)
     R = (lambda key, v: rnd(v) if (rnd is not None and key in points) else v)
-    for l in range(s.n_layers):
+    for l in range(s.n_layers if n_layers is None else n_layers):
         p = f"layers.{l}."
-        h = R("hn", O.rms_norm(x, pol.W(p + "attn_norm"), s.rms_eps))
+        h = R("hn_a", O.rms_norm(x, pol.W(p + "attn_norm"), s.rms_eps))
         q = R("q", O.rope((h @ pol.W(p + "wq").T).reshape(n, H, hd), pos, s.rope_theta))
         k = R("k", O.rope((h @ pol.W(p + "wk").T).reshape(n, H, hd), pos, s.rope_theta))
         v = R("v", (h @ pol.W(p + "wv").T).reshape(n, H, hd))
         att = R("att", O.causal_attention(q, k, v, pos).reshape(n, -1))
         x = x + att @ pol.W(p + "wo").T
-        h = R("hn", O.rms_norm(x, pol.W(p + "ffn_norm"), s.rms_eps))
+        h = R("hn_f", O.rms_norm(x, pol.W(p + "ffn_norm"), s.rms_eps))
         act = R("act", O.silu(h @ pol.W(p + "w_gate").T) * (h @ pol.W(p + "w_up").T))
         x = x + act @ pol.W(p + "w_down").T
     return pol.action_logits(x[-1])
