@@ -307,15 +307,6 @@ int vla_batcher_size(vla_batcher* b, int32_t* n);
 int vla_batcher_deadline(vla_batcher* b, double* t);
 int vla_batcher_poll(vla_batcher* b, double t_now, vla_request* out, int32_t cap, int32_t* n_out);
 
-/* Practical ceilings of the device the context runs on, for reporting next to the vendor peaks (benchmark
- * support, not part of the policy path; unlike every other call it waits for its own kernels).  Needs loaded
- * weights on the 16-bit path.
- *   kind 0: an MFMA-only loop (8 independent 32x32x16 half-precision MFMAs per iteration and wave, two waves
- *           per SIMD, operands = real weight fragments held in registers) -> *value_out in TFLOP/s
- *   kind 1: a plain 16-byte-per-lane streaming read of all layer weights                -> *value_out in GB/s
- * Best of three timed runs after a warm-up. */
-int vla_probe(vla_ctx* ctx, int32_t kind, double* value_out, void* hip_stream);
-
 /* Selection alone, for callers that drive vla_prefill / vla_decode_step themselves:
  * logits [B, n_action_bins] (device) -> bin index, log-prob, action, for token index k of the
  * chunk (k selects the action dimension k mod action_dim and the row [b, k] of gumbel [B, K, A]).
@@ -324,17 +315,6 @@ int vla_select(vla_ctx* ctx, int32_t B, const float* logits, float temperature, 
                int32_t k, int32_t n_tokens, const float* act_scale, const float* act_offset,
                int32_t action_dim, int32_t* tokens_out, float* logp_out, float* actions_out,
                int32_t out_stride, int32_t* next_ids_out, void* hip_stream);
-
-/* Timing hooks for the benchmark: duration of the launches of one kernel family, measured with
- * HIP events recorded on the launch stream around each launch.  vla_prof_enable(ctx, mask) clears
- * what was collected and then times the families whose bit (1 << index) is set in mask (0 = off).
- * vla_prof_read synchronises the recorded events (host-blocking) and reports, for family index i
- * (0 <= i < vla_prof_count()), its name, number of launches and total milliseconds.  Families are
- * named by the read-out itself: the four GEMMs (qkv, o, gate-up, down) and the attention of prefill
- * and of decode, rmsnorm, head_select, misc. */
-int vla_prof_enable(vla_ctx* ctx, int32_t mask);
-int vla_prof_count(void);
-int vla_prof_read(vla_ctx* ctx, int32_t i, const char** name, int64_t* launches, double* total_ms);
 
 #ifdef __cplusplus
 }

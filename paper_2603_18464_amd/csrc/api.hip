@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "../../include/vla.h"
+#include "../../include/vla_bench.h"
 #include "common.h"
 
 using namespace vla;
