@@ -375,10 +375,10 @@ void flash_prefill(const f16* q, int ldq, const f16* k_cache, const f16* v_cache
 // shuffles, the probability-weighted values stay in 8 per-lane accumulators, and the partial softmax
 // statistics and outputs of the waves are merged through LDS at the end.
 //
-// FUSED: the query and the new key / value row of this (sequence, head) are not read from memory but formed
-// here from the split-K partial sums of the QKV GEMM (summed in plane order, RoPE applied, rounded to half
-// precision exactly as the stand-alone reduce kernel does); the new row is appended to the cache for the
-// following steps and used from LDS in this one.
+// The query and the new key / value row of this (sequence, head) are not read from memory but formed here from
+// the split-K partial sums of the QKV GEMM (summed in plane order, RoPE applied; the query stays in float32, the
+// key / value row is rounded as the cache holds it); the new row is appended to the cache for the following steps
+// and used from LDS in this one.
 struct QkvPartials {
   const float* part;       // [ksplit][rows][3 * d_model]
   int ksplit, rows;
@@ -386,12 +386,12 @@ struct QkvPartials {
   const float* rope_sin;
 };
 
-// TWO (two-term mode): the cache holds every key / value as hi + lo half-precision terms (k_lo / v_lo, same
-// indexing), both are streamed and added in float32; the query stays in float32 (fused) or is read as hi + lo
-// (low terms at column d_model of q); the output is written as hi and lo fragments (out_frag_lo).
-template <int HD, bool FUSED, bool TWO>
+// TWO (two-term mode): the cache holds every key / value as a half-precision high term plus a one-byte low term
+// (k_lo / v_lo, same indexing, bf8(16 * lo)); both are streamed and added in float32; the output is written as hi
+// and lo fragments (out_frag_lo).
+template <int HD, bool TWO>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
-    const f16* __restrict__ q, int ldq, f16* __restrict__ k_cache, f16* __restrict__ v_cache,
+    f16* __restrict__ k_cache, f16* __restrict__ v_cache,
     unsigned char* __restrict__ k_lo, unsigned char* __restrict__ v_lo, const int32_t* __restrict__ tok_seq,
     const int32_t* __restrict__ tok_pos,
     f16* __restrict__ out_frag, f16* __restrict__ out_frag_lo, int d_model, int n_heads, int max_seq,
@@ -411,8 +411,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   f16* vb = v_cache + blk;
   unsigned char* kbl = TWO ? k_lo + blk : nullptr;     // low terms: one byte per element, bf8(16 * lo)
   unsigned char* vbl = TWO ? v_lo + blk : nullptr;
-  const int last_global = FUSED ? ctx - 2 : ctx - 1;   // last row that is read from the cache
-  if constexpr (FUSED) {
+  const int last_global = ctx - 2;                     // last row that is read from the cache
+  {
     constexpr int HALF = HD / 2;
     if (threadIdx.x < HALF) {
       const int i = threadIdx.x, c0 = head * HD + i, c1 = c0 + HALF, d = d_model, pos = ctx - 1;
@@ -446,19 +446,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     __syncthreads();
   }
   float qf[8];
-  if constexpr (FUSED) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) qf[j] = s_q[c * 8 + j];
-  } else {
-    const f16x8 qv = *(const f16x8*)(q + (size_t)b * ldq + head * HD + c * 8);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) qf[j] = (float)qv[j];
-    if constexpr (TWO) {
-      const f16x8 ql = *(const f16x8*)(q + (size_t)b * ldq + d_model + head * HD + c * 8);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) qf[j] += (float)ql[j];
-    }
-  }
+  for (int j = 0; j < 8; ++j) qf[j] = s_q[c * 8 + j];
   const float scale = rsqrtf((float)HD);
 
   // One pass with a running maximum per lane (row = (it*4 + wave)*RPI + sub): the key row and the value row of
@@ -496,7 +485,7 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
           vf[j] += unpack_lo8(vl[u][j >> 2], j & 3);
         }
       }
-      if (FUSED && row > last_global) {                      // the new row, from LDS
+      if (row > last_global) {                               // the new row, from LDS
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           kf[j] = s_k[c * 8 + j];
@@ -561,27 +550,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
   }
 }
 
-// Row b of the step lives in cache slot tok_seq[b].  k_lo != nullptr selects two-term mode.
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const unsigned char* k_lo,
-                      const unsigned char* v_lo, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag,
-                      f16* out_frag_lo, int B, int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st) {
-  const dim3 grid(B, n_heads);
-  const QkvPartials none{nullptr, 0, 0, nullptr, nullptr};
-#define VLA_DEC_ATT(HDV, TWOV)                                                                                       \
-  hipLaunchKernelGGL((decode_attention_kernel<HDV, false, TWOV>), grid, dim3(256), 0, st, q, ldq, (f16*)k_cache,     \
-                     (f16*)v_cache, (unsigned char*)k_lo, (unsigned char*)v_lo, tok_seq, tok_pos, out_frag, out_frag_lo,  \
-                     d_model, n_heads,                                                                               \
-                     max_seq, none)
-  if (k_lo) {
-    if (head_dim == 128) VLA_DEC_ATT(128, true);
-    else VLA_DEC_ATT(64, true);
-  } else {
-    if (head_dim == 128) VLA_DEC_ATT(128, false);
-    else VLA_DEC_ATT(64, false);
-  }
-#undef VLA_DEC_ATT
-}
-// Same, with the query and the new cache row taken from the QKV GEMM's partial sums part[ksplit][rows][3 * d_model].
+// Row b of the step lives in cache slot tok_seq[b]; the query and the new cache row come from the QKV GEMM's partial
+// sums part[ksplit][part_rows][3 * d_model].  k_lo != nullptr selects two-term mode.
 void decode_attention_fused(const float* part, int ksplit, int part_rows, const float* rope_cos, const float* rope_sin,
                             f16* k_cache, f16* v_cache, unsigned char* k_lo, unsigned char* v_lo, const int32_t* tok_seq,
                             const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B, int d_model, int n_heads,
@@ -589,7 +559,7 @@ void decode_attention_fused(const float* part, int ksplit, int part_rows, const 
   const dim3 grid(B, n_heads);
   const QkvPartials qp{part, ksplit, part_rows, rope_cos, rope_sin};
 #define VLA_DEC_ATT(HDV, TWOV)                                                                                     \
-  hipLaunchKernelGGL((decode_attention_kernel<HDV, true, TWOV>), grid, dim3(256), 0, st, nullptr, 0, k_cache, v_cache, \
+  hipLaunchKernelGGL((decode_attention_kernel<HDV, TWOV>), grid, dim3(256), 0, st, k_cache, v_cache,              \
                      k_lo, v_lo, tok_seq, tok_pos, out_frag, out_frag_lo, d_model, n_heads, max_seq, qp)
   if (k_lo) {
     if (head_dim == 128) VLA_DEC_ATT(128, true);
@@ -624,7 +594,4 @@ void attention_rows(const T* q, int ldq, const T* k_cache, const T* v_cache, con
 }
 template void attention_rows<float>(const float*, int, const float*, const float*, const int32_t*, const int32_t*,
                                     float*, int, int, int, int, int, bool, hipStream_t);
-template void attention_rows<f16>(const f16*, int, const f16*, const f16*, const int32_t*, const int32_t*,
-                                  f16*, int, int, int, int, int, bool, hipStream_t);
-
 }  // namespace vla

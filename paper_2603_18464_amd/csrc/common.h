@@ -185,9 +185,6 @@ void reduce_swiglu(const float* part, int ksplit, int plane_rows, int prow0, int
 
 // Decode attention of the 16-bit path (one query per row of the step); output in fragment order.  k_lo / v_lo
 // != nullptr: two-term mode (low terms of the cache, output also as low-term fragments out_frag_lo).
-void decode_attention(const f16* q, int ldq, const f16* k_cache, const f16* v_cache, const unsigned char* k_lo,
-                      const unsigned char* v_lo, const int32_t* tok_seq, const int32_t* tok_pos, f16* out_frag,
-                      f16* out_frag_lo, int B, int d_model, int n_heads, int head_dim, int max_seq, hipStream_t st);
 void decode_attention_fused(const float* part, int ksplit, int part_rows, const float* rope_cos, const float* rope_sin,
                             f16* k_cache, f16* v_cache, unsigned char* k_lo, unsigned char* v_lo, const int32_t* tok_seq,
                             const int32_t* tok_pos, f16* out_frag, f16* out_frag_lo, int B, int d_model, int n_heads,
