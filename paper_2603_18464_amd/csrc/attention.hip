@@ -97,12 +97,15 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
   const int b = blockIdx.y, head = blockIdx.z;
   const int row0 = cu_patch[b] + cu_instr[b];
   const int S = cu_patch[b + 1] + cu_instr[b + 1] - row0;
-  const int q0 = blockIdx.x * 128;
-  if (q0 >= S) return;
+  // Query tiles of 128 are aligned to the END of the sequence (the first tile is the short one): a tile needs the
+  // keys up to its last query, so a prefix of 290 costs 1 + 3 + 5 key tiles instead of 2 + 4 + 5.
+  const int nq = (S + 127) / 128;
+  if ((int)blockIdx.x >= nq) return;
+  const int q0 = S - 128 * (nq - (int)blockIdx.x);        // negative for a short first tile: those lanes are idle
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int half = lane >> 5, col = lane & 31;
-  const int qpos = q0 + wave * 32 + col;                 // this lane's query position
-  const int qrow = row0 + min(qpos, S - 1);               // clamped: rows past the end are never stored
+  const int qpos = q0 + wave * 32 + col;                 // this lane's query position (< S; idle if negative)
+  const int qrow = row0 + max(qpos, 0);                   // clamped: idle lanes are never stored
   const int slot = slot_map ? slot_map[b] : b;
   const size_t blk = ((size_t)slot * n_heads + head) * max_seq * HD;
   const f16* kbase = k_cache + blk;
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
   float m_run = -INFINITY, l_run = 0.f;
   const float scale = rsqrtf((float)HD);
 
-  const int kend = min(S, q0 + 128);                      // keys needed by this workgroup
+  const int kend = q0 + 128;                              // keys needed by this workgroup (<= S)
   const int wave_last = q0 + wave * 32 + 31;              // last query position of this wave
   // The next tile's keys and values are fetched into registers while the current tile is being consumed, so
   // the global-memory latency of a tile hides under the MFMAs and the softmax of the one before.
@@ -230,7 +233,7 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
     }
     __syncthreads();
     if (k0 + 64 < kend) fetch(k0 + 64);                   // uniform across the workgroup
-    if (k0 > wave_last || q0 + wave * 32 >= S) continue;  // tile above this wave's diagonal, or no live query in the wave
+    if (k0 > wave_last || wave_last < 0) continue;        // tile above this wave's diagonal, or no live query in the wave
 
     // S^T for the two 32-key sub-tiles
     f32x16 sacc[2];
@@ -316,7 +319,7 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
         }
       }
   }
-  if (qpos < S) {
+  if (qpos >= 0) {
     const float inv = 1.0f / l_run;
     f16* orow = out + (size_t)(row0 + qpos) * ldo + head * HD;
 #pragma unroll
