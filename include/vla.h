@@ -47,12 +47,15 @@ typedef struct vla_ctx vla_ctx;
 enum vla_dtype { VLA_F32 = 0, VLA_BF16 = 1 };
 
 /* Arithmetic of the VLA_BF16 path (config.precision; ignored for VLA_F32).
- *   VLA_PREC_HIGH  activations that feed a matrix core (the normalised rows of the attention block, queries, keys,
- *                  values, softmax weights, attention output, SwiGLU output) and the cached keys / values are
- *                  carried as two half-precision terms hi + lo (about 22 significant bits); meets the stated
- *                  tolerances (logits 2e-2, log-probs 1e-2) at 32 layers.  The KV cache takes twice the bytes.
- *   VLA_PREC_FAST  one half-precision term everywhere: about 1.5x faster, logit error about 3x larger
- *                  (rms 7e-3 / max 3e-2 at 32 layers). */
+ *   VLA_PREC_HIGH  in the first config.two_term_layers layers every activation that feeds a matrix core (the
+ *                  normalised rows of both blocks, queries, keys, values, softmax weights, attention output, SwiGLU
+ *                  output) and the cached keys / values are carried as two terms hi + lo (about 22 significant
+ *                  bits; the cache of those layers takes 1.5x the bytes); the layers after them run with one
+ *                  half-precision term.  Rounding errors made in the first layers are amplified by all the
+ *                  layers that follow and dominate the logit error; with the default of 4 such layers the
+ *                  stated tolerances (logits 2e-2, log-probs 1e-2) hold at 32 layers with a margin of 3.
+ *   VLA_PREC_FAST  one half-precision term everywhere: about 5 % faster than the default above, logit error
+ *                  about 5x larger (rms 7e-3 / max 3e-2 at 32 layers). */
 enum vla_precision { VLA_PREC_HIGH = 0, VLA_PREC_FAST = 1 };
 
 enum vla_status {
@@ -82,6 +85,8 @@ typedef struct {
   int64_t max_prefill_tokens;
   int32_t value_max_steps;    /* rows of the value head's step-embedding table; 0 = no value head */
   int32_t precision;          /* enum vla_precision */
+  int32_t two_term_layers;    /* VLA_PREC_HIGH: leading layers with two-term operands; 0 = default (4); values
+                               * above n_layers mean all layers; negative values are rejected */
 } vla_config;
 
 /* One named tensor handed to vla_load_weights: device pointer, row-major, nn.Linear layout

@@ -33,17 +33,18 @@ TWO_TERM_POINTS = ("hn_a", "q", "k", "v", "att", "act")
 SINGLE_TERM_LEFT = ("hn_f",)
 
 
-def prefix_logits(pol: O.OraclePolicy, x: np.ndarray, rnd=None, points=POINTS, n_layers=None):
+def prefix_logits(pol: O.OraclePolicy, x: np.ndarray, rnd=None, points=POINTS, n_layers=None, first_layer=0):
     """Action logits at the last of the prefix rows x [S, d]; rnd (None = exact) is applied at `points`:
     hn_a / hn_f = the normalised rows that feed the QKV / the gate-up projections, q, k (after the rotary
-    embedding), v, att = attention output, act = SwiGLU output."""
+    embedding), v, att = attention output, act = SwiGLU output; and only in layers >= first_layer (the layers
+    before it stand for layers whose operands are carried as two terms)."""
     s = pol.s
     H, hd = s.n_heads, s.head_dim
     n = x.shape[0]
     pos = np.arange(n)
-    R = (lambda key, v: rnd(v) if (rnd is not None and key in points) else v)
     for l in range(s.n_layers if n_layers is None else n_layers):
         p = f"layers.{l}."
+        R = (lambda key, v: rnd(v) if (rnd is not None and key in points and l >= first_layer) else v)
         h = R("hn_a", O.rms_norm(x, pol.W(p + "attn_norm"), s.rms_eps))
         q = R("q", O.rope((h @ pol.W(p + "wq").T).reshape(n, H, hd), pos, s.rope_theta))
         k = R("k", O.rope((h @ pol.W(p + "wk").T).reshape(n, H, hd), pos, s.rope_theta))

@@ -31,7 +31,8 @@ class vla_config(C.Structure):
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("n_action_bins", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float),
                 ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32),
-                ("max_prefill_tokens", C.c_int64), ("value_max_steps", C.c_int32), ("precision", C.c_int32)]
+                ("max_prefill_tokens", C.c_int64), ("value_max_steps", C.c_int32), ("precision", C.c_int32),
+                ("two_term_layers", C.c_int32)]
 
 
 class vla_tensor(C.Structure):
@@ -342,24 +343,25 @@ class Batcher:
 
 
 def make_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, value_max_steps: int = 0,
-                precision: int = VLA_PREC_HIGH) -> vla_config:
+                precision: int = VLA_PREC_HIGH, two_term_layers: int = 0) -> vla_config:
     return vla_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
                       shape.n_action_bins, shape.rope_theta, shape.rms_eps,
                       VLA_BF16 if shape.dtype == "bf16" else VLA_F32, max_batch, max_seq, max_prefill_tokens,
-                      value_max_steps, precision)
+                      value_max_steps, precision, two_term_layers)
 
 
 class VlaPolicy:
     """Holds a context plus the torch-allocated arena / KV cache / workspace it is bound to."""
 
     def __init__(self, shape, max_batch: int, max_seq: int, max_prefill_tokens: int, device="cuda:0",
-                 value_max_steps: int = 0, precision: int = VLA_PREC_HIGH):
+                 value_max_steps: int = 0, precision: int = VLA_PREC_HIGH, two_term_layers: int = 0):
         import torch
         self.torch = torch
         self.shape = shape
         self.device = torch.device(device)
         self.dtype_code = VLA_BF16 if shape.dtype == "bf16" else VLA_F32
-        self.cfg = make_config(shape, max_batch, max_seq, max_prefill_tokens, value_max_steps, precision)
+        self.cfg = make_config(shape, max_batch, max_seq, max_prefill_tokens, value_max_steps, precision,
+                               two_term_layers)
         self.ctx = vla_create(self.cfg)
         a, k, w = vla_query_sizes(self.cfg)
         self.sizes = (a, k, w)

@@ -28,7 +28,7 @@ constexpr int kMaxDevices = 64;
 
 struct LayerW {
   size_t g_attn, w_qkv, w_o, g_ffn, w_gu, w_down;   // byte offsets into the weight arena
-  size_t w_qkv8, w_o8, w_down8;                     // 8-bit copies for 8-bit low terms (two-term mode), else unused
+  size_t w_qkv8, w_o8, w_gu8, w_down8;              // 8-bit copies for 8-bit low terms (two-term layers), else unused
 };
 struct ArenaLayout {
   size_t embed, g_final, head, total;
@@ -46,12 +46,23 @@ size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
 // Two-term mode of the 16-bit path: activations that feed a matrix core, and the cached keys and values, are
 // carried as hi + lo half-precision terms.
 inline bool two_term(const vla_config& c) { return c.dtype == VLA_BF16 && c.precision == VLA_PREC_HIGH; }
+// ... in the leading layers only: nearly all of the logit error that single-term operands cause enters in the
+// first few layers (the rounding model: rounding every operand from layer 4 on leaves 18 % of the rms error of
+// rounding everywhere, from layer 2 on 25 %), so the layers after them run single-term.
+constexpr int kDefaultTwoTermLayers = 4;
+inline int two_term_layers(const vla_config& c) {
+  if (!two_term(c)) return 0;
+  const int n = c.two_term_layers > 0 ? c.two_term_layers : kDefaultTwoTermLayers;
+  return n < c.n_layers ? n : c.n_layers;
+}
+inline bool two_term_layer(const vla_config& c, int l) { return l < two_term_layers(c); }
 // Row-major two-term operands of the prefill GEMMs with contraction length K carry their low terms as bytes (and
 // the GEMM uses the 8-bit copy of its weights for them) when K allows whole pairs of 64-k slabs; otherwise as
-// half precision.  Row pitch of such an operand in halves; mode as the producing kernels take it.
-inline bool lo8(const vla_config& c, int K) { return two_term(c) && K % 128 == 0; }
-inline int lo_mode(const vla_config& c, int K) { return !two_term(c) ? 0 : (lo8(c, K) ? 2 : 1); }
-inline int two_pitch(const vla_config& c, int K) { return !two_term(c) ? K : (lo8(c, K) ? K + K / 2 : 2 * K); }
+// half precision.  Row pitch of such an operand in halves; mode as the producing kernels take it.  `two`: whether
+// the layer at hand is a two-term layer.
+inline bool lo8(bool two, int K) { return two && K % 128 == 0; }
+inline int lo_mode(bool two, int K) { return !two ? 0 : (lo8(two, K) ? 2 : 1); }
+inline int two_pitch(bool two, int K) { return !two ? K : (lo8(two, K) ? K + K / 2 : 2 * K); }
 
 ArenaLayout arena_layout(const vla_config& c) {
   ArenaLayout a;
@@ -60,16 +71,19 @@ ArenaLayout arena_layout(const vla_config& c) {
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   a.embed = take((size_t)c.vocab * d * es);
   a.layers.resize(c.n_layers);
+  int li = 0;
   for (auto& l : a.layers) {
+    const bool two = two_term_layer(c, li++);
     l.g_attn = take(d * 4);
     l.w_qkv = take(3 * d * d * es);
     l.w_o = take(d * d * es);
     l.g_ffn = take(d * 4);
     l.w_gu = take(2 * f * d * es);
     l.w_down = take(d * f * es);
-    l.w_qkv8 = take(lo8(c, (int)d) ? 3 * d * d : 0);
-    l.w_o8 = take(lo8(c, (int)d) ? d * d : 0);
-    l.w_down8 = take(lo8(c, (int)f) ? d * f : 0);
+    l.w_qkv8 = take(lo8(two, (int)d) ? 3 * d * d : 0);
+    l.w_o8 = take(lo8(two, (int)d) ? d * d : 0);
+    l.w_gu8 = take(lo8(two, (int)d) ? 2 * f * d : 0);
+    l.w_down8 = take(lo8(two, (int)f) ? d * f : 0);
   }
   a.g_final = take(d * 4);
   a.head = take((size_t)c.n_action_bins * d * es);
@@ -96,7 +110,7 @@ size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one l
 }
 // one set of planes [layer][K|V][slot][head][position][head_dim]; two-term mode appends a second set with the low terms
 size_t kv_plane_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
-size_t kv_lo_bytes(const vla_config& c) { return two_term(c) ? 2 * (size_t)c.n_layers * kv_layer_stride(c) : 0; }   // one byte each
+size_t kv_lo_bytes(const vla_config& c) { return 2 * (size_t)two_term_layers(c) * kv_layer_stride(c); }   // one byte each
 size_t kv_bytes(const vla_config& c) { return kv_plane_bytes(c) + align_up(kv_lo_bytes(c)); }
 
 size_t max_rows(const vla_config& c) {
@@ -161,6 +175,7 @@ const char* check_config(const vla_config& c) {
   if (c.max_batch <= 0 || c.max_seq <= 0 || c.max_prefill_tokens <= 0) return "capacities must be positive";
   if (c.value_max_steps < 0) return "value_max_steps must be >= 0";
   if (c.precision != VLA_PREC_HIGH && c.precision != VLA_PREC_FAST) return "precision must be VLA_PREC_HIGH or VLA_PREC_FAST";
+  if (c.two_term_layers < 0) return "two_term_layers must not be negative";
   if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128 && c.head_dim != 256) return "head_dim must be 32, 64, 128 or 256";
   if (c.d_model % 4) return "d_model must be a multiple of 4";
   if (c.dtype == VLA_BF16) {
@@ -286,7 +301,7 @@ RopeKv layer_rope_kv(vla_ctx* ctx, int l) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const size_t es = elem_size(c.dtype), kvl = kv_layer_stride(c) * es;   // bytes of K (or V) of one layer
-  const bool two = two_term(c);
+  const bool two = two_term_layer(c, l);
   RopeKv rk;
   rk.q = ctx->work + w.q;
   rk.k_cache = ctx->kv + (size_t)(2 * l) * kvl;
@@ -307,14 +322,13 @@ RopeKv layer_rope_kv(vla_ctx* ctx, int l) {
 
 // need / n_need (prefill only): the packed rows whose final hidden state is read afterwards.  When they are
 // few, the last layer's output projection and feed-forward run on those rows alone.
-// Two-term mode (16-bit path): the normalised rows that feed the QKV GEMM, q / k / v, the attention output and the
-// SwiGLU output are carried as [hi | lo]; the rows that feed the gate/up GEMM stay single-term.
+// Two-term layers (16-bit path, the leading layers of the high-precision mode): the normalised rows that feed the
+// QKV and the gate/up GEMMs, q / k / v, the attention output and the SwiGLU output are carried as [hi | lo].
 template <class T>
 int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_t* need = nullptr, int n_need = 0) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const int d = c.d_model, f = c.d_ffn;
-  const int pd = two_pitch(c, d), pf = two_pitch(c, f);     // row pitch of two-term operands with K = d, f
   const f16* no8 = nullptr;
   float* x = at<float>(ctx->work, w.x);
   T* hn = at<T>(ctx->work, w.hn);
@@ -329,15 +343,17 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& lw = ctx->al.layers[l];
     const RopeKv rk = layer_rope_kv(ctx, l);
+    const bool two = two_term_layer(c, l);
+    const int pd = two_pitch(two, d), pf = two_pitch(two, f);     // row pitch of this layer's operands with K = d, f
     {
       ProfScope ps(ctx, FAM_NORM, st);
-      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, lo_mode(c, d), st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, lo_mode(two, d), st);
     }
     {
       ProfScope ps(ctx, fam_gemm + 0, st);
       if constexpr (sizeof(T) == 2) {
         gemm_f16_qkv(GemmF16{(const f16*)hn, pd, at<f16>(ctx->arena, lw.w_qkv), rows, 3 * d, pd, d,
-                             lo8(c, d) ? at<f16>(ctx->arena, lw.w_qkv8) : no8}, rk, st);
+                             lo8(two, d) ? at<f16>(ctx->arena, lw.w_qkv8) : no8}, rk, st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_qkv), gemm_out, rows, 3 * d, d, st);
         rope_kv_f32(gemm_out, rows, rk, st);
@@ -348,7 +364,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       if constexpr (sizeof(T) == 2) {
         flash_prefill((const f16*)q, rk.ldq, (const f16*)rk.k_cache, (const f16*)rk.v_cache, (const unsigned char*)rk.k_lo,
                       (const unsigned char*)rk.v_lo, at<int32_t>(ctx->work, w.cu_patch), at<int32_t>(ctx->work, w.cu_instr),
-                      ctx->run_slots, (f16*)att, pd, lo8(c, d), ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim,
+                      ctx->run_slots, (f16*)att, pd, lo8(two, d), ctx->run_B, ctx->run_max_len, c.n_heads, c.head_dim,
                       kv_pitch(c), st);
       } else {
         attention_rows<T>(q, d, (const T*)rk.k_cache, (const T*)rk.v_cache, tok_seq, tok_pos, att, d, rows,
@@ -369,7 +385,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       ProfScope ps(ctx, fam_gemm + 1, st);
       if constexpr (sizeof(T) == 2) {
         gemm_f16_resid(GemmF16{(const f16*)att, pd, at<f16>(ctx->arena, lw.w_o), rows, d, pd, d,
-                               lo8(c, d) ? at<f16>(ctx->arena, lw.w_o8) : no8}, x, d, st);
+                               lo8(two, d) ? at<f16>(ctx->arena, lw.w_o8) : no8}, x, d, st);
       } else {
         gemm_f32((const float*)att, d, at<float>(ctx->arena, lw.w_o), gemm_out, rows, d, d, st);
         resid_add_f32(x, gemm_out, (size_t)rows * d, st);
@@ -377,13 +393,13 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
     }
     {
       ProfScope ps(ctx, FAM_NORM, st);
-      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, 0, st);
+      rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_ffn), hn, rows, d, c.rms_eps, nullptr, lo_mode(two, d), st);
     }
     {
       ProfScope ps(ctx, fam_gemm + 2, st);
       if constexpr (sizeof(T) == 2) {
-        gemm_f16_swiglu(GemmF16{(const f16*)hn, d, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, d, d, no8}, (f16*)act, pf,
-                        lo_mode(c, f), st);
+        gemm_f16_swiglu(GemmF16{(const f16*)hn, pd, at<f16>(ctx->arena, lw.w_gu), rows, 2 * f, pd, d,
+                                lo8(two, d) ? at<f16>(ctx->arena, lw.w_gu8) : no8}, (f16*)act, pf, lo_mode(two, f), st);
       } else {
         gemm_f32((const float*)hn, d, at<float>(ctx->arena, lw.w_gu), gemm_out, rows, 2 * f, d, st);
         swiglu_f32(gemm_out, (float*)act, rows, f, st);
@@ -393,7 +409,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
       ProfScope ps(ctx, fam_gemm + 3, st);
       if constexpr (sizeof(T) == 2) {
         gemm_f16_resid(GemmF16{(const f16*)act, pf, at<f16>(ctx->arena, lw.w_down), rows, d, pf, f,
-                               lo8(c, f) ? at<f16>(ctx->arena, lw.w_down8) : no8}, x, d, st);
+                               lo8(two, f) ? at<f16>(ctx->arena, lw.w_down8) : no8}, x, d, st);
       } else {
         gemm_f32((const float*)act, f, at<float>(ctx->arena, lw.w_down), gemm_out, rows, d, f, st);
         resid_add_f32(x, gemm_out, (size_t)rows * d, st);
@@ -406,6 +422,7 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
 // Fragment-order activations of the weight-streaming GEMMs: block row r0/32 of an [M, K] operand, and in two-term
 // mode the matching low-term blocks, kept max_rows * K elements further on in the same buffer.
 inline f16* frag_rows(f16* base, int row0, int K) { return base + (size_t)(row0 / 32) * (K / 16) * 512; }
+// (nullptr when no layer is a two-term layer; single-term layers of a two-term configuration pass nullptr on)
 inline f16* frag_lo(const vla_config& c, f16* base, int K) { return two_term(c) ? base + max_rows(c) * (size_t)K : nullptr; }
 
 // Decode step of the 16-bit path: weight-streaming split-K GEMMs over chunks of at most kSkinnyMaxRows rows (a
@@ -432,41 +449,45 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
                   ks, B, r0, st);
     }
   };
+  f16* const none = nullptr;
   {
     ProfScope ps(ctx, FAM_NORM, st);
-    rmsnorm_frag(x, B, d, at<float>(ctx->arena, ctx->al.layers[0].g_attn), c.rms_eps, hn, hn_lo, st);
+    rmsnorm_frag(x, B, d, at<float>(ctx->arena, ctx->al.layers[0].g_attn), c.rms_eps, hn,
+                 two_term_layer(c, 0) ? hn_lo : none, st);
   }
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& lw = ctx->al.layers[l];
-    const RopeKv rk = layer_rope_kv(ctx, l);
+    const RopeKv rk = layer_rope_kv(ctx, l);      // low-term planes only in two-term layers
+    const bool two = two_term_layer(c, l), two_next = two_term_layer(c, l + 1);
     {
       ProfScope ps(ctx, FAM_GEMM_QKV_DECODE, st);
-      gemm(hn, hn_lo, lw.w_qkv, 3 * d, d, ks_qkv);
+      gemm(hn, two ? hn_lo : none, lw.w_qkv, 3 * d, d, ks_qkv);
     }
     {
       // the attention kernel itself sums the QKV partials of its (sequence, head), applies RoPE and appends the
       // new cache row
       ProfScope ps(ctx, FAM_ATTN_DECODE, st);
       decode_attention_fused(part, ks_qkv, B, rk.rope_cos, rk.rope_sin, (f16*)rk.k_cache, (f16*)rk.v_cache,
-                             (unsigned char*)rk.k_lo, (unsigned char*)rk.v_lo, rk.tok_seq, rk.tok_pos, att, att_lo, B, d, c.n_heads, c.head_dim,
+                             (unsigned char*)rk.k_lo, (unsigned char*)rk.v_lo, rk.tok_seq, rk.tok_pos, att, two ? att_lo : none, B, d,
+                             c.n_heads, c.head_dim,
                              kv_pitch(c), st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_O_DECODE, st);
-      gemm(att, att_lo, lw.w_o, d, d, ks_o);
-      // the rows that feed the gate/up GEMM stay single-term
-      reduce_resid_norm(part, ks_o, B, 0, B, d, x, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, nullptr, 0, st);
+      gemm(att, two ? att_lo : none, lw.w_o, d, d, ks_o);
+      reduce_resid_norm(part, ks_o, B, 0, B, d, x, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, two ? hn_lo : none, 0,
+                        st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_GATEUP_DECODE, st);
-      gemm(hn, nullptr, lw.w_gu, 2 * f, d, ks_gu);
-      reduce_swiglu(part, ks_gu, B, 0, B, f, act, act_lo, 0, st);
+      gemm(hn, two ? hn_lo : none, lw.w_gu, 2 * f, d, ks_gu);
+      reduce_swiglu(part, ks_gu, B, 0, B, f, act, two ? act_lo : none, 0, st);
     }
     {
       ProfScope ps(ctx, FAM_GEMM_DOWN_DECODE, st);
       const float* next_gain = l + 1 < c.n_layers ? at<float>(ctx->arena, ctx->al.layers[l + 1].g_attn) : nullptr;
-      gemm(act, act_lo, lw.w_down, d, f, ks_dn);
-      reduce_resid_norm(part, ks_dn, B, 0, B, d, x, next_gain, c.rms_eps, hn, hn_lo, 0, st);
+      gemm(act, two ? act_lo : none, lw.w_down, d, f, ks_dn);
+      reduce_resid_norm(part, ks_dn, B, 0, B, d, x, next_gain, c.rms_eps, hn, two_next ? hn_lo : none, 0, st);
     }
   }
   return VLA_OK;
@@ -479,30 +500,34 @@ void run_tail_f16(vla_ctx* ctx, const LayerW& lw, const int32_t* need, int n_nee
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
   const int d = c.d_model, f = c.d_ffn;
-  const bool two = two_term(c);
+  const bool two = two_term_layer(c, c.n_layers - 1);    // the layer this is the tail of
   ProfScope ps(ctx, FAM_TAIL, st);
   float* x = at<float>(ctx->work, w.x);
   f16* att = at<f16>(ctx->work, w.att);
   f16* att_frag = at<f16>(ctx->work, w.q);
   f16* hn = at<f16>(ctx->work, w.hn);
   f16* act = at<f16>(ctx->work, w.act);
-  f16 *att_frag_lo = frag_lo(c, att_frag, d), *act_lo = frag_lo(c, act, f);
+  f16* const none = nullptr;
+  f16* att_frag_lo = two ? frag_lo(c, att_frag, d) : none;
+  f16* hn_lo = two ? frag_lo(c, hn, d) : none;
+  f16* act_lo = two ? frag_lo(c, act, f) : none;
   float* part = at<float>(ctx->work, w.part);
   const size_t pad32 = ((size_t)n_need + 31) / 32 * 32;
-  // the float32 residual rows of the compact set sit behind the SwiGLU fragments (hi, and lo in two-term mode: the
-  // lo blocks start max_rows * f elements in, so the rows go behind the whole buffer's used part)
+  // the float32 residual rows of the compact set sit behind the SwiGLU fragments (hi, and lo in a two-term
+  // layer: the lo blocks start max_rows * f elements in, so the rows go behind the whole buffer's used part)
   float* x_c = reinterpret_cast<float*>(reinterpret_cast<char*>(act) +
                                         (two ? max_rows(c) * (size_t)f * sizeof(f16) : 0) +
                                         align_up(pad32 * f * sizeof(f16)));
   const int ks_o = skinny_ksplit(d, d), ks_gu = skinny_ksplit(2 * f, d), ks_dn = skinny_ksplit(d, f);
   const int chunk = (int)(part_rows(c) < (size_t)kSkinnyMaxRows ? part_rows(c) : (size_t)kSkinnyMaxRows);
-  gather_tail(att, two_pitch(c, d), lo8(c, d), x, need, n_need, d, att_frag, att_frag_lo, x_c, st);
+  gather_tail(att, two_pitch(two, d), lo8(two, d), x, need, n_need, d, att_frag, att_frag_lo, x_c, st);
   for (int r0 = 0; r0 < n_need; r0 += chunk) {
     const int m = n_need - r0 < chunk ? n_need - r0 : chunk;
     skinny_gemm(frag_rows(att_frag, r0, d), two ? frag_rows(att_frag_lo, r0, d) : nullptr, at<f16>(ctx->arena, lw.w_o),
                 part, m, d, d, ks_o, m, 0, st);
-    reduce_resid_norm(part, ks_o, m, 0, m, d, x_c, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, nullptr, r0, st);
-    skinny_gemm(frag_rows(hn, r0, d), nullptr, at<f16>(ctx->arena, lw.w_gu), part, m, 2 * f, d, ks_gu, m, 0, st);
+    reduce_resid_norm(part, ks_o, m, 0, m, d, x_c, at<float>(ctx->arena, lw.g_ffn), c.rms_eps, hn, hn_lo, r0, st);
+    skinny_gemm(frag_rows(hn, r0, d), two ? frag_rows(hn_lo, r0, d) : nullptr, at<f16>(ctx->arena, lw.w_gu), part, m,
+                2 * f, d, ks_gu, m, 0, st);
     reduce_swiglu(part, ks_gu, m, 0, m, f, act, act_lo, r0, st);
     skinny_gemm(frag_rows(act, r0, f), two ? frag_rows(act_lo, r0, f) : nullptr, at<f16>(ctx->arena, lw.w_down), part, m, d,
                 f, ks_dn, m, 0, st);
@@ -944,6 +969,8 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
   const ArenaLayout& a = ctx->al;
   const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab, A = c.n_action_bins;
   const bool bf = c.dtype == VLA_BF16;
+  const int np = policy_slots(c);
+  const bool two = s >= 3 && s < np && two_term_layer(c, (s - 3) / 9);   // tensor of a two-term layer
   auto to_f32 = [&](size_t off, size_t n) {
     if (bf) convert_copy<bf16>((const bf16*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
     else convert_copy<float>((const float*)t->dev_ptr, at<float>(ctx->arena, off), n, st);
@@ -952,7 +979,7 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
   auto matrix = [&](size_t off, size_t off8, int64_t rows, int64_t K, int64_t row0, int mode) {
     if (bf) {
       pack_weight_f16((const bf16*)t->dev_ptr, (int)rows, (int)K, at<f16>(ctx->arena, off),
-                      (mode == 0 && lo8(c, (int)K)) ? at<unsigned char>(ctx->arena, off8) : nullptr, (int)row0, mode,
+                      lo8(two, (int)K) ? at<unsigned char>(ctx->arena, off8) : nullptr, (int)row0, mode,
                       at<int32_t>(ctx->work, ctx->wl.range_flag), st);
     } else {
       const int64_t r0 = mode == 2 ? rows : row0;   // float32 path keeps [gate rows | up rows]
@@ -963,7 +990,6 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
     if (bf) plain_copy<bf16>((const bf16*)src, at<bf16>(ctx->arena, off), n, st);
     else plain_copy<float>((const float*)src, at<float>(ctx->arena, off), n, st);
   };
-  const int np = policy_slots(c);
   if (s == 0) raw(t->dev_ptr, a.embed, (size_t)(V * d));
   else if (s == 1) to_f32(a.g_final, d);
   else if (s == 2) {
@@ -978,8 +1004,8 @@ void write_slot(vla_ctx* ctx, int s, const vla_tensor* t, hipStream_t st) {
       case 3: matrix(lw.w_qkv, lw.w_qkv8, d, d, 2 * d, 0); break;
       case 4: matrix(lw.w_o, lw.w_o8, d, d, 0, 0); break;
       case 5: to_f32(lw.g_ffn, d); break;
-      case 6: matrix(lw.w_gu, 0, f, d, 0, 1); break;     // the rows that feed gate / up stay single-term
-      case 7: matrix(lw.w_gu, 0, f, d, 0, 2); break;
+      case 6: matrix(lw.w_gu, lw.w_gu8, f, d, 0, 1); break;
+      case 7: matrix(lw.w_gu, lw.w_gu8, f, d, 0, 2); break;
       default: matrix(lw.w_down, lw.w_down8, d, f, 0, 0); break;
     }
   } else {

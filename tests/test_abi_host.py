@@ -35,19 +35,27 @@ def test_config_validation_and_sizes():
     arena, kv, work = B.vla_query_sizes(cfg)
     s = wl.shape
     assert kv == 2 * s.n_layers * wl.batch * s.n_heads * (wl.max_seq | 1) * s.head_dim * 2     # odd position pitch
-    # two-term mode keeps a second set of planes with the low terms of the cached keys and values, one byte each
+    # two-term layers keep a second set of planes with the low terms of their cached keys and values, one byte each,
+    # and an 8-bit copy of their matrices for the 8-bit low terms of the operands
     hi = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
-    assert hi.precision == B.VLA_PREC_HIGH
+    assert hi.precision == B.VLA_PREC_HIGH and hi.two_term_layers == 0          # 0 = the default of 4 layers
+    per_layer_kv = kv // s.n_layers
+    per_layer_w8 = 4 * s.d_model ** 2 + 3 * s.d_model * s.d_ffn
     arena_hi, kv_hi, work_hi = B.vla_query_sizes(hi)
-    assert kv_hi == kv + kv // 2 and work_hi > work
-    # ... and an 8-bit copy of the matrices whose operand carries 8-bit low terms (QKV, output, down projections)
-    assert arena_hi - arena >= s.n_layers * (4 * s.d_model ** 2 + s.d_model * s.d_ffn)
+    assert kv_hi == kv + 4 * per_layer_kv // 2 and work_hi > work
+    assert 4 * per_layer_w8 <= arena_hi - arena < 4 * per_layer_w8 + (1 << 20)
+    for n, n_eff in [(1, 1), (7, 7), (32, 32), (1000, 32)]:
+        cn = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290, two_term_layers=n)
+        arena_n, kv_n, work_n = B.vla_query_sizes(cn)
+        assert kv_n == kv + n_eff * per_layer_kv // 2 and work_n == work_hi
+        assert n_eff * per_layer_w8 <= arena_n - arena < n_eff * per_layer_w8 + (1 << 20)
     assert arena >= 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model)
     assert arena < 2 * (s.n_matrix_params + (s.vocab + 256) * s.d_model) + (4 << 20)   # head is slimmed: no second [V,d] matrix
     ctx = B.vla_create(cfg)
     B.vla_destroy(ctx)
     for field, value in [("n_heads", 31), ("dtype", 5), ("n_action_bins", 0), ("n_action_bins", 40000),
-                         ("max_seq", 0), ("head_dim", 100), ("rope_theta", 0.0), ("precision", 2)]:
+                         ("max_seq", 0), ("head_dim", 100), ("rope_theta", 0.0), ("precision", 2),
+                         ("two_term_layers", -1)]:
         bad = B.make_config(wl.shape, wl.batch, wl.max_seq, wl.batch * 290)
         setattr(bad, field, value)
         with pytest.raises(B.VlaError) as e:

@@ -24,8 +24,8 @@ def as_f32(bits):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("batch,fast", [(200, False), (300, False), (300, True)],
-                         ids=["B200_two_term", "B300_two_term", "B300_fast"])
+@pytest.mark.parametrize("batch,fast", [(200, False), (300, False), (200, "first"), (300, True)],
+                         ids=["B200_two_term", "B300_two_term", "B200_two_term_layer0_only", "B300_fast"])
 def test_every_row_of_a_large_ragged_batch(batch, fast):
     """More sequences than one weight-streaming launch takes (256 rows) and than one 128-row group of the
     last prefill layer: every row of the prefill and of three decode steps is compared with the oracle."""

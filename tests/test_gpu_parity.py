@@ -13,18 +13,21 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def make_policy(wl, weights, max_batch=None, extra_seq=0, fast=False):
-    """fast=True: the single-term mode of the 16-bit path (VLA_PREC_FAST); default is the two-term mode."""
+    """fast: False = the default high-precision mode of the 16-bit path (two-term operands in the leading layers:
+    all layers of the small shapes, 4 of the 32 at 7B); True = the single-term mode (VLA_PREC_FAST); "first" = two-term
+    operands in layer 0 only, so that a small model has layers of both kinds; "all" = in every layer."""
     from paper_2603_18464_amd import VlaPolicy
     from paper_2603_18464_amd.binding import VLA_PREC_FAST, VLA_PREC_HIGH
     B = max_batch or wl.batch
     # token capacity: the longest prefix for every slot, plus the fed positions of the one-pass entry points
     pol = VlaPolicy(wl.shape, B, wl.max_seq + extra_seq, B * (wl.n_patches + wl.instr_len[1] + wl.n_tokens - 1),
-                    precision=VLA_PREC_FAST if fast else VLA_PREC_HIGH)
+                    precision=VLA_PREC_FAST if fast is True else VLA_PREC_HIGH,
+                    two_term_layers={"first": 1, "all": wl.shape.n_layers}.get(fast, 0))
     pol.load_weights(weights)
     return pol
 
 
-FAST_MODES = pytest.mark.parametrize("fast", [False, True], ids=["two_term", "fast"])
+FAST_MODES = pytest.mark.parametrize("fast", [False, "first", True], ids=["two_term", "two_term_layer0_only", "fast"])
 
 
 def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, offset=None, fast=False, weights=None):
@@ -46,10 +49,10 @@ def run_both(wl, obs=None, gumbel=None, rows=None, mode="cached", scale=None, of
     if scale is not None:
         from oracle.vla_oracle import detokenise
         ora["actions"] = detokenise(ora["tokens"], wl.shape.n_action_bins, wl.action_dim, scale, offset)
-    tol = P.tolerances(wl, fast)
+    tol = P.tolerances(wl, fast is True)
     stats = P.check_free_running(wl, gpu, ora, rows, tol)
     tf_err, tf_rms = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
-    print(f"\n[{wl.name}{' fast' if fast else ''}] free-running {stats}; teacher-forced logit err max {tf_err:.3e} rms {tf_rms:.3e}")
+    print(f"\n[{wl.name}{' mode ' + str(fast) if fast else ''}] free-running {stats}; teacher-forced logit err max {tf_err:.3e} rms {tf_rms:.3e}")
     pol.close()
     return stats, gpu, ora
 
@@ -137,13 +140,14 @@ def test_c2_bf16_whole_batch(fast):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,fast", [("C3", False), ("C4", False), ("C5", False), ("C3", True)],
-                         ids=["C3", "C4", "C5", "C3_fast_mode"])
+@pytest.mark.parametrize("name,fast", [("C3", False), ("C4", False), ("C5", False), ("C3", "all"), ("C3", True)],
+                         ids=["C3", "C4", "C5", "C3_two_term_in_all_layers", "C3_fast_mode"])
 def test_7b_workloads_against_stored_oracle_rows(name, fast):
     """Full-size batch in the benchmark's launch configuration; the oracle's rows were written by
     tests/golden/make_7b_goldens.py (sequences are independent, so rows of a batched run must equal
-    the same sequences run alone).  The default two-term mode is held to the stated tolerances; the single-term
-    fast mode is run once (C3) against its own wider bars."""
+    the same sequences run alone).  The default mode (two-term operands in the first 4 layers) and two-term
+    operands in all layers are held to the stated tolerances; the single-term fast mode is run once (C3) against
+    its own wider bars."""
     import torch
     path = os.path.join(GOLDEN, f"{name.lower()}_oracle.npz")
     if not os.path.exists(path):
@@ -169,7 +173,7 @@ def test_7b_workloads_against_stored_oracle_rows(name, fast):
     assert np.isfinite(gpu["logits"]).all() and np.isfinite(gpu["logp"]).all()
     assert (gpu["tokens"] >= 0).all() and (gpu["tokens"] < wl.shape.n_action_bins).all()
     assert (gpu["logp"] <= 0).all()
-    tol = P.tolerances(wl, fast)
+    tol = P.tolerances(wl, fast is True)
     stats = P.check_free_running(wl, gpu, ora, rows, tol)
     print(f"[{name}] teacher-forced pass", flush=True)
     tf_err, tf_rms = P.check_teacher_forced(pol, wl, dev, obs, ora, rows, gpu["tokens"], tol)
