@@ -289,7 +289,8 @@ struct ProfScope {
 const char* kFamilyNames[FAM_COUNT] = {"gemm_qkv_prefill", "gemm_o_prefill", "gemm_gateup_prefill",
                                        "gemm_down_prefill", "attn_prefill", "gemm_qkv_decode", "gemm_o_decode",
                                        "gemm_gateup_decode", "gemm_down_decode", "attn_decode", "rmsnorm",
-                                       "head_select", "misc", "prefill_tail"};
+                                       "head_select", "misc", "prefill_tail", "gemm_qkv_two_prefill",
+                                       "gemm_o_two_prefill", "gemm_gateup_two_prefill", "gemm_down_two_prefill"};
 
 template <class T> T* at(char* base, size_t off) { return reinterpret_cast<T*>(base + off); }
 
@@ -338,13 +339,14 @@ int run_layers(vla_ctx* ctx, int rows, bool decode, hipStream_t st, const int32_
   float* gemm_out = ctx->part_override ? ctx->part_override : at<float>(ctx->work, w.scratch);
   const int32_t* tok_seq = at<int32_t>(ctx->work, w.tok_seq);
   const int32_t* tok_pos = at<int32_t>(ctx->work, w.tok_pos);
-  const int fam_gemm = decode ? FAM_GEMM_QKV_DECODE : FAM_GEMM_QKV_PREFILL;   // + 0 qkv, 1 o, 2 gate-up, 3 down
   const int fam_attn = decode ? FAM_ATTN_DECODE : FAM_ATTN_PREFILL;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& lw = ctx->al.layers[l];
     const RopeKv rk = layer_rope_kv(ctx, l);
     const bool two = two_term_layer(c, l);
     const int pd = two_pitch(two, d), pf = two_pitch(two, f);     // row pitch of this layer's operands with K = d, f
+    const int fam_gemm = decode ? FAM_GEMM_QKV_DECODE                  // + 0 qkv, 1 o, 2 gate-up, 3 down
+                                : (two ? FAM_GEMM_QKV_TWO_PREFILL : FAM_GEMM_QKV_PREFILL);
     {
       ProfScope ps(ctx, FAM_NORM, st);
       rmsnorm<T>(x, nullptr, at<float>(ctx->arena, lw.g_attn), hn, rows, d, c.rms_eps, nullptr, lo_mode(two, d), st);

@@ -55,6 +55,10 @@ enum Family {
   FAM_HEAD,
   FAM_MISC,
   FAM_TAIL,      // last prefill layer restricted to the rows that feed the head
+  FAM_GEMM_QKV_TWO_PREFILL,      // the prefill GEMMs of two-term layers (with their low-term pass), same order
+  FAM_GEMM_O_TWO_PREFILL,
+  FAM_GEMM_GATEUP_TWO_PREFILL,
+  FAM_GEMM_DOWN_TWO_PREFILL,
   FAM_COUNT
 };
 
