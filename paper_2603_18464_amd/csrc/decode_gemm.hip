@@ -21,7 +21,7 @@ namespace vla {
 // used for the hi and the lo activation fragments (weights are read once, the MFMA work doubles).
 // Output rows: the M rows of this launch are rows row0 .. row0 + M - 1 of planes of plane_rows rows each.
 template <int MT, int D, bool TWO>
-__global__ __launch_bounds__(256, MT <= 2 ? 2 : 1) void skinny_gemm_kernel(const f16* __restrict__ Af, const f16* __restrict__ Af_lo,
+__global__ __launch_bounds__(256, (MT <= 2 || !TWO) ? 2 : 1) void skinny_gemm_kernel(const f16* __restrict__ Af, const f16* __restrict__ Af_lo,
                                                           const f16* __restrict__ Wp, float* __restrict__ part, int M,
                                                           int N, int K, int kgroups, int plane_rows, int row0) {
   // Workgroup = one pair of 32-row weight blocks (64 output columns) x one group of 4 K slices; wave w
@@ -185,7 +185,7 @@ void skinny_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* pa
     VLA_SKINNY_CASE(1, 8, 6)
     VLA_SKINNY_CASE(2, 6, 4)
     VLA_SKINNY_CASE(3, 4, 3)
-    VLA_SKINNY_CASE(4, 4, 3)
+    VLA_SKINNY_CASE(4, 3, 3)
     default: break;                                        // callers keep M <= kSkinnyMaxRows
   }
 #undef VLA_SKINNY_CASE
