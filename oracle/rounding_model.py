@@ -26,9 +26,10 @@ def round_f16(x: np.ndarray) -> np.ndarray:
 
 
 POINTS = ("hn_a", "hn_f", "q", "k", "v", "att", "act")
-# The operands the two-term mode of the HIP path carries as hi + lo (their rounding error drops by 2^-11 or, with
-# 8-bit low terms, by a factor of about 12, i.e. out of the picture); what is left is the one point it keeps in a
-# single half-precision term: the normalised rows that feed the gate / up projections.
+# A split of the rounding points used to show that their contributions add in variance and that none of them can
+# be left single-term for free: the normalised rows that feed the gate / up projections against the other six.
+# (An operand carried as hi + lo terms has its rounding error cut by 2^-11 or, with 8-bit low terms, by a factor of
+# about 2^-3 more than one term: out of the picture either way.)
 TWO_TERM_POINTS = ("hn_a", "q", "k", "v", "att", "act")
 SINGLE_TERM_LEFT = ("hn_f",)
 

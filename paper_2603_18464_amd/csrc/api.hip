@@ -43,8 +43,8 @@ struct WorkLayout {
 
 size_t elem_size(int dtype) { return dtype == VLA_BF16 ? 2 : 4; }
 
-// Two-term mode of the 16-bit path: activations that feed a matrix core, and the cached keys and values, are
-// carried as hi + lo half-precision terms.
+// High-precision mode of the 16-bit path: in the leading layers the activations that feed a matrix core, and the
+// cached keys and values, are carried as hi + lo terms (two-term layers); buffers are sized for two terms.
 inline bool two_term(const vla_config& c) { return c.dtype == VLA_BF16 && c.precision == VLA_PREC_HIGH; }
 // ... in the leading layers only: nearly all of the logit error that single-term operands cause enters in the
 // first few layers (the rounding model: rounding every operand from layer 4 on leaves 18 % of the rms error of
@@ -108,7 +108,8 @@ inline int kv_pitch(const vla_config& c) { return c.max_seq | 1; }
 size_t kv_layer_stride(const vla_config& c) {   // elements of K (or V) of one layer
   return (size_t)c.max_batch * c.n_heads * kv_pitch(c) * c.head_dim;
 }
-// one set of planes [layer][K|V][slot][head][position][head_dim]; two-term mode appends a second set with the low terms
+// one set of planes [layer][K|V][slot][head][position][head_dim]; a second set, for the two-term layers only, holds
+// the low terms
 size_t kv_plane_bytes(const vla_config& c) { return 2 * (size_t)c.n_layers * kv_layer_stride(c) * elem_size(c.dtype); }
 size_t kv_lo_bytes(const vla_config& c) { return 2 * (size_t)two_term_layers(c) * kv_layer_stride(c); }   // one byte each
 size_t kv_bytes(const vla_config& c) { return kv_plane_bytes(c) + align_up(kv_lo_bytes(c)); }
@@ -130,7 +131,7 @@ WorkLayout work_layout(const vla_config& c) {
   const size_t es = elem_size(c.dtype), d = c.d_model, f = c.d_ffn, T = max_rows(c), B = c.max_batch;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-  const size_t terms = two_term(c) ? 2 : 1;      // two-term mode: rows [hi | lo], or a second set of fragment blocks
+  const size_t terms = two_term(c) ? 2 : 1;      // two-term layers: rows [hi | lo], or a second set of fragment blocks
   w.x = take(T * d * 4);
   w.hn = take(T * d * es * terms);
   w.q = take(T * d * es * terms);

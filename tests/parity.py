@@ -16,8 +16,8 @@ import numpy as np
 import workloads as W
 from oracle import vla_oracle as O
 
-# Tolerances: the stated bars.  float32: max-abs logit error 1e-4.  16-bit path in its default two-term mode
-# (VLA_PREC_HIGH), at every depth: max-abs logit error 2e-2, log-prob error 1e-2, tokens identical unless the
+# Tolerances: the stated bars.  float32: max-abs logit error 1e-4.  16-bit path in its default mode
+# (VLA_PREC_HIGH: two-term operands in the leading layers), at every depth: max-abs logit error 2e-2, log-prob error 1e-2, tokens identical unless the
 # oracle's top-2 gap of the selection scores is below 1e-2.  The single-term mode (VLA_PREC_FAST) is a named fast
 # mode, not the headline: it meets the same bars up to 12 layers; at 32 layers rounding every matrix-core operand
 # to one half-precision term costs rms 7e-3 / max 3e-2 in the oracle's own fp64 arithmetic

@@ -1,10 +1,10 @@
-"""Why the 16-bit path feeds the matrix cores in half precision, and why its default mode carries most
-operands as two terms.
+"""Why the 16-bit path feeds the matrix cores in half precision, and why its default mode carries the
+operands of the leading layers as two terms.
 
 A pipeline that rounds its GEMM/attention operands to bfloat16 cannot meet a 2e-2 max-abs logit
 tolerance even on the 12-layer workload C2: the oracle's own arithmetic with those roundings (and
 nothing else changed) is already further away.  Half precision operands (3 more mantissa bits) are
-8x closer, but the error grows like the square root of the depth: at the 32 layers of the 7B shape
+8x closer, but the error grows with the depth: at the 32 layers of the 7B shape
 one half-precision term per operand gives rms 7e-3 / max 3e-2 (measured on C3 rows with this model),
 above the 2e-2 / 1e-2 bars.  The contributions of the rounding points add in variance, the rows that
 feed the QKV projections being the largest.  Across the depth they are far from equal: what is rounded in
@@ -46,9 +46,10 @@ def _errors(pol, x, sets, n_layers=None, first_layers=()):
     return e
 
 
-def test_two_term_set_leaves_a_third_of_the_error_on_c2():
-    """Rounding only the point the two-term mode keeps single (the gate/up operand) against rounding all of them;
-    and the contributions add in variance."""
+def test_rounding_points_add_in_variance_and_leading_layers_dominate_on_c2():
+    """Rounding only the gate/up operand, or only the other six points, against rounding all of them: the
+    contributions add in variance, and the gate/up operand alone is more than a third of it (it cannot be left
+    single-term for free); and the leading layers dominate."""
     wl = W.get_workload("C2")
     weights = W.make_weights(wl.shape, wl.seed)
     obs = W.make_observations(wl.scaled(batch=2))
@@ -72,7 +73,7 @@ def test_two_term_set_leaves_a_third_of_the_error_on_c2():
     assert r["from1"] < 0.62 * r["all"] and r["from4"] < 0.36 * r["all"]
 
 
-def test_two_term_set_and_leading_layers_on_the_7b_shape_eight_layers():
+def test_gate_up_operand_and_leading_layers_on_the_7b_shape_eight_layers():
     """The same on one prefix of the 7B-shaped workload C3, cut to 8 of its 32 layers to stay within the CPU
     suite's time: all points rms 3e-3..5e-3 (x2 at 32 layers: 7e-3), gate/up operand alone under 45 % of it."""
     wl = W.get_workload("C3")
