@@ -428,11 +428,14 @@ inline f16* frag_rows(f16* base, int row0, int K) { return base + (size_t)(row0 
 // (nullptr when no layer is a two-term layer; single-term layers of a two-term configuration pass nullptr on)
 inline f16* frag_lo(const vla_config& c, f16* base, int K) { return two_term(c) ? base + max_rows(c) * (size_t)K : nullptr; }
 
-// Decode step of the 16-bit path: weight-streaming split-K GEMMs over chunks of at most kSkinnyMaxRows rows (a
-// 128-row accumulator tile is what a wave's registers hold without spilling; for larger batches the launches of
-// the later chunks follow the first at once and find the matrix they re-read in the 256 MB last-level cache, the
-// largest one being 180 MB), partial planes that span the whole batch, and one kernel after each GEMM that sums the
-// planes and applies the elementwise step for all rows.
+// Decode step of the 16-bit path: split-K GEMMs whose partial planes span the whole batch, and one kernel after each
+// GEMM that sums the planes and applies the elementwise step for all rows.  Batches of up to kSkinnyMaxRows rows
+// use the weight-streaming kernel (every wave an independent stream; a 128-row accumulator tile is what a wave's
+// registers hold without spilling).  Larger batches send their wide matrices through the 256 x 256 tiled kernel in
+// chunks of 256 rows, split over K (activations shared through LDS, every weight read once per 256 rows); a
+// remainder of at most 128 rows, and the matrices the tiled kernel does not take, go to the weight-streaming
+// kernel in chunks of 128 rows with the same number of planes (the later chunks find the matrix they re-read in
+// the 256 MB last-level cache).
 int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
   const vla_config& c = ctx->cfg;
   const WorkLayout& w = ctx->wl;
@@ -443,10 +446,27 @@ int run_layers_decode_f16(vla_ctx* ctx, int B, hipStream_t st) {
   f16* act = at<f16>(ctx->work, w.act);
   f16 *hn_lo = frag_lo(c, hn, d), *att_lo = frag_lo(c, att, d), *act_lo = frag_lo(c, act, f);
   float* part = ctx->part_override ? ctx->part_override : at<float>(ctx->work, w.part);
-  const int ks_qkv = skinny_ksplit(3 * d, d), ks_o = skinny_ksplit(d, d), ks_gu = skinny_ksplit(2 * f, d),
-            ks_dn = skinny_ksplit(d, f);
+  // the tiled split-K kernel takes the chunks of more than 128 rows of the wide matrices (QKV, gate/up at 7B): it
+  // needs about half the compute units busy to beat two weight-streaming launches (measured at 256 rows on the 7B
+  // shape: QKV 44 against 74 us, gate/up 82 against 122; but the N = 4096 projections, 64 workgroups, 46 and 83
+  // against 45 and 72)
+  // (matrices of up to 2 M elements are launch-bound either way: one tiled launch per 256 rows instead of two)
+  auto tiled = [&](int N, int K) {
+    return B > kSkinnyMaxRows && splitk_gemm_fits(256, N, K) &&
+           ((N / 256) * splitk_ksplit(N, K) >= 128 || (size_t)N * K <= ((size_t)2 << 20));
+  };
+  auto planes = [&](int N, int K) { return tiled(N, K) ? splitk_ksplit(N, K) : skinny_ksplit(N, K); };
+  const int ks_qkv = planes(3 * d, d), ks_o = planes(d, d), ks_gu = planes(2 * f, d), ks_dn = planes(d, f);
   auto gemm = [&](f16* a, f16* a_lo, size_t w_off, int N, int K, int ks) {
-    for (int r0 = 0; r0 < B; r0 += kSkinnyMaxRows) {
+    int r0 = 0;
+    if (tiled(N, K)) {
+      for (; B - r0 > kSkinnyMaxRows; r0 += 256) {
+        const int m = B - r0 < 256 ? B - r0 : 256;
+        splitk_gemm(frag_rows(a, r0, K), a_lo ? frag_rows(a_lo, r0, K) : nullptr, at<f16>(ctx->arena, w_off), part, m,
+                    N, K, ks, B, r0, st);
+      }
+    }
+    for (; r0 < B; r0 += kSkinnyMaxRows) {
       const int m = B - r0 < kSkinnyMaxRows ? B - r0 : kSkinnyMaxRows;
       skinny_gemm(frag_rows(a, r0, K), a_lo ? frag_rows(a_lo, r0, K) : nullptr, at<f16>(ctx->arena, w_off), part, m, N, K,
                   ks, B, r0, st);

@@ -180,6 +180,13 @@ constexpr int kSkinnyMaxRows = 128;   // most rows of one weight-streaming GEMM 
 // The M rows of a launch are rows prow0 .. prow0 + M - 1 of partial planes of plane_rows rows each.
 void skinny_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* part, int M, int N, int K, int ksplit,
                  int plane_rows, int prow0, hipStream_t st);
+// The same product for up to 256 rows on the 256 x 256 tiled kernel, split over `ksplit` K slices (one partial plane
+// each): activations go through LDS once per workgroup instead of once per wave, which is what a large batch needs
+// to stream every weight once at full rate.  Needs N % 256 == 0 and K % 64 == 0 (splitk_gemm_fits).
+bool splitk_gemm_fits(int M, int N, int K);
+int splitk_ksplit(int N, int K);
+void splitk_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* part, int M, int N, int K, int ksplit,
+                 int plane_rows, int prow0, hipStream_t st);
 void reduce_resid_norm(const float* part, int ksplit, int plane_rows, int prow0, int M, int d, float* x,
                        const float* gain, float eps, f16* hn_frag, f16* hn_frag_lo, int row0, hipStream_t st);
 void rmsnorm_frag(const float* x, int M, int d, const float* gain, float eps, f16* hn_frag, f16* hn_frag_lo,

@@ -88,6 +88,23 @@ struct EpiResid {
 
 // Fused gate/up weights are interleaved in blocks of 32 rows: [gate 0..31, up 0..31, gate 32..63, ...]
 // so that a wave's even 32-column tiles are gates and the following odd tiles the matching ups.
+// Split-K form (decode steps of large batches): the tile's partial sums over one K slice go, with the weight scale
+// divided out, to plane `kz` of part[ksplit][plane_rows][N]; the reduce kernels of the decode path add the planes.
+struct EpiPartial {
+  float* part;          // plane 0; the kernel moves it to its slice's plane
+  int plane_rows, row0, N;
+  const f16* a_lo;      // low-term activation fragments (two-term operands), or nullptr
+  __device__ __forceinline__ void consume(const float* tile, int m_base, int nb, int lane, int M) const {
+    const int r0 = lane >> 5, c4 = (lane & 31) * 4;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int m = m_base + it * 2 + r0;
+      const f32x4 v = *(const f32x4*)(tile + (it * 2 + r0) * kStagePitch + c4);
+      if (m < M) *(f32x4*)(part + (size_t)(row0 + m) * N + nb + c4) = v * (1.0f / kWeightScale);
+    }
+  }
+};
+
 struct EpiSwiglu {
   f16* act;
   int ld;
@@ -616,12 +633,15 @@ __device__ __forceinline__ void wait_vmcnt() {
 #endif
 }
 
-template <int WGM, int WGN, class Epi, bool LO8>
+// SPLITK (with EpiPartial; one row of tiles, M <= 256): A is in the fragment order of the decode path
+// ([m/32][k/16][lane][8], the low terms of two-term operands in a second buffer of the same order), `tiles_m` is
+// the number of K slices, and workgroup (tile column tn, slice kz) accumulates slice kz of K only.
+template <int WGM, int WGN, class Epi, bool LO8, bool SPLITK = false>
 __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const f16* __restrict__ A, int lda,
                                                                          const f16* __restrict__ Wp,
                                                                          const f16* __restrict__ W8, int M, int N,
                                                                          int K, int Kw, int tiles_m, int tiles_n,
-                                                                         Epi epi) {
+                                                                         Epi epi_in) {
   constexpr int BM = 256, BN = 256, NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, MT = WTM / 32, NT = WTN / 32;
   constexpr int A_INSTR = (BM / 16) / NW;      // 16 rows per load instruction -> 2 per wave
@@ -635,35 +655,68 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   const int per_xcd = gridDim.x >> 3;
   const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (pid >= nblk) return;
-  constexpr int GM = 4;
-  const int per_group = GM * tiles_n;
-  const int grp = pid / per_group;
-  const int first_m = grp * GM;
-  const int gm = min(tiles_m - first_m, GM);
-  const int in_grp = pid - grp * per_group;
-  const int tm = first_m + in_grp % gm;
-  const int tn = in_grp / gm;
+  int tm, tn, kz = 0;
+  if constexpr (SPLITK) {                      // consecutive workgroups of an XCD share a K slice (the A slabs)
+    tm = 0;
+    tn = pid % tiles_n;
+    kz = pid / tiles_n;
+  } else {
+    constexpr int GM = 4;
+    const int per_group = GM * tiles_n;
+    const int grp = pid / per_group;
+    const int first_m = grp * GM;
+    const int gm = min(tiles_m - first_m, GM);
+    const int in_grp = pid - grp * per_group;
+    tm = first_m + in_grp % gm;
+    tn = in_grp / gm;
+  }
   const int m0 = tm * BM, n0 = tn * BN;
+  Epi epi = epi_in;
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
   // K == 2 * Kw: two-term A with half-precision low terms, the weight slabs wrap; K == 1.5 * Kw and W8: 8-bit low
   // terms, whose slabs (64 k each, same bytes as a 32-k slab of halves) come after the KTw slabs of high terms
-  const int KB16 = Kw >> 4, KT = K / PK, KTw = Kw / PK;
+  const int KB16 = Kw >> 4;
+  int KT = K / PK, KTw = Kw / PK;
+  size_t slab0 = 0;                                      // first slab of this workgroup's K range
+  if constexpr (SPLITK) {
+    // slices in units of two slabs (64 k), so that every slice has an even number of slabs; K == 2 * Kw: the
+    // slice of low-term slabs follows the slice of high-term slabs, against the same weight slabs
+    const int U = Kw >> 6, u0 = (int)((long long)kz * U / tiles_m), u1 = (int)((long long)(kz + 1) * U / tiles_m);
+    slab0 = 2 * (size_t)u0;
+    KTw = 2 * (u1 - u0);
+    KT = K > Kw ? 2 * KTw : KTw;
+    epi.part += (size_t)kz * epi.plane_rows * epi.N;
+  }
 
   const f16* a_src[A_INSTR];
+  const f16* a_lo_src[A_INSTR];
 #pragma unroll
   for (int i = 0; i < A_INSTR; ++i) {
-    const int r = (wave * A_INSTR + i) * 16 + (lane >> 2);
-    const int c = (lane & 3) ^ ((r >> 2) & 3);
-    a_src[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
+    if constexpr (SPLITK) {
+      const int j = wave * A_INSTR + i;                  // KiB of the slab: block row j/2 (clamped to the rows
+      const int rb = min(j >> 1, (M - 1) >> 5);          // that exist), k-step j%2
+      const size_t off = ((size_t)rb * KB16 + 2 * slab0 + (j & 1)) * 512 + lane * 8;
+      a_src[i] = A + off;
+      a_lo_src[i] = (epi.a_lo ? epi.a_lo : A) + off;
+    } else {
+      const int r = (wave * A_INSTR + i) * 16 + (lane >> 2);
+      const int c = (lane & 3) ^ ((r >> 2) & 3);
+      a_src[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
+      a_lo_src[i] = a_src[i];
+    }
   }
+  auto a_slab = [&](int i, int ks) {                     // source of the i-th activation load of slab ks
+    if constexpr (SPLITK) return ks < KTw ? a_src[i] + (size_t)ks * 2 * 512 : a_lo_src[i] + (size_t)(ks - KTw) * 2 * 512;
+    else return a_src[i] + (size_t)ks * PK;
+  };
   const f16* w_src[W_INSTR];
 #pragma unroll
   for (int i = 0; i < W_INSTR; ++i) {
     const int j = wave * W_INSTR + i;                    // KiB of the slab: block row j/2, k-step j%2
-    w_src[i] = Wp + ((size_t)(n0 / 32 + (j >> 1)) * KB16 + (j & 1)) * 512 + lane * 8;
+    w_src[i] = Wp + ((size_t)(n0 / 32 + (j >> 1)) * KB16 + 2 * slab0 + (j & 1)) * 512 + lane * 8;
   }
   const f16* w8_src[W_INSTR];
 #pragma unroll
@@ -680,7 +733,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
     f16* as = As + buf * P_STAGE_HALVES + wave * A_INSTR * 512;
     f16* ws = Ws + buf * P_STAGE_HALVES + wave * W_INSTR * 512;
 #pragma unroll
-    for (int i = 0; i < A_INSTR; ++i) load_to_lds_16(a_src[i] + (size_t)ks * PK, as + i * 512);
+    for (int i = 0; i < A_INSTR; ++i) load_to_lds_16(a_slab(i, ks), as + i * 512);
 #pragma unroll
     for (int i = 0; i < W_INSTR; ++i) load_to_lds_16(w_slab(i, ks), ws + i * 512);
   };
@@ -697,8 +750,11 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
   const unsigned lds0 = (unsigned)(size_t)((__attribute__((address_space(3))) unsigned char*)smem);
   const int frow = wm * WTM + (lane & 31);
   const int fhalf = lane >> 5;
-  const unsigned a_k0 = lds0 + 2u * (unsigned)(frow * PK + (((0 + fhalf) ^ ((frow >> 2) & 3)) << 3));
-  const unsigned a_k1 = lds0 + 2u * (unsigned)(frow * PK + (((2 + fhalf) ^ ((frow >> 2) & 3)) << 3));
+  // (SPLITK: the A slab sits in LDS in fragment order like the weights: block row rb, k-step s at KiB 2 rb + s)
+  const unsigned a_k0 = SPLITK ? lds0 + (unsigned)(wm * MT * 2) * 1024u + (unsigned)lane * 16u
+                               : lds0 + 2u * (unsigned)(frow * PK + (((0 + fhalf) ^ ((frow >> 2) & 3)) << 3));
+  const unsigned a_k1 = SPLITK ? a_k0 + 1024u
+                               : lds0 + 2u * (unsigned)(frow * PK + (((2 + fhalf) ^ ((frow >> 2) & 3)) << 3));
   const unsigned w_b = lds0 + 2u * (unsigned)(P_STAGES * P_STAGE_HALVES + wn * NT * 2 * 512 + lane * 8);
 
   // Fragments are double buffered in registers: while the MFMAs of slab kt run, the reads of slab kt+1
@@ -712,7 +768,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, 1) void gemm_f16_pipe_kernel(const 
     const int buf = kt & (P_STAGES - 1);
     const int ks = min(kt, KT - 1);
     if (i < A_INSTR)
-      load_to_lds_16(a_src[i] + (size_t)ks * PK, As + buf * P_STAGE_HALVES + (wave * A_INSTR + i) * 512);
+      load_to_lds_16(a_slab(i, ks), As + buf * P_STAGE_HALVES + (wave * A_INSTR + i) * 512);
     else
       load_to_lds_16(w_slab(i - A_INSTR, ks), Ws + buf * P_STAGE_HALVES + (wave * W_INSTR + i - A_INSTR) * 512);
   };
@@ -886,6 +942,33 @@ static void launch_pipe(const GemmF16& g, const Epi& epi, hipStream_t st) {
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, st, g.A, g.lda, g.Wp, g.W8, g.M, g.N, g.K, g.Kw,
                      tiles_m, tiles_n, epi);
+}
+
+// Decode GEMM of a large batch: partial sums of `ksplit` K slices, see EpiPartial and the SPLITK form of the kernel.
+// Afrag / Afrag_lo: activation fragments of rows row0 .. row0 + M - 1 (their block row 0 = row row0, a multiple of 32).
+bool splitk_gemm_fits(int M, int N, int K) { return M <= 256 && N % 256 == 0 && K % 64 == 0 && K >= 128; }
+int splitk_ksplit(int N, int K) {
+  int ks = 256 / (N / 256);                  // about one workgroup per compute unit
+  if (ks > kMaxKSplit) ks = kMaxKSplit;
+  while (ks > 1 && K / 64 < 4 * ks) --ks;    // at least 8 slabs per slice
+  return ks < 1 ? 1 : ks;
+}
+void splitk_gemm(const f16* Afrag, const f16* Afrag_lo, const f16* Wp, float* part, int M, int N, int K, int ksplit,
+                 int plane_rows, int row0, hipStream_t st) {
+  const int tiles_n = N / 256, nblk = tiles_n * ksplit;
+  const int grid = (nblk + 7) / 8 * 8;
+  constexpr size_t slabs = 2 * (size_t)P_STAGES * P_STAGE_HALVES * sizeof(f16);
+  constexpr size_t stage = (size_t)4 * kStageFloats * sizeof(float);
+  constexpr size_t smem = slabs > stage ? slabs : stage;
+  auto kern = gemm_f16_pipe_kernel<2, 2, EpiPartial, false, true>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    attr_set = true;
+  }
+  const f16* no8 = nullptr;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, st, Afrag, 0, Wp, no8, M, N, Afrag_lo ? 2 * K : K, K, ksplit,
+                     tiles_n, EpiPartial{part, plane_rows, row0, N, Afrag_lo});
 }
 
 template <int BM, int BN, int WGM, int WGN, class Epi, bool LO8>

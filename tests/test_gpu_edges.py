@@ -13,6 +13,9 @@ from tests.test_gpu_parity import make_policy, ragged_obs, run_both
 pytestmark = pytest.mark.gpu
 
 SMALL = W.PolicyShape(2, 256, 2, 128, 704, 1024, dtype="bf16")
+# every matrix a multiple of 256 columns and of 64 in depth: what the tiled split-K decode GEMM of batches above
+# 128 rows takes (with SMALL, the gate/up projection of such a batch stays on the weight-streaming kernel)
+TILED = W.PolicyShape(2, 512, 4, 128, 1024, 1024, dtype="bf16")
 
 
 def bf16(x):
@@ -24,15 +27,20 @@ def as_f32(bits):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("batch,fast", [(200, False), (300, False), (200, "first"), (300, True)],
-                         ids=["B200_two_term", "B300_two_term", "B200_two_term_layer0_only", "B300_fast"])
-def test_every_row_of_a_large_ragged_batch(batch, fast):
-    """More sequences than one weight-streaming launch takes (256 rows) and than one 128-row group of the
-    last prefill layer: every row of the prefill and of three decode steps is compared with the oracle."""
+@pytest.mark.parametrize("shape,batch,fast", [(SMALL, 200, False), (SMALL, 300, False), (SMALL, 200, "first"),
+                                              (SMALL, 300, True), (TILED, 200, False), (TILED, 300, "first"),
+                                              (TILED, 420, True), (TILED, 129, False)],
+                         ids=["B200_two_term", "B300_two_term", "B200_two_term_layer0_only", "B300_fast",
+                              "tiled_B200_two_term", "tiled_B300_two_term_layer0_only", "tiled_B420_fast",
+                              "tiled_B129_two_term"])
+def test_every_row_of_a_large_ragged_batch(shape, batch, fast):
+    """More sequences than one weight-streaming launch takes (128 rows), than one tile of the split-K decode GEMM
+    (256 rows: 300 = 256 + a remainder on the weight-streaming kernel, 420 = 256 + 164) and than one 128-row group of
+    the last prefill layer: every row of the prefill and of three decode steps is compared with the oracle."""
     g = np.random.default_rng(5 + batch)
     lens = g.integers(0, 13, size=batch)
     nps = g.integers(1, 25, size=batch)
-    wl = W.Workload("Tb", 41, SMALL, batch=batch, n_patches=24, instr_len=(0, 12), n_tokens=4,
+    wl = W.Workload("Tb", 41, shape, batch=batch, n_patches=24, instr_len=(0, 12), n_tokens=4,
                     sampling="gumbel", temperature=1.0)
     obs = ragged_obs(wl, list(nps), list(lens), seed=93)
     stats, gpu, ora = run_both(wl, obs=obs, gumbel=W.make_gumbel(wl), fast=fast)
