@@ -136,8 +136,13 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+  // Softmax statistics are kept in the base-2 domain: scores are scaled by log2(e) / sqrt(HD) once, and every
+  // exponential is a bare exp2.  m_run is a reference point, not necessarily the running maximum: it is moved up
+  // (and the accumulators rescaled) only when some query of the wave has found a score more than kLazy above it,
+  // so most tiles skip the rescaling; probabilities relative to it stay below 2^kLazy, well inside half precision.
   float m_run = -INFINITY, l_run = 0.f;
-  const float scale = rsqrtf((float)HD);
+  const float scale2 = rsqrtf((float)HD) * 1.44269504088896341f;
+  constexpr float kLazy = 8.0f;
 
   const int kend = q0 + 128;                              // keys needed by this workgroup (<= S)
   const int wave_last = q0 + wave * 32 + 31;              // last query position of this wave
@@ -264,37 +269,53 @@ __global__ __launch_bounds__(256, 2) void flash_prefill_kernel(
         }
       }
     }
-    // mask, running max
+    // scale, causal mask (only the tiles that reach past the wave's first query need one; a key position is below
+    // S whenever it is at most the position of a live query), tile maximum
     float m_tile = -INFINITY;
+    if (k0 + 63 > q0 + wave * 32) {
+      // element (st, e) is key k0 + 4 * half + [st * 32 + 8 * (e >> 2) + (e & 3)]: visible iff [..] <= lim
+      const int lim = qpos - k0 - 4 * half;
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
+      for (int st = 0; st < 2; ++st)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int kp = k0 + st * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-        const float v = (kp <= qpos && kp < S) ? sacc[st][e] * scale : -INFINITY;
-        sacc[st][e] = v;
-        m_tile = fmaxf(m_tile, v);
-      }
+        for (int e = 0; e < 16; ++e) {
+          const float v = (st * 32 + 8 * (e >> 2) + (e & 3) <= lim) ? sacc[st][e] * scale2 : -INFINITY;
+          sacc[st][e] = v;
+          m_tile = fmaxf(m_tile, v);
+        }
+    } else {
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          sacc[st][e] *= scale2;
+          m_tile = fmaxf(m_tile, sacc[st][e]);
+        }
+    }
     m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-    const float m_new = fmaxf(m_run, m_tile);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;  // fully masked so far: keep everything at zero
-    const float alpha = __expf(m_run - m_use);              // exp(-inf) = 0 on the first live tile
+    if (__any(m_tile > m_run + kLazy)) {                    // (-inf + kLazy = -inf: true on the first live tile)
+      const float m_new = fmaxf(m_run, m_tile);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;  // fully masked so far: keep everything at zero
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // exp2(-inf) = 0 on the first live tile
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+    }
+    const float m_ref = m_run == -INFINITY ? 0.f : m_run;
     float l_tile = 0.f;
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float p = __expf(sacc[st][e] - m_use);
+        const float p = __builtin_amdgcn_exp2f(sacc[st][e] - m_ref);
         sacc[st][e] = p;
         l_tile += p;
       }
     l_tile += __shfl_xor(l_tile, 32, 64);
-    l_run = l_run * alpha + l_tile;
-    m_run = m_new;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+    l_run += l_tile;
     // O^T += V^T P^T   (two-term mode: P too is split, P_hi V_hi + P_hi V_lo + P_lo V_hi)
 #pragma unroll
     for (int st = 0; st < 2; ++st)
