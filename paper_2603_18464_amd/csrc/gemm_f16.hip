@@ -105,6 +105,13 @@ struct EpiPartial {
   }
 };
 
+// silu(g) * u for accumulator values G = g * kWeightScale, U = u * kWeightScale, with the scale folded into the
+// constants: (G * U / scale^2) / (1 + 2^(-G * log2(e) / scale)).  One form for both kernels (same bits).
+__device__ __forceinline__ float swiglu_scaled(float G, float U) {
+  constexpr float c1 = 1.44269504088896341f / kWeightScale, c2 = 1.0f / (kWeightScale * kWeightScale);
+  return (G * U * c2) * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-(G * c1)));
+}
+
 struct EpiSwiglu {
   f16* act;
   int ld;
@@ -117,22 +124,31 @@ struct EpiSwiglu {
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int r = it * 4 + rs, m = m_base + r;
-      const f32x4 g = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + c4) * (1.0f / kWeightScale);
-      const f32x4 u = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + 32 + c4) * (1.0f / kWeightScale);
-      f16x4 o, oe;
-      float e[4];
+      const f32x4 g = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + c4);
+      const f32x4 u = *(const f32x4*)(tile + r * kStagePitch + jb * 64 + 32 + c4);
+      f16x4 o;
+      float a[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float a = g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j])) * u[j];
-        o[j] = from_f32<f16>(a);
-        e[j] = a - (float)o[j];
-        oe[j] = from_f32<f16>(e[j]);
+        a[j] = swiglu_scaled(g[j], u[j]);
+        o[j] = from_f32<f16>(a[j]);
       }
       if (m < M) {
         f16* row = act + (size_t)m * ld;
         *(f16x4*)(row + nb / 2 + jb * 32 + c4) = o;
-        if (lo_mode == 1) *(f16x4*)(row + f + nb / 2 + jb * 32 + c4) = oe;
-        if (lo_mode == 2) *(int*)((unsigned char*)(row + f) + nb / 2 + jb * 32 + c4) = pack_lo8(e[0], e[1], e[2], e[3]);
+        if (lo_mode != 0) {                  // (uniform) low terms only where the layer carries them
+          float e[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) e[j] = a[j] - (float)o[j];
+          if (lo_mode == 1) {
+            f16x4 oe;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) oe[j] = from_f32<f16>(e[j]);
+            *(f16x4*)(row + f + nb / 2 + jb * 32 + c4) = oe;
+          } else {
+            *(int*)((unsigned char*)(row + f) + nb / 2 + jb * 32 + c4) = pack_lo8(e[0], e[1], e[2], e[3]);
+          }
+        }
       }
     }
   }
@@ -151,9 +167,7 @@ struct EpiSwiglu {
             f16* row = act + (size_t)m * ld + nb / 2 + c;
 #pragma unroll
             for (int j = 0; j < NT / 2; ++j) {
-              const float g = acc[mt][2 * j][4 * blk + r] * (1.0f / kWeightScale);
-              const float u = acc[mt][2 * j + 1][4 * blk + r] * (1.0f / kWeightScale);
-              const float a = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+              const float a = swiglu_scaled(acc[mt][2 * j][4 * blk + r], acc[mt][2 * j + 1][4 * blk + r]);
               const f16 a16 = from_f32<f16>(a);
               row[j * 32] = a16;
               if (lo_mode == 1) row[f + j * 32] = from_f32<f16>(a - (float)a16);
