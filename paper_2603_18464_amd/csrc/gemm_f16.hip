@@ -235,27 +235,36 @@ struct EpiQkv {
           hi[j] = b;
         }
       }
-      f16x4 l4, h4, l4e, h4e;
-      float le[4], he[4];
+      f16x4 l4, h4;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         l4[j] = from_f32<f16>(lo[j]);
         h4[j] = from_f32<f16>(hi[j]);
-        le[j] = lo[j] - (float)l4[j];
-        he[j] = hi[j] - (float)h4[j];
-        l4e[j] = from_f32<f16>(le[j]);
-        h4e[j] = from_f32<f16>(he[j]);
       }
       if (m < M) {
         *(f16x4*)(dst + c4) = l4;
         *(f16x4*)(dst + HALF + c4) = h4;
-        if (dst_lo) {
-          *(f16x4*)(dst_lo + c4) = l4e;
-          *(f16x4*)(dst_lo + HALF + c4) = h4e;
-        }
-        if (dst_lo8) {
-          *(int*)(dst_lo8 + c4) = pack_lo8(le[0], le[1], le[2], le[3]);
-          *(int*)(dst_lo8 + HALF + c4) = pack_lo8(he[0], he[1], he[2], he[3]);
+        if (o.k_lo) {                        // (uniform) low terms only in two-term layers
+          float le[4], he[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            le[j] = lo[j] - (float)l4[j];
+            he[j] = hi[j] - (float)h4[j];
+          }
+          if (dst_lo) {
+            f16x4 l4e, h4e;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              l4e[j] = from_f32<f16>(le[j]);
+              h4e[j] = from_f32<f16>(he[j]);
+            }
+            *(f16x4*)(dst_lo + c4) = l4e;
+            *(f16x4*)(dst_lo + HALF + c4) = h4e;
+          }
+          if (dst_lo8) {
+            *(int*)(dst_lo8 + c4) = pack_lo8(le[0], le[1], le[2], le[3]);
+            *(int*)(dst_lo8 + HALF + c4) = pack_lo8(he[0], he[1], he[2], he[3]);
+          }
         }
       }
     }
